@@ -1,0 +1,151 @@
+/*
+ * kfac.h -- C ABI of the MI355X (gfx950) K-FAC hot path.
+ *
+ * The library computes, for one data-parallel worker, the three per-iteration
+ * K-FAC operations of Shi, Zhang, Li, "Accelerating Distributed K-FAC with Smart
+ * Parallelism of Computing and Communication Tasks" (arXiv 2107.06533):
+ *
+ *   kfac_update_factors   Kronecker factors A = a a^T, G = g g^T   (Sec. II-B,
+ *                         Eq. factorA / Eq. factorG), batch-averaged and folded
+ *                         into a running average;
+ *   kfac_invert_batch     f(T_i) = (T_i + gamma I)^-1 applied to a whole set of
+ *                         symmetric tensors T_i in R^{d_i x d_i} (Sec. II-B damped
+ *                         update rule; problem statement of Sec. IV-B);
+ *   kfac_precondition     (A+gamma I)^-1 (x) (G+gamma I)^-1 applied to a layer's
+ *                         gradient (Eq. kfacfinal), i.e.  G^-1 . V . A^-1.
+ *
+ * Conventions shared by every call
+ *   - All DATA pointers are DEVICE pointers to fp32 buffers owned by the caller.
+ *     The pointer ARRAYS (float* const*), the layer/dims arrays and every scalar
+ *     are HOST memory; they are copied during the call and may be freed on return.
+ *   - Matrices are dense row-major with leading dimension = number of columns.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*, NULL
+ *     = the default stream).  Calls on one context must be issued in stream
+ *     order; a context is not thread-safe.
+ *   - The context owns a device workspace that grows on demand (hipMalloc at the
+ *     first call that needs more; query with kfac_workspace_bytes_*).
+ *   - Errors are returned, never thrown.  Arguments are validated on the host
+ *     before anything is launched; kfac_last_error() describes the last failure.
+ *   - Arithmetic is fp32 throughout (fp32 MFMA, fp32 accumulation).
+ */
+#ifndef KFAC_H_
+#define KFAC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KFAC_OK = 0,
+  KFAC_ERR_INVALID_ARG = 1, /* rejected on the host, nothing was launched        */
+  KFAC_ERR_NOT_SPD = 2,     /* reported by kfac_check_info                        */
+  KFAC_ERR_WORKSPACE = 3,   /* device workspace could not be (re)allocated        */
+  KFAC_ERR_DEVICE = 4       /* HIP error, or a host-only context asked to launch  */
+} kfac_status;
+
+typedef struct kfac_ctx kfac_ctx; /* opaque: workspace + cached schedules only */
+
+/* One preconditioned layer (one factor pair). */
+typedef struct {
+  int32_t kind;     /* 0 linear : act [rows, c_in],   gout [rows, c_out]   row-major
+                       1 conv2d : act [n, c_in, h, w], gout [n, c_out, oh, ow] NCHW, dilation 1, groups 1 */
+  int32_t n, c_in, h, w, c_out, kh, kw, stride, pad; /* n,h,w,kh,kw,stride,pad: conv only */
+  int32_t rows;     /* linear only; a convolution has rows = n*oh*ow */
+  int32_t has_bias; /* 1: a ones column is appended LAST to the activations,
+                          dA = c_in*kh*kw + has_bias                           */
+} kfac_layer;
+
+/* Create a context on HIP device `device` (>= 0).  device = -1 creates a host-only
+ * context: every call still validates its arguments and builds its schedule, then
+ * returns KFAC_ERR_DEVICE instead of launching (used by CPU-only tests). */
+kfac_status kfac_create(kfac_ctx** out, int device);
+void kfac_destroy(kfac_ctx* ctx);
+const char* kfac_last_error(const kfac_ctx* ctx); /* never NULL; ctx may be NULL */
+
+/* Factor dimensions implied by a layer (pure host). Return 0 for an invalid layer. */
+int32_t kfac_layer_dA(const kfac_layer* layer);
+int32_t kfac_layer_dG(const kfac_layer* layer);
+int64_t kfac_layer_rows(const kfac_layer* layer);
+
+/* Workspace each call needs for the given shapes (pure host; 0 on invalid input). */
+size_t kfac_workspace_bytes_factors(const kfac_ctx* ctx, int n_layers, const kfac_layer* layers);
+size_t kfac_workspace_bytes_invert(const kfac_ctx* ctx, int n_mats, const int32_t* dims);
+size_t kfac_workspace_bytes_precondition(const kfac_ctx* ctx, int n_layers, const int32_t* dG, const int32_t* dA);
+
+/*
+ * Factor build with running average (Sec. II-B, Eq. factorA, Eq. factorG).
+ * For every layer l:
+ *     a-bar = [patches(act_l), 1]   [R, dA]  (patch expansion fused, never materialised;
+ *                                              column q = (c*kh + i)*kw + j, ones column last)
+ *     A_l <- xi * A_l + (1 - xi) * scale_a * a-bar^T a-bar
+ *     G_l <- xi * G_l + (1 - xi) * scale_g * g-bar^T g-bar     g-bar [R, dG], one row per sample / output pixel
+ * scale_a, scale_g <= 0 select the default 1/R (R = rows of a-bar).
+ * act, gout: host arrays of n_layers device pointers; an array, or single entries,
+ *     may be NULL to skip that factor (then the matching A / G entry is ignored).
+ * A, G: in/out device matrices [dA,dA] / [dG,dG]; the result is written full and
+ *     exactly symmetric.  Only the lower triangle of the old value is read.
+ * Returns INVALID_ARG for: NULL ctx/layers, n_layers < 0, a malformed layer (non-positive
+ * dimension, empty output, kind not 0/1, has_bias not 0/1), xi outside [0,1] or NaN, a
+ * non-NULL act/gout entry whose factor pointer is NULL.  n_layers == 0 is a no-op.
+ */
+kfac_status kfac_update_factors(kfac_ctx* ctx, int n_layers, const kfac_layer* layers,
+                                const float* const* act, const float* const* gout,
+                                float* const* A, float* const* G,
+                                float xi, float scale_a, float scale_g, void* hip_stream);
+
+/*
+ * Damped inverse of a heterogeneous set of symmetric positive-definite matrices
+ * (Sec. II-B: Tikhonov term gamma I added before inverting; Sec. IV-B: N tensors
+ * T_i in R^{d_i x d_i}, the same f applied to each):
+ *     X_i = (F_i + gamma I)^-1,   i = 0 .. n_mats-1.
+ * dims: host array of d_i >= 1.  F, X: host arrays of device pointers, [d_i, d_i];
+ * only the lower triangle of F_i is read; X_i is written full and exactly symmetric;
+ * X_i must not alias F_i (F_i is left untouched).
+ * info_dev: optional DEVICE array of n_mats int32 (may be NULL).  Entry i is set to 0
+ *     on success or to k > 0 when the leading minor of order k of F_i + gamma I is not
+ *     positive (LAPACK convention); X_i is then unspecified, other matrices are still
+ *     valid.  Read it after the stream has finished, e.g. with kfac_check_info.
+ * Returns INVALID_ARG for: NULL ctx/dims/F/X, n_mats < 0, d_i < 1, NULL or aliased
+ * entries, gamma negative or NaN.  n_mats == 0 is a no-op.
+ */
+kfac_status kfac_invert_batch(kfac_ctx* ctx, int n_mats, const int32_t* dims,
+                              const float* const* F, float* const* X,
+                              float gamma, int32_t* info_dev, void* hip_stream);
+
+/* Synchronise `hip_stream`, copy info_dev[0..n) to info_host (may be NULL) and return
+ * KFAC_ERR_NOT_SPD if any entry is non-zero, else KFAC_OK. */
+kfac_status kfac_check_info(kfac_ctx* ctx, int n, const int32_t* info_dev, int32_t* info_host,
+                            void* hip_stream);
+
+/*
+ * Two-sided preconditioning (Eq. kfacfinal with the inverses already formed):
+ *     out_l = Ginv_l . gradW_l . Ainv_l        gradW_l, out_l : [dG_l, dA_l]
+ * gradW_l is the layer's weight gradient flattened to [C_out, C_in*kh*kw] with the bias
+ * gradient as last column when the layer has a bias.  Ginv_l [dG,dG], Ainv_l [dA,dA] are
+ * used as stored (full matrices; they are symmetric when produced by kfac_invert_batch).
+ * out_l may alias gradW_l; it must not alias the inverses.
+ * Returns INVALID_ARG for NULL arrays/entries, n_layers < 0, non-positive dimensions.
+ */
+kfac_status kfac_precondition(kfac_ctx* ctx, int n_layers, const int32_t* dG, const int32_t* dA,
+                              const float* const* Ginv, const float* const* Ainv,
+                              const float* const* gradW, float* const* out, void* hip_stream);
+
+/* Schedule statistics of the most recent call of each kind on this context (pure host;
+ * for tests and benchmarks).  Fields that do not apply are 0. */
+typedef struct {
+  int64_t n_jobs;      /* tile jobs launched (all kernels of the call)          */
+  int64_t n_launches;  /* kernel launches the call enqueues                     */
+  int64_t n_split;     /* factors: tiles whose reduction is split along R       */
+  int64_t mfma_flops;  /* flops the tile jobs execute (tile granularity)        */
+  int64_t ws_bytes;    /* workspace the call uses                               */
+} kfac_plan_stats;
+void kfac_get_plan_stats(const kfac_ctx* ctx, int which /*0 factors, 1 invert, 2 precondition*/,
+                         kfac_plan_stats* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KFAC_H_ */

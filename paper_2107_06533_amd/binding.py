@@ -1,0 +1,208 @@
+"""ctypes binding with the same names as the C ABI (kfac_update_factors, kfac_invert_batch,
+kfac_precondition).  Tensors are anything with .data_ptr() (torch tensors on the GPU) or
+plain integer device addresses."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+KFAC_OK, KFAC_ERR_INVALID_ARG, KFAC_ERR_NOT_SPD, KFAC_ERR_WORKSPACE, KFAC_ERR_DEVICE = range(5)
+
+# every symbol include/kfac.h declares
+EXPORTS = [
+    "kfac_create", "kfac_destroy", "kfac_last_error",
+    "kfac_layer_dA", "kfac_layer_dG", "kfac_layer_rows",
+    "kfac_workspace_bytes_factors", "kfac_workspace_bytes_invert", "kfac_workspace_bytes_precondition",
+    "kfac_update_factors", "kfac_invert_batch", "kfac_check_info", "kfac_precondition",
+    "kfac_get_plan_stats",
+]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class KfacError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"kfac status {status}: {msg}")
+        self.status = status
+
+
+class layer_struct(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("kind", "n", "c_in", "h", "w", "c_out", "kh", "kw", "stride", "pad", "rows", "has_bias")]
+
+
+class plan_stats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("n_jobs", "n_launches", "n_split", "mfma_flops", "ws_bytes")]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libkfac_hip.so")
+
+
+def is_built() -> bool:
+    return os.path.exists(lib_path())
+
+
+def load():
+    """dlopen libkfac_hip.so (built in-tree by paper_2107_06533_amd.build / __graft_entry__.build)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not is_built():
+        raise RuntimeError(f"{lib_path()} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    # PyTorch ships its own HIP runtime (same soname).  Import it first so that the loader binds this
+    # library to that one runtime; two runtimes in one process do not share devices, streams or memory.
+    import torch  # noqa: F401
+    lib = C.CDLL(lib_path())
+    vp, i32p, fpp = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_void_p)
+    lp = C.POINTER(layer_struct)
+    lib.kfac_create.argtypes = [C.POINTER(vp), C.c_int]
+    lib.kfac_create.restype = C.c_int
+    lib.kfac_destroy.argtypes = [vp]
+    lib.kfac_destroy.restype = None
+    lib.kfac_last_error.argtypes = [vp]
+    lib.kfac_last_error.restype = C.c_char_p
+    for f in ("kfac_layer_dA", "kfac_layer_dG"):
+        getattr(lib, f).argtypes = [lp]
+        getattr(lib, f).restype = C.c_int32
+    lib.kfac_layer_rows.argtypes = [lp]
+    lib.kfac_layer_rows.restype = C.c_int64
+    lib.kfac_workspace_bytes_factors.argtypes = [vp, C.c_int, lp]
+    lib.kfac_workspace_bytes_factors.restype = C.c_size_t
+    lib.kfac_workspace_bytes_invert.argtypes = [vp, C.c_int, i32p]
+    lib.kfac_workspace_bytes_invert.restype = C.c_size_t
+    lib.kfac_workspace_bytes_precondition.argtypes = [vp, C.c_int, i32p, i32p]
+    lib.kfac_workspace_bytes_precondition.restype = C.c_size_t
+    lib.kfac_update_factors.argtypes = [vp, C.c_int, lp, fpp, fpp, fpp, fpp, C.c_float, C.c_float, C.c_float, vp]
+    lib.kfac_update_factors.restype = C.c_int
+    lib.kfac_invert_batch.argtypes = [vp, C.c_int, i32p, fpp, fpp, C.c_float, vp, vp]
+    lib.kfac_invert_batch.restype = C.c_int
+    lib.kfac_check_info.argtypes = [vp, C.c_int, vp, i32p, vp]
+    lib.kfac_check_info.restype = C.c_int
+    lib.kfac_precondition.argtypes = [vp, C.c_int, i32p, i32p, fpp, fpp, fpp, fpp, vp]
+    lib.kfac_precondition.restype = C.c_int
+    lib.kfac_get_plan_stats.argtypes = [vp, C.c_int, C.POINTER(plan_stats)]
+    lib.kfac_get_plan_stats.restype = None
+    _LIB = lib
+    return lib
+
+
+def make_layer(l) -> layer_struct:
+    """From any object with the fields of synth.shapes.Layer (or a dict)."""
+    g = (lambda k: l[k]) if isinstance(l, dict) else (lambda k: getattr(l, k))
+    return layer_struct(*[int(g(n)) for n, _ in layer_struct._fields_])
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _ptr_array(xs: Optional[Sequence], n: int):
+    if xs is None:
+        return None
+    assert len(xs) == n
+    return (C.c_void_p * n)(*[_ptr(x) for x in xs])
+
+
+def _i32_array(xs: Sequence[int]):
+    return (C.c_int32 * len(xs))(*[int(v) for v in xs])
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        try:
+            import torch
+            if torch.cuda.is_available():
+                return int(torch.cuda.current_stream().cuda_stream) or None
+        except Exception:
+            pass
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+class Context:
+    """Owns one kfac_ctx.  device=-1 gives a host-only context (validation and planning)."""
+
+    def __init__(self, device: int = 0):
+        self.lib = load()
+        h = C.c_void_p()
+        st = self.lib.kfac_create(C.byref(h), int(device))
+        if st != KFAC_OK:
+            raise KfacError(st, self.lib.kfac_last_error(None).decode())
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.kfac_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self) -> str:
+        return self.lib.kfac_last_error(self.h).decode()
+
+    def _check(self, st: int):
+        if st != KFAC_OK:
+            raise KfacError(st, self.last_error())
+
+    # -- the three calls of the hot path (same names as the C ABI) -------------------------
+    def kfac_update_factors(self, layers, act, gout, A, G, xi: float, scale_a: float = 0.0,
+                            scale_g: float = 0.0, stream=None, check: bool = True) -> int:
+        n = len(layers)
+        arr = (layer_struct * max(n, 1))(*[make_layer(l) for l in layers])
+        st = self.lib.kfac_update_factors(self.h, n, arr, _ptr_array(act, n), _ptr_array(gout, n),
+                                          _ptr_array(A, n), _ptr_array(G, n),
+                                          float(xi), float(scale_a), float(scale_g), _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def kfac_invert_batch(self, dims, F, X, gamma: float, info=None, stream=None, check: bool = True) -> int:
+        n = len(dims)
+        st = self.lib.kfac_invert_batch(self.h, n, _i32_array(dims) if n else None, _ptr_array(F, n),
+                                        _ptr_array(X, n), float(gamma), _ptr(info), _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def kfac_check_info(self, n: int, info, stream=None):
+        host = (C.c_int32 * max(n, 1))()
+        st = self.lib.kfac_check_info(self.h, n, _ptr(info), host, _stream_handle(stream))
+        return st, list(host)[:n]
+
+    def kfac_precondition(self, dG, dA, Ginv, Ainv, gradW, out, stream=None, check: bool = True) -> int:
+        n = len(dG)
+        st = self.lib.kfac_precondition(self.h, n, _i32_array(dG) if n else None, _i32_array(dA) if n else None,
+                                        _ptr_array(Ginv, n), _ptr_array(Ainv, n), _ptr_array(gradW, n),
+                                        _ptr_array(out, n), _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    # -- host-side queries -------------------------------------------------------------------
+    def workspace_bytes_factors(self, layers) -> int:
+        arr = (layer_struct * max(len(layers), 1))(*[make_layer(l) for l in layers])
+        return int(self.lib.kfac_workspace_bytes_factors(self.h, len(layers), arr))
+
+    def workspace_bytes_invert(self, dims) -> int:
+        return int(self.lib.kfac_workspace_bytes_invert(self.h, len(dims), _i32_array(dims)))
+
+    def workspace_bytes_precondition(self, dG, dA) -> int:
+        return int(self.lib.kfac_workspace_bytes_precondition(self.h, len(dG), _i32_array(dG), _i32_array(dA)))
+
+    def plan_stats(self, which: int) -> dict:
+        s = plan_stats()
+        self.lib.kfac_get_plan_stats(self.h, which, C.byref(s))
+        return {n: int(getattr(s, n)) for n, _ in plan_stats._fields_}

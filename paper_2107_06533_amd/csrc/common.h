@@ -1,0 +1,106 @@
+// Shared host/device descriptors of the K-FAC kernels (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kfac {
+
+// ---- exact unsigned division by a run-time invariant (multiply-high + shifts) -------------
+struct FastDiv {
+  uint32_t m, sh1, sh2;
+};
+
+inline FastDiv make_fastdiv(uint32_t d) {
+  // round-up method for invariant divisors: l = ceil(log2 d), m = floor(2^32 (2^l - d) / d) + 1
+  uint32_t l = 0;
+  while ((uint64_t(1) << l) < d) ++l;
+  FastDiv f;
+  f.m = uint32_t(((uint64_t(1) << 32) * ((uint64_t(1) << l) - d)) / d + 1);
+  f.sh1 = l < 1 ? l : 1;
+  f.sh2 = l > 0 ? l - 1 : 0;
+  return f;
+}
+
+__host__ __device__ inline uint32_t fast_div(uint32_t n, FastDiv f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  uint32_t t = __umulhi(f.m, n);
+#else
+  uint32_t t = uint32_t((uint64_t(f.m) * n) >> 32);
+#endif
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
+// ---- tile geometry -------------------------------------------------------------------------
+constexpr int BM = 128;   // output tile rows
+constexpr int BN = 128;   // output tile columns
+constexpr int KC = 32;    // contraction depth staged in LDS per step
+constexpr int NT = 256;   // threads per workgroup (4 wavefronts, 2x2, 64x64 outputs each)
+constexpr int PITCH = 129;              // LDS row pitch in floats (odd: conflict-free column writes)
+constexpr int PANEL = KC * PITCH;       // floats of one staged operand panel
+constexpr int ACC_FLUSH = 64;           // k-tiles between flushes of the MFMA accumulator (2048 rows)
+
+// ---- a GEMM operand seen as a [K x M] matrix, k = contraction index ------------------------
+enum : int32_t {
+  OP_KMAJOR = 0,   // element (k, m) at ptr[k*ld + m]; optional virtual ones column at m = M-1
+  OP_CONV11 = 1,   // NCHW tensor through a 1x1 window (also: plain [M, K] row-major matrices)
+  OP_CONV33 = 2,   // 3x3 window
+  OP_CONV77 = 3,   // 7x7 window
+  OP_CONVGEN = 4   // any window (run-time kh, kw)
+};
+
+struct Operand {
+  const float* ptr;
+  int32_t type;
+  int32_t K;        // contraction extent (rows R of the activation / gradient matrix)
+  int32_t M;        // free extent, including the ones column when bias = 1
+  int32_t bias;     // 1: column M-1 is an implicit column of ones
+  int32_t ld;       // OP_KMAJOR: row pitch in elements
+  // convolution view: k = (n*OH + oy)*OW + ox,  m = (c*KH + i)*KW + j
+  int32_t C, H, W, OH, OW, stride, pad, KH, KW;
+  FastDiv dOW, dOHW;
+};
+
+// out = beta * out + alpha * (a^T b), optionally on the lower triangle with mirroring
+enum : int32_t { MIRROR_NONE = 0, MIRROR_ALL = 1, MIRROR_DIAG_TILE = 2 };
+
+struct TileDesc {
+  Operand a, b;
+  float* out;
+  float* partial;   // split-reduction slots, [slot][BM*BN]
+  int32_t ldo;
+  int32_t M, N;     // output extents
+  int32_t sym;      // 1: only tiles bi >= bj exist; a diagonal tile stages one panel, skips blocks above the diagonal
+  int32_t mirror;
+  float alpha, beta;
+};
+
+struct TileJob {
+  int32_t desc;
+  int32_t bi, bj;
+  int32_t kbeg, kend;
+  int32_t part;     // >= 0: write the raw tile to partial slot `part`; -1: apply the epilogue directly
+  int32_t pad0, pad1;
+};
+
+// reduction of split tiles: out = beta*out + alpha * sum_s partial[part0 + s]
+struct ReduceJob {
+  int32_t desc;
+  int32_t bi, bj;
+  int32_t part0, nsplit;
+  int32_t pad0, pad1, pad2;
+};
+
+// ---- batched inversion ---------------------------------------------------------------------
+constexpr int NB = 128;   // pivot block order of the blocked symmetric sweep
+
+struct InvMat {
+  const float* F;   // input [d, d]
+  float* X;         // output / in-place work matrix [d, d]
+  float* Wt;        // panel workspace [NB][ldp]: new column panel (scaled by the inverse pivot)
+  float* Zt;        // panel workspace [NB][ldp]: old column panel
+  float* Q;         // inverse pivot block [NB][NB]
+  int32_t* info;    // may be null
+  int32_t d, ldp, nblk, pad;
+};
+
+}  // namespace kfac

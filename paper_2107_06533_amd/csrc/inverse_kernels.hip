@@ -1,0 +1,260 @@
+// Batched damped SPD inverse by a blocked symmetric sweep (block Gauss-Jordan on the lower
+// triangle).  For a symmetric matrix M partitioned in NB-wide blocks, sweeping pivot block k
+//     M_kk <- -P^-1,   M_ik <- M_ik P^-1,   M_ij <- M_ij - M_ik P^-1 M_kj   (i, j != k),  P = M_kk
+// for every k leaves -M^-1.  Every step is one pivot-block inverse (in registers, one workgroup),
+// one panel product and one rank-NB update of the whole lower triangle, so all steps expose
+// the same parallelism; total work is d^3 flops, the same as Cholesky + triangular inverse +
+// triangular product.  Pivot blocks are Schur complements of an SPD matrix, hence SPD: a
+// non-positive scalar pivot is exactly a non-positive leading minor.
+#include "tile_core.h"
+#include "launch.h"
+
+namespace kfac {
+
+struct MatJob {
+  int32_t mat, bi, bj, aux;
+};
+
+// ---- X(lower tiles) = F + gamma I; info = 0 ---------------------------------------------------
+__global__ __launch_bounds__(NT) void gj_init_kernel(const InvMat* __restrict__ mats,
+                                                     const MatJob* __restrict__ jobs, int njobs, float gamma) {
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const MatJob J = jobs[g];
+  const InvMat Mx = mats[J.mat];
+  const int d = Mx.d;
+  if (J.bi == 0 && J.bj == 0 && threadIdx.x == 0 && Mx.info) *Mx.info = 0;
+  for (int e = threadIdx.x; e < BM * BN; e += NT) {
+    const int i = J.bi * BM + (e >> 7), j = J.bj * BN + (e & 127);
+    if (i >= d || j >= d) continue;
+    const int hi = i > j ? i : j, lo = i > j ? j : i;   // diagonal tiles are kept full
+    float v = Mx.F[(size_t)hi * d + lo];
+    if (i == j) v += gamma;
+    Mx.X[(size_t)i * d + j] = v;
+  }
+}
+
+// ---- pivot block: in-register symmetric sweep of an n x n (n <= 128) SPD block ------------------
+// 256 threads as 16 x 16; thread (ty, tx) holds elements (ty + 16a, tx + 16b), a, b = 0..7.
+// small = 1: block = F + gamma I (whole matrix, d <= NB), result written to X as +inverse.
+// small = 0: block = diagonal block `step` of X; writes Q = +inverse (zero padded to NB x NB)
+//            and the swept block (-inverse) back into X.
+__global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__ mats, int mat0, int step,
+                                                      float gamma, int small) {
+  __shared__ float col[2][NB];
+  __shared__ int bad;
+  const InvMat Mx = mats[mat0 + blockIdx.x];
+  const int t = threadIdx.x, ty = t >> 4, tx = t & 15;
+  const int d = Mx.d;
+  const int k0 = small ? 0 : step * NB;
+  const int n = small ? d : (d - k0 < NB ? d - k0 : NB);
+  const float* src = small ? Mx.F : Mx.X;
+  const float damp = small ? gamma : 0.f;
+
+  float m[8][8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const int i = ty + 16 * a, j = tx + 16 * b;
+      float v = (i == j) ? 1.f : 0.f;
+      if (i < n && j < n) {
+        const int hi = i > j ? i : j, lo = i > j ? j : i;
+        v = src[(size_t)(k0 + hi) * d + k0 + lo];
+        if (i == j) v += damp;
+      }
+      m[a][b] = v;
+    }
+  if (t == 0) bad = 0;
+  __syncthreads();
+
+#pragma unroll
+  for (int kb = 0; kb < 8; ++kb) {
+    if (kb * 16 < n) {
+      const int kk_end = (n - kb * 16 < 16) ? n - kb * 16 : 16;
+      for (int kk = 0; kk < kk_end; ++kk) {
+        const int k = kb * 16 + kk;
+        float* cb = col[k & 1];
+        if (tx == kk) {
+#pragma unroll
+          for (int a = 0; a < 8; ++a) cb[ty + 16 * a] = m[a][kb];
+        }
+        __syncthreads();
+        const float p = cb[k];
+        if (!(p > 0.f) && t == 0 && bad == 0) bad = k + 1;
+        const float ip = 1.f / p;
+        float ci[8], cj[8];
+#pragma unroll
+        for (int a = 0; a < 8; ++a) ci[a] = cb[ty + 16 * a];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) cj[b] = cb[tx + 16 * b];
+#pragma unroll
+        for (int a = 0; a < 8; ++a)
+#pragma unroll
+          for (int b = 0; b < 8; ++b) m[a][b] = fmaf(-(ci[a] * cj[b]), ip, m[a][b]);
+        if (tx == kk) {
+#pragma unroll
+          for (int a = 0; a < 8; ++a) m[a][kb] = ci[a] * ip;
+        }
+        if (ty == kk) {
+#pragma unroll
+          for (int b = 0; b < 8; ++b) m[kb][b] = cj[b] * ip;
+        }
+        if (tx == kk && ty == kk) m[kb][kb] = -ip;
+      }
+    }
+  }
+  __syncthreads();
+  if (t == 0 && Mx.info) {
+    if (small) *Mx.info = bad;                                // whole matrix: sole writer
+    else if (bad && *Mx.info == 0) *Mx.info = k0 + bad;       // first failing sweep wins (zeroed by the init kernel)
+  }
+
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const int i = ty + 16 * a, j = tx + 16 * b;
+      const bool in = i < n && j < n;
+      if (small) {
+        if (in) Mx.X[(size_t)i * d + j] = -m[a][b];
+      } else {
+        Mx.Q[i * NB + j] = in ? -m[a][b] : 0.f;
+        if (in) Mx.X[(size_t)(k0 + i) * d + k0 + j] = m[a][b];
+      }
+    }
+}
+
+// ---- panel: Zt = old block column `step` (as [NB][ldp], k-major), Wt = Q * Zt, X panel <- W -----
+// One job per 128-row tile `it` of the block column (it != step).  Tiles above the pivot live in
+// block row `step` of the lower triangle (read along rows), tiles below in block column `step`.
+__global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restrict__ mats,
+                                                         const MatJob* __restrict__ jobs, int njobs, int step) {
+  __shared__ float Qs[PANEL];
+  __shared__ float Zs[PANEL];
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const MatJob J = jobs[g];
+  const InvMat Mx = mats[J.mat];
+  const int it = J.bi;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
+  const int d = Mx.d, ldp = Mx.ldp;
+  const int k0 = step * NB, i0 = it * BM;
+  const int kb = d - k0 < NB ? d - k0 : NB;
+  const bool above = it < step;
+  const int ml = t & 127, kp = t >> 7;   // row-contiguous mapping
+  const int kl = t & 31, mg = t >> 5;    // column-contiguous mapping
+
+  unsigned mask = 0;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+      if (wm * 64 + a * 32 < kb && i0 + wn * 64 + b * 32 < d) mask |= 1u << (a * 2 + b);
+
+  Acc4 acc;
+  acc_zero(acc);
+  for (int kk0 = 0; kk0 < NB; kk0 += KC) {
+    float rq[16], rz[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) rq[u] = Mx.Q[(kk0 + kp + 2 * u) * NB + ml];
+    if (above) {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int kk = kk0 + kp + 2 * u;
+        rz[u] = (kk < kb) ? Mx.X[(size_t)(k0 + kk) * d + i0 + ml] : 0.f;
+      }
+    } else {
+      const int kk = kk0 + kl;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int i = i0 + mg + 8 * u;
+        rz[u] = (kk < kb && i < d) ? Mx.X[(size_t)i * d + k0 + kk] : 0.f;
+      }
+    }
+    __syncthreads();   // previous chunk fully consumed
+#pragma unroll
+    for (int u = 0; u < 16; ++u) Qs[(kp + 2 * u) * PITCH + ml] = rq[u];
+    if (above) {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) Zs[(kp + 2 * u) * PITCH + ml] = rz[u];
+    } else {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) Zs[kl * PITCH + mg + 8 * u] = rz[u];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 16; ++u) Mx.Zt[(size_t)(kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[(kp + 2 * u) * PITCH + ml];
+    if (mask == 0xFu)
+      mma_ktile<false>(Qs, Zs, acc, wm, wn, lane, mask);
+    else if (mask)
+      mma_ktile<true>(Qs, Zs, acc, wm, wn, lane, mask);
+  }
+
+  // acc(m, i) = W[i][m]: new panel entry for matrix row/col i0+i and pivot column k0+m
+#pragma unroll
+  for (int qd = 0; qd < 4; ++qd) {
+    const int mb0 = wm * 64 + (qd >> 1) * 32, ib0 = wn * 64 + (qd & 1) * 32;
+    const int i = ib0 + mfma_col(lane);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int mm = mb0 + mfma_row(v, lane);
+      const float val = (mask & (1u << qd)) ? acc.c[qd][v] : 0.f;
+      Mx.Wt[(size_t)mm * ldp + i0 + i] = val;
+      if (mm < kb && i0 + i < d) {
+        if (above) Mx.X[(size_t)(k0 + mm) * d + i0 + i] = val;
+        else Mx.X[(size_t)(i0 + i) * d + k0 + mm] = val;
+      }
+    }
+  }
+}
+
+// ---- finish: X = -(swept lower triangle), mirrored to a full symmetric matrix -------------------
+__global__ __launch_bounds__(NT) void gj_finish_kernel(const InvMat* __restrict__ mats,
+                                                       const MatJob* __restrict__ jobs, int njobs) {
+  __shared__ float tile[32][33];
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const MatJob J = jobs[g];
+  const InvMat Mx = mats[J.mat];
+  const int d = Mx.d;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  const int i0 = J.bi * 32, j0 = J.bj * 32;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int li = ty + 8 * r;
+    const int i = i0 + li, j = j0 + tx;
+    float v = 0.f;
+    if (i < d && j < d && i >= j) {
+      v = -Mx.X[(size_t)i * d + j];
+      Mx.X[(size_t)i * d + j] = v;
+    }
+    tile[li][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int lj = ty + 8 * r;             // row of the mirrored tile = column index of the source
+    const int j = j0 + lj, i = i0 + tx;    // writes X[j][i] = X[i][j], i > j
+    if (i < d && j < d && i > j) Mx.X[(size_t)j * d + i] = tile[tx][lj];
+  }
+}
+
+void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(gj_init_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, gamma);
+}
+void launch_gj_pivot(const InvMat* mats, int mat0, int nmats, int step, float gamma, int small, hipStream_t s) {
+  if (nmats <= 0) return;
+  hipLaunchKernelGGL(gj_pivot_kernel, dim3(nmats), dim3(NT), 0, s, mats, mat0, step, gamma, small);
+}
+void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(gj_panel_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, step);
+}
+void launch_gj_finish(const InvMat* mats, const void* jobs, int njobs, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(gj_finish_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs);
+}
+
+}  // namespace kfac

@@ -1,0 +1,797 @@
+// C ABI of the K-FAC hot path: argument validation, schedule construction (host only) and
+// kernel launches.  Everything that decides WHAT runs is here; the arithmetic is in the kernels.
+#include "../../include/kfac.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "launch.h"
+
+using namespace kfac;
+
+namespace {
+
+struct MatJobH {
+  int32_t mat, bi, bj, aux;
+};
+
+inline int ceil_div(int64_t a, int64_t b) { return int((a + b - 1) / b); }
+
+// A device table that is re-uploaded whenever its host image changes.
+struct DynTable {
+  void* dev = nullptr;
+  void* pin = nullptr;
+  size_t cap = 0;
+  hipEvent_t ev = nullptr;
+  bool pending = false;
+  std::vector<unsigned char> last;   // image currently on the device
+};
+
+struct FactorPlan {
+  bool valid = false;
+  std::vector<kfac_layer> layers;
+  std::vector<uint8_t> present;      // [2*l] A wanted, [2*l+1] G wanted
+  std::vector<int> desc_of;          // [2*l + which] -> descriptor index or -1
+  std::vector<TileDesc> descs;       // shape part filled at build time, pointers/scalars per call
+  void* d_jobs = nullptr;
+  void* d_rjobs = nullptr;
+  int njobs = 0, nrjobs = 0;
+  size_t nslots = 0;
+  DynTable tab;
+  kfac_plan_stats stats{};
+};
+
+struct InvertPlan {
+  bool valid = false;
+  std::vector<int32_t> dims;
+  std::vector<int> order;            // sorted position -> caller index (large first, descending d)
+  int n_large = 0, n_small = 0, nsteps = 0;
+  std::vector<int> active;           // [step] number of large matrices still being swept
+  std::vector<int> panel_off, upd_off;
+  std::vector<size_t> ws_off;        // per large matrix: float offset of its workspace
+  void* d_init = nullptr; int n_init = 0;
+  void* d_finish = nullptr; int n_finish = 0;
+  void* d_panel = nullptr;
+  void* d_upd = nullptr;
+  DynTable tab;                      // [InvMat x n][TileDesc x n_large]
+  size_t ws_floats = 0;
+  kfac_plan_stats stats{};
+};
+
+struct PrecondPlan {
+  bool valid = false;
+  std::vector<int32_t> dG, dA;
+  std::vector<size_t> t_off;         // per layer: float offset of the intermediate Ginv.V
+  void* d_jobs1 = nullptr; void* d_jobs2 = nullptr;
+  int njobs1 = 0, njobs2 = 0;
+  DynTable tab;                      // [TileDesc x 2n]
+  size_t ws_floats = 0;
+  kfac_plan_stats stats{};
+};
+
+}  // namespace
+
+struct kfac_ctx {
+  int device = -1;
+  bool host_only = true;
+  std::string err;
+  void* ws = nullptr;
+  size_t ws_cap = 0;
+  int kjob = 8192;                   // longest contraction run of one factor tile job (rows)
+  FactorPlan fp;
+  InvertPlan ip;
+  PrecondPlan pp;
+};
+
+namespace {
+
+std::string g_noctx_err = "no context";
+
+kfac_status fail(kfac_ctx* ctx, kfac_status st, const std::string& msg) {
+  if (ctx) ctx->err = msg; else g_noctx_err = msg;
+  return st;
+}
+
+#define HIP_TRY(ctx, expr)                                                                   \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess)                                                                    \
+      return fail(ctx, KFAC_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+struct DeviceGuard {
+  int prev = -1;
+  bool active = false;
+  explicit DeviceGuard(const kfac_ctx* c) {
+    if (!c->host_only && hipGetDevice(&prev) == hipSuccess && prev != c->device) {
+      active = hipSetDevice(c->device) == hipSuccess;
+    }
+  }
+  ~DeviceGuard() {
+    if (active) (void)hipSetDevice(prev);
+  }
+};
+
+void free_dev(void*& p) {
+  if (p) { (void)hipFree(p); p = nullptr; }
+}
+
+void free_table(DynTable& t) {
+  free_dev(t.dev);
+  if (t.pin) { (void)hipHostFree(t.pin); t.pin = nullptr; }
+  if (t.ev) { (void)hipEventDestroy(t.ev); t.ev = nullptr; }
+  t.cap = 0; t.pending = false; t.last.clear();
+}
+
+kfac_status upload_static(kfac_ctx* ctx, void** dev, const void* src, size_t bytes) {
+  free_dev(*dev);
+  if (bytes == 0) return KFAC_OK;
+  HIP_TRY(ctx, hipMalloc(dev, bytes));
+  HIP_TRY(ctx, hipMemcpy(*dev, src, bytes, hipMemcpyHostToDevice));
+  return KFAC_OK;
+}
+
+// Stream-ordered refresh of a device table; skipped when the image is unchanged.
+kfac_status sync_table(kfac_ctx* ctx, DynTable& t, const void* img, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return KFAC_OK;
+  if (t.last.size() == bytes && std::memcmp(t.last.data(), img, bytes) == 0) return KFAC_OK;
+  if (bytes > t.cap) {
+    if (t.pending) HIP_TRY(ctx, hipEventSynchronize(t.ev));
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    free_dev(t.dev);
+    if (t.pin) { (void)hipHostFree(t.pin); t.pin = nullptr; }
+    HIP_TRY(ctx, hipMalloc(&t.dev, bytes));
+    HIP_TRY(ctx, hipHostMalloc(&t.pin, bytes, hipHostMallocDefault));
+    t.cap = bytes;
+    if (!t.ev) HIP_TRY(ctx, hipEventCreateWithFlags(&t.ev, hipEventDisableTiming));
+    t.pending = false;
+  }
+  if (t.pending) HIP_TRY(ctx, hipEventSynchronize(t.ev));
+  std::memcpy(t.pin, img, bytes);
+  HIP_TRY(ctx, hipMemcpyAsync(t.dev, t.pin, bytes, hipMemcpyHostToDevice, s));
+  HIP_TRY(ctx, hipEventRecord(t.ev, s));
+  t.pending = true;
+  t.last.assign(static_cast<const unsigned char*>(img), static_cast<const unsigned char*>(img) + bytes);
+  return KFAC_OK;
+}
+
+kfac_status ensure_ws(kfac_ctx* ctx, size_t bytes) {
+  if (bytes <= ctx->ws_cap) return KFAC_OK;
+  if (hipDeviceSynchronize() != hipSuccess) return fail(ctx, KFAC_ERR_DEVICE, "hipDeviceSynchronize failed");
+  free_dev(ctx->ws);
+  ctx->ws_cap = 0;
+  if (hipMalloc(&ctx->ws, bytes) != hipSuccess) {
+    ctx->ws = nullptr;
+    (void)hipGetLastError();
+    return fail(ctx, KFAC_ERR_WORKSPACE, "cannot allocate " + std::to_string(bytes) + " bytes of device workspace");
+  }
+  ctx->ws_cap = bytes;
+  return KFAC_OK;
+}
+
+// ------------------------------------------------------------------------------- layers
+bool layer_valid(const kfac_layer& L, std::string* why) {
+  auto bad = [&](const char* m) { if (why) *why = m; return false; };
+  if (L.kind != 0 && L.kind != 1) return bad("layer.kind must be 0 (linear) or 1 (conv2d)");
+  if (L.has_bias != 0 && L.has_bias != 1) return bad("layer.has_bias must be 0 or 1");
+  if (L.c_in < 1 || L.c_out < 1) return bad("layer.c_in and layer.c_out must be positive");
+  if (L.kind == 0) {
+    if (L.rows < 1) return bad("linear layer needs rows >= 1");
+    return true;
+  }
+  if (L.n < 1 || L.h < 1 || L.w < 1) return bad("conv layer needs n, h, w >= 1");
+  if (L.kh < 1 || L.kw < 1 || L.kh > 127 || L.kw > 127) return bad("conv kernel size must be in 1..127");
+  if (L.stride < 1) return bad("conv stride must be >= 1");
+  if (L.pad < 0 || L.pad > 127) return bad("conv pad must be in 0..127");
+  if (L.h + 2 * L.pad < L.kh || L.w + 2 * L.pad < L.kw) return bad("conv output is empty");
+  const int64_t oh = (L.h + 2 * L.pad - L.kh) / L.stride + 1, ow = (L.w + 2 * L.pad - L.kw) / L.stride + 1;
+  const int64_t lim = (int64_t(1) << 31) - 1;
+  if (int64_t(L.n) * oh * ow > lim) return bad("conv rows n*oh*ow exceed 2^31-1");
+  if (int64_t(L.c_in) * L.h * L.w > lim || int64_t(L.c_out) * oh * ow > lim) return bad("one sample exceeds 2^31-1 elements");
+  if (int64_t(L.c_in) * L.kh * L.kw + 1 > (1 << 20)) return bad("factor dimension exceeds 2^20");
+  return true;
+}
+
+int conv_oh(const kfac_layer& L) { return (L.h + 2 * L.pad - L.kh) / L.stride + 1; }
+int conv_ow(const kfac_layer& L) { return (L.w + 2 * L.pad - L.kw) / L.stride + 1; }
+int64_t rows_of(const kfac_layer& L) { return L.kind == 0 ? L.rows : int64_t(L.n) * conv_oh(L) * conv_ow(L); }
+int dA_of(const kfac_layer& L) { return (L.kind == 0 ? L.c_in : L.c_in * L.kh * L.kw) + L.has_bias; }
+
+Operand act_operand(const kfac_layer& L) {
+  Operand o{};
+  o.K = int32_t(rows_of(L));
+  o.M = dA_of(L);
+  o.bias = L.has_bias;
+  if (L.kind == 0) {
+    o.type = OP_KMAJOR;
+    o.ld = L.c_in;
+    return o;
+  }
+  if (L.kh == 1 && L.kw == 1 && L.pad == 0) o.type = OP_CONV11;
+  else if (L.kh == 3 && L.kw == 3) o.type = OP_CONV33;
+  else if (L.kh == 7 && L.kw == 7) o.type = OP_CONV77;
+  else o.type = OP_CONVGEN;
+  o.C = L.c_in; o.H = L.h; o.W = L.w; o.OH = conv_oh(L); o.OW = conv_ow(L);
+  o.stride = L.stride; o.pad = L.pad; o.KH = L.kh; o.KW = L.kw;
+  o.dOW = make_fastdiv(uint32_t(o.OW));
+  o.dOHW = make_fastdiv(uint32_t(o.OH) * uint32_t(o.OW));
+  return o;
+}
+
+Operand gout_operand(const kfac_layer& L) {
+  Operand o{};
+  o.K = int32_t(rows_of(L));
+  o.M = L.c_out;
+  o.bias = 0;
+  if (L.kind == 0) {
+    o.type = OP_KMAJOR;
+    o.ld = L.c_out;
+    return o;
+  }
+  o.type = OP_CONV11;   // [n, c_out, oh, ow] read through a 1x1 window: k = (n, oy, ox), m = channel
+  o.C = L.c_out; o.H = conv_oh(L); o.W = conv_ow(L); o.OH = o.H; o.OW = o.W;
+  o.stride = 1; o.pad = 0; o.KH = 1; o.KW = 1;
+  o.dOW = make_fastdiv(uint32_t(o.OW));
+  o.dOHW = make_fastdiv(uint32_t(o.OH) * uint32_t(o.OW));
+  return o;
+}
+
+Operand rowmajor_operand(const float* p, int K, int M, int ld) {   // element (k, m) at p[k*ld + m]
+  Operand o{};
+  o.ptr = p; o.type = OP_KMAJOR; o.K = K; o.M = M; o.bias = 0; o.ld = ld;
+  return o;
+}
+
+Operand transposed_operand(const float* p, int K, int M) {   // element (k, m) at p[m*K + k]
+  Operand o{};
+  o.ptr = p; o.type = OP_CONV11; o.K = K; o.M = M; o.bias = 0;
+  o.C = M; o.H = 1; o.W = K; o.OH = 1; o.OW = K; o.stride = 1; o.pad = 0; o.KH = 1; o.KW = 1;
+  o.dOW = make_fastdiv(uint32_t(K));
+  o.dOHW = make_fastdiv(uint32_t(K));
+  return o;
+}
+
+// 32x32 MFMA blocks of a 128x128 tile that hold wanted outputs
+int active_blocks(int M, int N, int bi, int bj, bool sym) {
+  const int rb = std::min(4, ceil_div(std::min(BM, M - bi * BM), 32));
+  const int cb = std::min(4, ceil_div(std::min(BN, N - bj * BN), 32));
+  if (!(sym && bi == bj)) return rb * cb;
+  int c = 0;
+  for (int r = 0; r < rb; ++r)
+    for (int q = 0; q < cb; ++q) c += r >= q;
+  return c;
+}
+
+// ------------------------------------------------------------------------------- factor plan
+void release(FactorPlan& p) {
+  free_dev(p.d_jobs); free_dev(p.d_rjobs); free_table(p.tab);
+  p = FactorPlan{};
+}
+void release(InvertPlan& p) {
+  free_dev(p.d_init); free_dev(p.d_finish); free_dev(p.d_panel); free_dev(p.d_upd); free_table(p.tab);
+  p = InvertPlan{};
+}
+void release(PrecondPlan& p) {
+  free_dev(p.d_jobs1); free_dev(p.d_jobs2); free_table(p.tab);
+  p = PrecondPlan{};
+}
+
+struct FactorSchedule {
+  std::vector<TileDesc> descs;
+  std::vector<int> desc_of;
+  std::vector<TileJob> jobs;
+  std::vector<ReduceJob> rjobs;
+  size_t nslots = 0;
+  kfac_plan_stats stats{};
+};
+
+FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vector<uint8_t>& present, int kjob) {
+  FactorSchedule S;
+  S.desc_of.assign(2 * n, -1);
+  for (int l = 0; l < n; ++l)
+    for (int which = 0; which < 2; ++which) {
+      if (!present[2 * l + which]) continue;
+      TileDesc D{};
+      D.a = which == 0 ? act_operand(layers[l]) : gout_operand(layers[l]);
+      D.b = D.a;
+      D.M = D.N = D.ldo = D.a.M;
+      D.sym = 1;
+      D.mirror = MIRROR_ALL;
+      S.desc_of[2 * l + which] = int(S.descs.size());
+      S.descs.push_back(D);
+    }
+  struct Tmp { TileJob j; int64_t cost; };
+  std::vector<Tmp> tmp;
+  for (size_t di = 0; di < S.descs.size(); ++di) {
+    const TileDesc& D = S.descs[di];
+    const int d = D.M, R = D.a.K, T = ceil_div(d, BM);
+    int nsplit = ceil_div(R, kjob);
+    int chunk = ceil_div(ceil_div(R, nsplit), KC) * KC;
+    nsplit = ceil_div(R, chunk);
+    for (int bi = 0; bi < T; ++bi)
+      for (int bj = 0; bj <= bi; ++bj) {
+        const int ab = active_blocks(d, d, bi, bj, true);
+        if (nsplit > 1) {
+          ReduceJob rj{};
+          rj.desc = int(di); rj.bi = bi; rj.bj = bj; rj.part0 = int(S.nslots); rj.nsplit = nsplit;
+          S.rjobs.push_back(rj);
+          S.stats.n_split++;
+        }
+        for (int s = 0; s < nsplit; ++s) {
+          TileJob j{};
+          j.desc = int(di); j.bi = bi; j.bj = bj;
+          j.kbeg = s * chunk; j.kend = std::min(R, (s + 1) * chunk);
+          j.part = nsplit > 1 ? int(S.nslots++) : -1;
+          const int64_t c = int64_t(j.kend - j.kbeg) * ab;
+          tmp.push_back({j, c});
+          S.stats.mfma_flops += c * 32 * 32 * 2;
+        }
+      }
+  }
+  // longest jobs first: the hardware dispatches workgroups in index order, so this is the
+  // list-scheduling (largest-first) rule applied to compute units
+  std::stable_sort(tmp.begin(), tmp.end(), [](const Tmp& x, const Tmp& y) { return x.cost > y.cost; });
+  S.jobs.reserve(tmp.size());
+  for (auto& t : tmp) S.jobs.push_back(t.j);
+  S.stats.n_jobs = int64_t(S.jobs.size() + S.rjobs.size());
+  S.stats.n_launches = 1 + (S.rjobs.empty() ? 0 : 1);
+  S.stats.ws_bytes = int64_t(S.nslots * size_t(BM) * BN * sizeof(float));
+  return S;
+}
+
+// ------------------------------------------------------------------------------- invert plan
+struct InvertSchedule {
+  std::vector<int> order;
+  int n_large = 0, n_small = 0, nsteps = 0;
+  std::vector<int> active, panel_off, upd_off;
+  std::vector<size_t> ws_off;
+  std::vector<int> nblk, ldp;
+  std::vector<MatJobH> init, finish, panel;
+  std::vector<TileJob> upd;
+  size_t ws_floats = 0;
+  kfac_plan_stats stats{};
+};
+
+InvertSchedule schedule_invert(int n, const int32_t* dims) {
+  InvertSchedule S;
+  S.order.resize(n);
+  for (int i = 0; i < n; ++i) S.order[i] = i;
+  std::stable_sort(S.order.begin(), S.order.end(), [&](int a, int b) { return dims[a] > dims[b]; });
+  for (int i = 0; i < n; ++i) (dims[S.order[i]] > NB ? S.n_large : S.n_small)++;
+  S.nblk.resize(S.n_large); S.ldp.resize(S.n_large); S.ws_off.resize(S.n_large);
+  for (int m = 0; m < S.n_large; ++m) {
+    const int d = dims[S.order[m]];
+    S.nblk[m] = ceil_div(d, NB);
+    S.ldp[m] = S.nblk[m] * NB;
+    S.ws_off[m] = S.ws_floats;
+    S.ws_floats += size_t(2) * NB * S.ldp[m] + size_t(NB) * NB;
+    S.nsteps = std::max(S.nsteps, S.nblk[m]);
+    for (int bi = 0; bi < S.nblk[m]; ++bi)
+      for (int bj = 0; bj <= bi; ++bj) S.init.push_back({m, bi, bj, 0});
+    const int t32 = ceil_div(d, 32);
+    for (int bi = 0; bi < t32; ++bi)
+      for (int bj = 0; bj <= bi; ++bj) S.finish.push_back({m, bi, bj, 0});
+  }
+  S.active.assign(S.nsteps, 0);
+  S.panel_off.assign(S.nsteps + 1, 0);
+  S.upd_off.assign(S.nsteps + 1, 0);
+  for (int s = 0; s < S.nsteps; ++s) {
+    for (int m = 0; m < S.n_large; ++m) {
+      if (S.nblk[m] <= s) continue;
+      S.active[s]++;
+      const int d = dims[S.order[m]];
+      const int kb = std::min(NB, d - s * NB);
+      for (int it = 0; it < S.nblk[m]; ++it)
+        if (it != s) S.panel.push_back({m, it, 0, 0});
+      for (int bi = 0; bi < S.nblk[m]; ++bi) {
+        if (bi == s) continue;
+        for (int bj = 0; bj <= bi; ++bj) {
+          if (bj == s) continue;
+          TileJob j{};
+          j.desc = m; j.bi = bi; j.bj = bj; j.kbeg = 0; j.kend = kb; j.part = -1;
+          S.upd.push_back(j);
+          S.stats.mfma_flops += int64_t(ceil_div(kb, KC) * KC) * active_blocks(d, d, bi, bj, true) * 32 * 32 * 2;
+        }
+      }
+      S.stats.mfma_flops += int64_t(S.nblk[m] - 1) * NB * 16 * 32 * 32 * 2;   // panel products
+    }
+    S.panel_off[s + 1] = int(S.panel.size());
+    S.upd_off[s + 1] = int(S.upd.size());
+  }
+  S.stats.n_jobs = int64_t(S.init.size() + S.finish.size() + S.panel.size() + S.upd.size()) + S.n_small;
+  S.stats.n_launches = (S.n_small ? 1 : 0) + (S.n_large ? 2 + 3 * S.nsteps : 0);
+  S.stats.ws_bytes = int64_t(S.ws_floats * sizeof(float));
+  return S;
+}
+
+// ------------------------------------------------------------------------------- precondition plan
+struct PrecondSchedule {
+  std::vector<size_t> t_off;
+  std::vector<TileJob> jobs1, jobs2;
+  size_t ws_floats = 0;
+  kfac_plan_stats stats{};
+};
+
+PrecondSchedule schedule_precond(int n, const int32_t* dG, const int32_t* dA) {
+  PrecondSchedule S;
+  S.t_off.resize(n);
+  struct Tmp { TileJob j; int64_t cost; };
+  std::vector<Tmp> t1, t2;
+  for (int l = 0; l < n; ++l) {
+    S.t_off[l] = S.ws_floats;
+    S.ws_floats += size_t(dG[l]) * dA[l];
+    const int Tm = ceil_div(dG[l], BM), Tn = ceil_div(dA[l], BN);
+    for (int bi = 0; bi < Tm; ++bi)
+      for (int bj = 0; bj < Tn; ++bj) {
+        const int ab = active_blocks(dG[l], dA[l], bi, bj, false);
+        TileJob j{};
+        j.bi = bi; j.bj = bj; j.kbeg = 0; j.part = -1;
+        j.desc = 2 * l; j.kend = dG[l];
+        t1.push_back({j, int64_t(dG[l]) * ab});
+        j.desc = 2 * l + 1; j.kend = dA[l];
+        t2.push_back({j, int64_t(dA[l]) * ab});
+        S.stats.mfma_flops += (int64_t(ceil_div(dG[l], KC)) + ceil_div(dA[l], KC)) * KC * ab * 32 * 32 * 2;
+      }
+  }
+  auto by_cost = [](const Tmp& x, const Tmp& y) { return x.cost > y.cost; };
+  std::stable_sort(t1.begin(), t1.end(), by_cost);
+  std::stable_sort(t2.begin(), t2.end(), by_cost);
+  for (auto& t : t1) S.jobs1.push_back(t.j);
+  for (auto& t : t2) S.jobs2.push_back(t.j);
+  S.stats.n_jobs = int64_t(S.jobs1.size() + S.jobs2.size());
+  S.stats.n_launches = n ? 2 : 0;
+  S.stats.ws_bytes = int64_t(S.ws_floats * sizeof(float));
+  return S;
+}
+
+bool finite_in(float v, float lo, float hi) { return v >= lo && v <= hi; }
+
+}  // namespace
+
+// =================================================================================== C ABI
+extern "C" {
+
+kfac_status kfac_create(kfac_ctx** out, int device) {
+  if (!out) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_create: out is NULL");
+  *out = nullptr;
+  if (device < -1) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_create: device must be >= -1");
+  kfac_ctx* c = new kfac_ctx();
+  c->device = device;
+  c->host_only = device < 0;
+  if (const char* e = std::getenv("KFAC_KJOB")) {
+    const int v = std::atoi(e);
+    if (v >= KC) c->kjob = v;
+  }
+  if (!c->host_only) {
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device >= count) {
+      (void)hipGetLastError();
+      delete c;
+      return fail(nullptr, KFAC_ERR_DEVICE, "kfac_create: no such HIP device");
+    }
+  }
+  *out = c;
+  return KFAC_OK;
+}
+
+void kfac_destroy(kfac_ctx* ctx) {
+  if (!ctx) return;
+  if (!ctx->host_only) {
+    DeviceGuard g(ctx);
+    (void)hipDeviceSynchronize();
+    release(ctx->fp); release(ctx->ip); release(ctx->pp);
+    free_dev(ctx->ws);
+  }
+  delete ctx;
+}
+
+const char* kfac_last_error(const kfac_ctx* ctx) { return ctx ? ctx->err.c_str() : g_noctx_err.c_str(); }
+
+int32_t kfac_layer_dA(const kfac_layer* L) { return (L && layer_valid(*L, nullptr)) ? dA_of(*L) : 0; }
+int32_t kfac_layer_dG(const kfac_layer* L) { return (L && layer_valid(*L, nullptr)) ? L->c_out : 0; }
+int64_t kfac_layer_rows(const kfac_layer* L) { return (L && layer_valid(*L, nullptr)) ? rows_of(*L) : 0; }
+
+size_t kfac_workspace_bytes_factors(const kfac_ctx* ctx, int n, const kfac_layer* layers) {
+  if (n <= 0 || !layers) return 0;
+  for (int l = 0; l < n; ++l)
+    if (!layer_valid(layers[l], nullptr)) return 0;
+  std::vector<uint8_t> present(2 * n, 1);
+  return size_t(schedule_factors(n, layers, present, ctx ? ctx->kjob : 8192).stats.ws_bytes);
+}
+
+size_t kfac_workspace_bytes_invert(const kfac_ctx*, int n, const int32_t* dims) {
+  if (n <= 0 || !dims) return 0;
+  for (int i = 0; i < n; ++i)
+    if (dims[i] < 1) return 0;
+  return size_t(schedule_invert(n, dims).stats.ws_bytes);
+}
+
+size_t kfac_workspace_bytes_precondition(const kfac_ctx*, int n, const int32_t* dG, const int32_t* dA) {
+  if (n <= 0 || !dG || !dA) return 0;
+  for (int i = 0; i < n; ++i)
+    if (dG[i] < 1 || dA[i] < 1) return 0;
+  return size_t(schedule_precond(n, dG, dA).stats.ws_bytes);
+}
+
+void kfac_get_plan_stats(const kfac_ctx* ctx, int which, kfac_plan_stats* out) {
+  if (!out) return;
+  *out = kfac_plan_stats{};
+  if (!ctx) return;
+  if (which == 0) *out = ctx->fp.stats;
+  else if (which == 1) *out = ctx->ip.stats;
+  else if (which == 2) *out = ctx->pp.stats;
+}
+
+// ----------------------------------------------------------------------------------- factors
+kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
+                                const float* const* act, const float* const* gout,
+                                float* const* A, float* const* G,
+                                float xi, float scale_a, float scale_g, void* hip_stream) {
+  if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_update_factors: ctx is NULL");
+  if (n < 0) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors: n_layers < 0");
+  if (n == 0) return KFAC_OK;
+  if (!layers) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors: layers is NULL");
+  if (!finite_in(xi, 0.f, 1.f)) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors: xi must be in [0, 1]");
+  if (std::isnan(scale_a) || std::isnan(scale_g) || std::isinf(scale_a) || std::isinf(scale_g))
+    return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors: scale must be finite");
+  std::vector<uint8_t> present(2 * n, 0);
+  for (int l = 0; l < n; ++l) {
+    std::string why;
+    if (!layer_valid(layers[l], &why))
+      return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors: layer " + std::to_string(l) + ": " + why);
+    if (act && act[l]) {
+      if (!A || !A[l]) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors: act given but A is NULL for layer " + std::to_string(l));
+      present[2 * l] = 1;
+    }
+    if (gout && gout[l]) {
+      if (!G || !G[l]) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors: gout given but G is NULL for layer " + std::to_string(l));
+      present[2 * l + 1] = 1;
+    }
+  }
+
+  FactorPlan& P = ctx->fp;
+  const bool same = P.valid && int(P.layers.size()) == n && P.present == present &&
+                    std::memcmp(P.layers.data(), layers, sizeof(kfac_layer) * n) == 0;
+  DeviceGuard guard(ctx);
+  if (!same) {
+    FactorSchedule S = schedule_factors(n, layers, present, ctx->kjob);
+    if (!ctx->host_only) {
+      HIP_TRY(ctx, hipDeviceSynchronize());
+      release(P);
+    } else {
+      P = FactorPlan{};
+    }
+    P.layers.assign(layers, layers + n);
+    P.present = present;
+    P.desc_of = S.desc_of;
+    P.descs = S.descs;
+    P.njobs = int(S.jobs.size());
+    P.nrjobs = int(S.rjobs.size());
+    P.nslots = S.nslots;
+    P.stats = S.stats;
+    if (!ctx->host_only) {
+      kfac_status st = upload_static(ctx, &P.d_jobs, S.jobs.data(), S.jobs.size() * sizeof(TileJob));
+      if (st != KFAC_OK) return st;
+      st = upload_static(ctx, &P.d_rjobs, S.rjobs.data(), S.rjobs.size() * sizeof(ReduceJob));
+      if (st != KFAC_OK) return st;
+    }
+    P.valid = true;
+  }
+  if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  kfac_status st = ensure_ws(ctx, P.nslots * size_t(BM) * BN * sizeof(float));
+  if (st != KFAC_OK) return st;
+  for (int l = 0; l < n; ++l)
+    for (int which = 0; which < 2; ++which) {
+      const int di = P.desc_of[2 * l + which];
+      if (di < 0) continue;
+      TileDesc& D = P.descs[di];
+      D.a.ptr = which == 0 ? act[l] : gout[l];
+      D.b.ptr = D.a.ptr;
+      D.out = which == 0 ? A[l] : G[l];
+      D.partial = static_cast<float*>(ctx->ws);
+      const float sc = which == 0 ? scale_a : scale_g;
+      const float scale = sc > 0.f ? sc : float(1.0 / double(D.a.K));
+      D.alpha = (1.f - xi) * scale;
+      D.beta = xi;
+    }
+  st = sync_table(ctx, P.tab, P.descs.data(), P.descs.size() * sizeof(TileDesc), s);
+  if (st != KFAC_OK) return st;
+  const TileDesc* d_descs = static_cast<const TileDesc*>(P.tab.dev);
+  launch_tile_any(d_descs, static_cast<const TileJob*>(P.d_jobs), P.njobs, 0, s);
+  launch_tile_reduce(d_descs, static_cast<const ReduceJob*>(P.d_rjobs), P.nrjobs, s);
+  HIP_TRY(ctx, hipGetLastError());
+  return KFAC_OK;
+}
+
+// ----------------------------------------------------------------------------------- inverse
+kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const float* const* F,
+                              float* const* X, float gamma, int32_t* info_dev, void* hip_stream) {
+  if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: ctx is NULL");
+  if (n < 0) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: n_mats < 0");
+  if (n == 0) return KFAC_OK;
+  if (!dims || !F || !X) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: dims, F or X is NULL");
+  if (!(gamma >= 0.f) || std::isinf(gamma)) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: gamma must be finite and >= 0");
+  for (int i = 0; i < n; ++i) {
+    if (dims[i] < 1 || dims[i] > (1 << 20))
+      return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: dims[" + std::to_string(i) + "] out of range");
+    if (!F[i] || !X[i]) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: NULL matrix pointer at " + std::to_string(i));
+    if (F[i] == X[i]) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: X must not alias F at " + std::to_string(i));
+  }
+
+  InvertPlan& P = ctx->ip;
+  const bool same = P.valid && int(P.dims.size()) == n && std::memcmp(P.dims.data(), dims, sizeof(int32_t) * n) == 0;
+  DeviceGuard guard(ctx);
+  if (!same) {
+    InvertSchedule S = schedule_invert(n, dims);
+    if (!ctx->host_only) {
+      HIP_TRY(ctx, hipDeviceSynchronize());
+      release(P);
+    } else {
+      P = InvertPlan{};
+    }
+    P.dims.assign(dims, dims + n);
+    P.order = S.order; P.n_large = S.n_large; P.n_small = S.n_small; P.nsteps = S.nsteps;
+    P.active = S.active; P.panel_off = S.panel_off; P.upd_off = S.upd_off; P.ws_off = S.ws_off;
+    P.n_init = int(S.init.size()); P.n_finish = int(S.finish.size());
+    P.ws_floats = S.ws_floats;
+    P.stats = S.stats;
+    if (!ctx->host_only) {
+      kfac_status st;
+      if ((st = upload_static(ctx, &P.d_init, S.init.data(), S.init.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+      if ((st = upload_static(ctx, &P.d_finish, S.finish.data(), S.finish.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+      if ((st = upload_static(ctx, &P.d_panel, S.panel.data(), S.panel.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+      if ((st = upload_static(ctx, &P.d_upd, S.upd.data(), S.upd.size() * sizeof(TileJob))) != KFAC_OK) return st;
+    }
+    P.valid = true;
+  }
+  if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  kfac_status st = ensure_ws(ctx, P.ws_floats * sizeof(float));
+  if (st != KFAC_OK) return st;
+
+  // per-call tables: [InvMat x n] then [TileDesc x n_large]
+  const size_t mats_bytes = sizeof(InvMat) * size_t(n);
+  const size_t tab_bytes = mats_bytes + sizeof(TileDesc) * size_t(P.n_large);
+  std::vector<unsigned char> img(tab_bytes, 0);
+  InvMat* hm = reinterpret_cast<InvMat*>(img.data());
+  TileDesc* hd = reinterpret_cast<TileDesc*>(img.data() + mats_bytes);
+  float* wsf = static_cast<float*>(ctx->ws);
+  for (int m = 0; m < n; ++m) {
+    const int o = P.order[m];
+    InvMat& M = hm[m];
+    M.F = F[o]; M.X = X[o]; M.d = dims[o];
+    M.info = info_dev ? info_dev + o : nullptr;
+    if (m < P.n_large) {
+      M.nblk = ceil_div(M.d, NB);
+      M.ldp = M.nblk * NB;
+      M.Wt = wsf + P.ws_off[m];
+      M.Zt = M.Wt + size_t(NB) * M.ldp;
+      M.Q = M.Zt + size_t(NB) * M.ldp;
+      TileDesc& D = hd[m];
+      D.a = rowmajor_operand(M.Wt, NB, M.ldp, M.ldp);
+      D.b = rowmajor_operand(M.Zt, NB, M.ldp, M.ldp);
+      D.out = M.X; D.ldo = M.d; D.M = D.N = M.d;
+      D.sym = 1; D.mirror = MIRROR_DIAG_TILE; D.alpha = -1.f; D.beta = 1.f;
+    } else {
+      M.nblk = 1; M.ldp = NB;
+    }
+  }
+  st = sync_table(ctx, P.tab, img.data(), tab_bytes, s);
+  if (st != KFAC_OK) return st;
+  const InvMat* d_mats = static_cast<const InvMat*>(P.tab.dev);
+  const TileDesc* d_descs = reinterpret_cast<const TileDesc*>(static_cast<const unsigned char*>(P.tab.dev) + mats_bytes);
+
+  launch_gj_pivot(d_mats, P.n_large, P.n_small, 0, gamma, 1, s);
+  if (P.n_large) {
+    launch_gj_init(d_mats, P.d_init, P.n_init, gamma, s);
+    for (int step = 0; step < P.nsteps; ++step) {
+      launch_gj_pivot(d_mats, 0, P.active[step], step, gamma, 0, s);
+      launch_gj_panel(d_mats, static_cast<const MatJobH*>(P.d_panel) + P.panel_off[step],
+                      P.panel_off[step + 1] - P.panel_off[step], step, s);
+      launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_upd) + P.upd_off[step],
+                       P.upd_off[step + 1] - P.upd_off[step], 0, s);
+    }
+    launch_gj_finish(d_mats, P.d_finish, P.n_finish, s);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  return KFAC_OK;
+}
+
+kfac_status kfac_check_info(kfac_ctx* ctx, int n, const int32_t* info_dev, int32_t* info_host, void* hip_stream) {
+  if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_check_info: ctx is NULL");
+  if (n < 0 || (n > 0 && !info_dev)) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_check_info: bad arguments");
+  if (n == 0) return KFAC_OK;
+  if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context");
+  DeviceGuard guard(ctx);
+  std::vector<int32_t> tmp(n);
+  HIP_TRY(ctx, hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+  HIP_TRY(ctx, hipMemcpy(tmp.data(), info_dev, sizeof(int32_t) * n, hipMemcpyDeviceToHost));
+  if (info_host) std::memcpy(info_host, tmp.data(), sizeof(int32_t) * n);
+  for (int i = 0; i < n; ++i)
+    if (tmp[i] != 0)
+      return fail(ctx, KFAC_ERR_NOT_SPD, "matrix " + std::to_string(i) + ": leading minor of order " +
+                                             std::to_string(tmp[i]) + " is not positive");
+  return KFAC_OK;
+}
+
+// ----------------------------------------------------------------------------------- precondition
+kfac_status kfac_precondition(kfac_ctx* ctx, int n, const int32_t* dG, const int32_t* dA,
+                              const float* const* Ginv, const float* const* Ainv,
+                              const float* const* gradW, float* const* out, void* hip_stream) {
+  if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_precondition: ctx is NULL");
+  if (n < 0) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition: n_layers < 0");
+  if (n == 0) return KFAC_OK;
+  if (!dG || !dA || !Ginv || !Ainv || !gradW || !out)
+    return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition: NULL array argument");
+  for (int l = 0; l < n; ++l) {
+    if (dG[l] < 1 || dA[l] < 1 || dG[l] > (1 << 20) || dA[l] > (1 << 20) ||
+        int64_t(dG[l]) * std::max(dG[l], dA[l]) > (int64_t(1) << 31) - 1)
+      return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition: dimension out of range at layer " + std::to_string(l));
+    if (!Ginv[l] || !Ainv[l] || !gradW[l] || !out[l])
+      return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition: NULL matrix pointer at layer " + std::to_string(l));
+    if (out[l] == Ginv[l] || out[l] == Ainv[l])
+      return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition: out aliases an inverse at layer " + std::to_string(l));
+  }
+  PrecondPlan& P = ctx->pp;
+  const bool same = P.valid && int(P.dG.size()) == n && std::memcmp(P.dG.data(), dG, sizeof(int32_t) * n) == 0 &&
+                    std::memcmp(P.dA.data(), dA, sizeof(int32_t) * n) == 0;
+  DeviceGuard guard(ctx);
+  if (!same) {
+    PrecondSchedule S = schedule_precond(n, dG, dA);
+    if (!ctx->host_only) {
+      HIP_TRY(ctx, hipDeviceSynchronize());
+      release(P);
+    } else {
+      P = PrecondPlan{};
+    }
+    P.dG.assign(dG, dG + n); P.dA.assign(dA, dA + n);
+    P.t_off = S.t_off; P.ws_floats = S.ws_floats; P.stats = S.stats;
+    P.njobs1 = int(S.jobs1.size()); P.njobs2 = int(S.jobs2.size());
+    if (!ctx->host_only) {
+      kfac_status st;
+      if ((st = upload_static(ctx, &P.d_jobs1, S.jobs1.data(), S.jobs1.size() * sizeof(TileJob))) != KFAC_OK) return st;
+      if ((st = upload_static(ctx, &P.d_jobs2, S.jobs2.data(), S.jobs2.size() * sizeof(TileJob))) != KFAC_OK) return st;
+    }
+    P.valid = true;
+  }
+  if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  kfac_status st = ensure_ws(ctx, P.ws_floats * sizeof(float));
+  if (st != KFAC_OK) return st;
+  std::vector<TileDesc> descs(2 * size_t(n));
+  float* wsf = static_cast<float*>(ctx->ws);
+  for (int l = 0; l < n; ++l) {
+    float* T = wsf + P.t_off[l];
+    TileDesc& D1 = descs[2 * l];       // T = Ginv . V : a(k, i) = Ginv[i][k]
+    D1 = TileDesc{};
+    D1.a = transposed_operand(Ginv[l], dG[l], dG[l]);
+    D1.b = rowmajor_operand(gradW[l], dG[l], dA[l], dA[l]);
+    D1.out = T; D1.ldo = dA[l]; D1.M = dG[l]; D1.N = dA[l];
+    D1.sym = 0; D1.mirror = MIRROR_NONE; D1.alpha = 1.f; D1.beta = 0.f;
+    TileDesc& D2 = descs[2 * l + 1];   // out = T . Ainv
+    D2 = TileDesc{};
+    D2.a = transposed_operand(T, dA[l], dG[l]);
+    D2.b = rowmajor_operand(Ainv[l], dA[l], dA[l], dA[l]);
+    D2.out = out[l]; D2.ldo = dA[l]; D2.M = dG[l]; D2.N = dA[l];
+    D2.sym = 0; D2.mirror = MIRROR_NONE; D2.alpha = 1.f; D2.beta = 0.f;
+  }
+  st = sync_table(ctx, P.tab, descs.data(), descs.size() * sizeof(TileDesc), s);
+  if (st != KFAC_OK) return st;
+  const TileDesc* d_descs = static_cast<const TileDesc*>(P.tab.dev);
+  launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_jobs1), P.njobs1, 0, s);
+  launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_jobs2), P.njobs2, 0, s);
+  HIP_TRY(ctx, hipGetLastError());
+  return KFAC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,16 @@
+// Host-callable launchers of the gfx950 kernels (implemented in the .hip files).
+#pragma once
+#include "common.h"
+
+namespace kfac {
+
+void launch_tile_any(const TileDesc* descs, const TileJob* jobs, int njobs, int xcd_order, hipStream_t s);
+void launch_tile_gemm(const TileDesc* descs, const TileJob* jobs, int njobs, int xcd_order, hipStream_t s);
+void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs, hipStream_t s);
+
+void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma, hipStream_t s);
+void launch_gj_pivot(const InvMat* mats, int mat0, int nmats, int step, float gamma, int small, hipStream_t s);
+void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s);
+void launch_gj_finish(const InvMat* mats, const void* jobs, int njobs, hipStream_t s);
+
+}  // namespace kfac

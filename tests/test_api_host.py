@@ -1,0 +1,104 @@
+"""Host-side behaviour of the C ABI that needs no GPU: exported symbols, argument validation
+(performed before any launch) and schedule construction on a host-only context."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2107_06533_amd as pk
+from synth import shapes
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def hctx():
+    if not pk.is_built():
+        import __graft_entry__
+        __graft_entry__.build()
+    c = pk.Context(-1)
+    yield c
+    c.close()
+
+
+def test_every_declared_symbol_is_exported(hctx):
+    header = open(os.path.join(ROOT, "include", "kfac.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(kfac_[a-z_A-Z0-9]+)\s*\(", header))
+    assert declared == set(pk.EXPORTS)
+    lib = ctypes.CDLL(pk.lib_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_layer_queries(hctx):
+    lib = pk.load()
+    for l in shapes.config_layers("r50")[:8] + shapes.config_layers("fc"):
+        s = pk.make_layer(l)
+        assert lib.kfac_layer_dA(ctypes.byref(s)) == l.dA
+        assert lib.kfac_layer_dG(ctypes.byref(s)) == l.dG
+        assert lib.kfac_layer_rows(ctypes.byref(s)) == l.R
+    bad = pk.make_layer(shapes.Layer(kind=1, n=1, c_in=1, h=2, w=2, c_out=1, kh=3, kw=3))   # empty output
+    assert lib.kfac_layer_dA(ctypes.byref(bad)) == 0
+
+
+def test_update_factors_validation(hctx):
+    L = shapes.linear(4, 3, 2)
+    ok = dict(layers=[L], act=[1], gout=[1], A=[1], G=[1], xi=0.5)
+    call = lambda **kw: hctx.kfac_update_factors(check=False, **{**ok, **kw})
+    assert call() == pk.KFAC_ERR_DEVICE                       # valid, but host-only: nothing launched
+    assert call(xi=1.5) == pk.KFAC_ERR_INVALID_ARG
+    assert call(xi=-0.1) == pk.KFAC_ERR_INVALID_ARG
+    assert call(xi=float("nan")) == pk.KFAC_ERR_INVALID_ARG
+    assert call(A=[None]) == pk.KFAC_ERR_INVALID_ARG
+    assert call(G=None) == pk.KFAC_ERR_INVALID_ARG
+    assert call(scale_a=float("inf")) == pk.KFAC_ERR_INVALID_ARG
+    assert call(act=None, A=None) == pk.KFAC_ERR_DEVICE       # skipping every A is fine
+    for bad in (shapes.linear(0, 3, 2), shapes.linear(4, 0, 2), shapes.replace(L, kind=2), shapes.replace(L, has_bias=3),
+                shapes.conv(1, 1, 2, 2, 1, 3), shapes.conv(1, 1, 8, 8, 1, 3, stride=0)):
+        assert call(layers=[bad]) == pk.KFAC_ERR_INVALID_ARG, bad
+        assert "layer 0" in hctx.last_error()
+    assert hctx.kfac_update_factors([], None, None, None, None, 0.5) == pk.KFAC_OK   # empty: no-op
+    lib = pk.load()
+    assert lib.kfac_update_factors(None, 0, None, None, None, None, None, 0.5, 0, 0, None) == pk.KFAC_ERR_INVALID_ARG
+
+
+def test_invert_validation(hctx):
+    call = lambda dims=(3,), F=(1,), X=(2,), gamma=0.1: hctx.kfac_invert_batch(list(dims), list(F), list(X), gamma, check=False)
+    assert call() == pk.KFAC_ERR_DEVICE
+    assert call(dims=(0,)) == pk.KFAC_ERR_INVALID_ARG
+    assert call(gamma=-1.0) == pk.KFAC_ERR_INVALID_ARG
+    assert call(gamma=float("nan")) == pk.KFAC_ERR_INVALID_ARG
+    assert call(X=(1,)) == pk.KFAC_ERR_INVALID_ARG            # aliasing
+    assert call(F=(None,)) == pk.KFAC_ERR_INVALID_ARG
+    assert hctx.kfac_invert_batch([], None, None, 0.1) == pk.KFAC_OK
+
+
+def test_precondition_validation(hctx):
+    call = lambda dG=(2,), dA=(3,), g=(1,), a=(2,), v=(3,), o=(4,): hctx.kfac_precondition(
+        list(dG), list(dA), list(g), list(a), list(v), list(o), check=False)
+    assert call() == pk.KFAC_ERR_DEVICE
+    assert call(o=(3,)) == pk.KFAC_ERR_DEVICE                 # out may alias gradW
+    assert call(o=(1,)) == pk.KFAC_ERR_INVALID_ARG            # ... but not an inverse
+    assert call(dG=(0,)) == pk.KFAC_ERR_INVALID_ARG
+    assert call(v=(None,)) == pk.KFAC_ERR_INVALID_ARG
+
+
+def test_r50_schedule(hctx):
+    ls = shapes.config_layers("r50")
+    n = len(ls)
+    assert hctx.kfac_update_factors(ls, [1] * n, [1] * n, [1] * n, [1] * n, 0.95, check=False) == pk.KFAC_ERR_DEVICE
+    st = hctx.plan_stats(0)
+    alg = shapes.flops(ls)
+    assert alg["factor_a"] + alg["factor_g"] <= st["mfma_flops"] <= 1.2 * (alg["factor_a"] + alg["factor_g"])
+    assert st["ws_bytes"] == hctx.workspace_bytes_factors(ls)
+    dims = [l.dA for l in ls] + [l.dG for l in ls]
+    assert hctx.kfac_invert_batch(dims, [1] * 2 * n, [2] * 2 * n, 0.03, check=False) == pk.KFAC_ERR_DEVICE
+    st = hctx.plan_stats(1)
+    assert alg["inverse"] * 0.95 <= st["mfma_flops"] <= 1.15 * alg["inverse"]
+    assert st["n_launches"] == 1 + 2 + 3 * 37                 # small bucket + init/finish + 37 sweeps of (pivot, panel, update)
+    assert st["ws_bytes"] == hctx.workspace_bytes_invert(dims)
+    assert hctx.kfac_precondition([l.dG for l in ls], [l.dA for l in ls], [1] * n, [2] * n, [3] * n, [4] * n, check=False) == pk.KFAC_ERR_DEVICE
+    st = hctx.plan_stats(2)
+    assert alg["precondition"] <= st["mfma_flops"] <= 1.1 * alg["precondition"]

@@ -1,0 +1,266 @@
+"""GPU parity: every call of the C ABI against the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from synth import shapes, inputs
+from gpu_util import dev, host64, rel_fro, inv_residual, TOL_FACTOR, TOL_INVERSE, TOL_PRECOND
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(kfac_lib):
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = kfac_lib.Context(0)
+    yield c
+    c.close()
+
+
+def run_factors(ctx, layers, acts, gouts, A0, G0, xi, scale_a=0.0, scale_g=0.0):
+    import torch
+    a_d = [dev(a) if a is not None else None for a in acts]
+    g_d = [dev(g) if g is not None else None for g in gouts]
+    A_d = [dev(A.astype(np.float32)) for A in A0]
+    G_d = [dev(G.astype(np.float32)) for G in G0]
+    ctx.kfac_update_factors(layers, a_d, g_d, A_d, G_d, xi, scale_a, scale_g)
+    torch.cuda.synchronize()
+    return A_d, G_d
+
+
+def check_factor(got_t, want, what):
+    got = host64(got_t)
+    assert np.array_equal(got, got.T), f"{what}: not exactly symmetric"
+    err = rel_fro(got, want)
+    assert err <= TOL_FACTOR, f"{what}: rel Frobenius {err:.3e}"
+    return err
+
+
+# ------------------------------------------------------------------------------ factors
+LINEAR_CASES = [
+    (32, 64, 32, 1),        # the small FC workload's shape
+    (1000, 300, 7, 1),      # ragged tiles, ragged k
+    (257, 129, 130, 0),     # one past a tile edge, no bias
+    (20000, 96, 200, 1),    # split reduction (R > one job)
+    (1, 5, 3, 1),           # single row
+]
+
+
+@pytest.mark.parametrize("R,cin,cout,bias", LINEAR_CASES)
+def test_linear_factors(ctx, R, cin, cout, bias):
+    rng = np.random.default_rng(R + cin)
+    layer = shapes.linear(R, cin, cout, bias)
+    a = np.maximum(rng.standard_normal((R, cin)), 0).astype(np.float32)
+    g = (1e-3 * rng.standard_normal((R, cout))).astype(np.float32)
+    A0 = np.eye(layer.dA) + 0.1 * np.ones((layer.dA, layer.dA))
+    G0 = np.eye(layer.dG)
+    A_d, G_d = run_factors(ctx, [layer], [a], [g], [A0], [G0], 0.95)
+    check_factor(A_d[0], oracle.update_factor_A(layer, a, A0.astype(np.float32), 0.95), "A")
+    check_factor(G_d[0], oracle.update_factor_G(layer, g, G0, 0.95), "G")
+    if bias:
+        assert abs(float(A_d[0][-1, -1]) - (0.95 * 1.1 + 0.05)) < 1e-6
+
+
+CONV_CASES = [
+    # n, cin, h, w, cout, kh, kw, stride, pad, bias
+    (2, 3, 5, 6, 4, 1, 1, 1, 0, 1),
+    (4, 70, 9, 9, 130, 1, 1, 1, 0, 1),      # G spans two tiles
+    (3, 16, 10, 10, 8, 1, 1, 2, 0, 1),      # strided 1x1 (projection shortcut)
+    (2, 3, 8, 8, 5, 3, 3, 1, 1, 1),
+    (2, 20, 12, 11, 6, 3, 3, 1, 1, 1),      # dA = 181: two tiles, ragged
+    (2, 16, 13, 13, 6, 3, 3, 2, 1, 0),      # strided 3x3
+    (2, 3, 23, 21, 6, 7, 7, 2, 3, 1),       # stem-like 7x7/2
+    (2, 4, 9, 8, 3, 5, 5, 1, 2, 1),         # generic window
+    (2, 4, 9, 8, 3, 2, 3, 1, 0, 1),         # rectangular window
+    (2, 4, 9, 8, 3, 1, 1, 1, 1, 1),         # padded 1x1 goes through the generic window path
+    (16, 8, 40, 40, 8, 3, 3, 1, 1, 1),      # R = 25600 > one job: split reduction with patches
+]
+
+
+@pytest.mark.parametrize("n,cin,h,w,cout,kh,kw,s,p,bias", CONV_CASES)
+def test_conv_factors(ctx, n, cin, h, w, cout, kh, kw, s, p, bias):
+    rng = np.random.default_rng(n * 1000 + cin * 10 + kh)
+    layer = shapes.Layer(kind=1, n=n, c_in=cin, h=h, w=w, c_out=cout, kh=kh, kw=kw, stride=s, pad=p, has_bias=bias)
+    a = np.maximum(rng.standard_normal(layer.act_shape), 0).astype(np.float32)
+    g = (1e-3 * rng.standard_normal(layer.gout_shape)).astype(np.float32)
+    A0, G0 = np.eye(layer.dA), np.eye(layer.dG)
+    A_d, G_d = run_factors(ctx, [layer], [a], [g], [A0], [G0], 0.9)
+    check_factor(A_d[0], oracle.update_factor_A(layer, a, A0, 0.9), "A")
+    check_factor(G_d[0], oracle.update_factor_G(layer, g, G0, 0.9), "G")
+
+
+def test_factor_options(ctx):
+    """Custom scales, xi = 0 and 1, skipping A or G."""
+    import torch
+    rng = np.random.default_rng(5)
+    layer = shapes.linear(50, 20, 10, 1)
+    a = rng.standard_normal((50, 20)).astype(np.float32)
+    g = rng.standard_normal((50, 10)).astype(np.float32)
+    A0, G0 = np.eye(21), 2 * np.eye(10)
+    A_d, G_d = run_factors(ctx, [layer], [a], [g], [A0], [G0], 0.5, scale_a=0.25, scale_g=2.0)
+    check_factor(A_d[0], oracle.update_factor_A(layer, a, A0, 0.5, scale=0.25), "A scaled")
+    check_factor(G_d[0], oracle.update_factor_G(layer, g, G0, 0.5, scale=2.0), "G scaled")
+    A_d, G_d = run_factors(ctx, [layer], [a], [g], [A0], [G0], 0.0)
+    check_factor(A_d[0], oracle.update_factor_A(layer, a, A0, 0.0), "xi=0")
+    A_d, G_d = run_factors(ctx, [layer], [a], [g], [A0], [G0], 1.0)
+    assert np.array_equal(host64(A_d[0]), A0) and np.array_equal(host64(G_d[0]), G0)
+    A_d, G_d = run_factors(ctx, [layer], [a], [None], [A0], [G0], 0.5)     # G skipped
+    assert np.array_equal(host64(G_d[0]), G0)
+    check_factor(A_d[0], oracle.update_factor_A(layer, a, A0, 0.5), "A only")
+    # xi = 0 must not read the old factor (NaN would propagate)
+    Anan = torch.full((21, 21), float("nan"), device="cuda")
+    ctx.kfac_update_factors([layer], [dev(a)], None, [Anan], None, 0.0)
+    torch.cuda.synchronize()
+    check_factor(Anan, oracle.update_factor_A(layer, a, A0, 0.0), "xi=0 over NaN")
+
+
+# ------------------------------------------------------------------------------ inverse
+def spd(d, seed, cond):
+    rng = np.random.default_rng(seed)
+    r = rng.standard_normal((max(d // 2, 1), d))
+    F = r.T @ r / r.shape[0]                      # rank-deficient PSD, like a factor with few rows
+    F *= cond / max(np.linalg.eigvalsh(F).max(), 1e-30)
+    return F
+
+
+def run_invert(ctx, Fs, gamma):
+    import torch
+    F_d = [dev(F.astype(np.float32)) for F in Fs]
+    X_d = [torch.full_like(f, float("nan")) for f in F_d]
+    info = torch.full((len(Fs),), -7, dtype=torch.int32, device="cuda")
+    ctx.kfac_invert_batch([F.shape[0] for F in Fs], F_d, X_d, gamma, info)
+    torch.cuda.synchronize()
+    return F_d, X_d, info.cpu().numpy()
+
+
+def test_invert_batch_mixed_sizes(ctx):
+    dims = [1, 2, 3, 17, 64, 65, 127, 128, 129, 148, 256, 257, 300, 513, 640, 1025]
+    gamma = 0.03
+    Fs = [spd(d, d, 5.0) + 0.5 * np.eye(d) for d in dims]
+    F_d, X_d, info = run_invert(ctx, Fs, gamma)
+    assert np.all(info == 0)
+    for d, F, Fd, Xd in zip(dims, Fs, F_d, X_d):
+        F32 = host64(Fd)                       # the fp32 bytes both sides see
+        X = host64(Xd)
+        assert np.array_equal(X, X.T), f"d={d}: inverse not exactly symmetric"
+        res = inv_residual(F32, gamma, X)
+        assert res <= TOL_INVERSE, f"d={d}: residual {res:.3e}"
+        want = oracle.damped_inverse(F32, gamma)
+        assert rel_fro(X, want) <= 1e-4, f"d={d}: rel error vs oracle {rel_fro(X, want):.3e}"
+        np.testing.assert_array_equal(host64(Fd), F.astype(np.float32).astype(np.float64))   # F untouched
+
+
+def test_invert_identity_and_diagonal(ctx):
+    Fs = [np.eye(200), np.diag(np.arange(1.0, 131.0))]
+    _, X_d, info = run_invert(ctx, Fs, 0.03)
+    assert np.all(info == 0)
+    np.testing.assert_allclose(host64(X_d[0]), np.eye(200) / 1.03, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(host64(X_d[1]), np.diag(1 / (np.arange(1.0, 131.0) + 0.03)), rtol=1e-6, atol=1e-9)
+
+
+def test_invert_uses_lower_triangle_only(ctx):
+    F = spd(150, 3, 4.0) + np.eye(150)
+    Fu = F.copy()
+    Fu[np.triu_indices(150, 1)] = 1e6           # garbage above the diagonal must not matter
+    _, X_d, _ = run_invert(ctx, [F, Fu], 0.03)
+    assert np.array_equal(host64(X_d[0]), host64(X_d[1]))
+
+
+def test_invert_not_spd_info(ctx):
+    good = spd(300, 1, 3.0) + np.eye(300)
+    bad_small = np.diag([1.0, 2.0, -1.0, 3.0])
+    bad_large = good.copy()
+    bad_large[200, 200] = -50.0                  # leading minor 201 fails
+    _, X_d, info = run_invert(ctx, [good, bad_small, bad_large, good[:100, :100]], 0.5)
+    assert info[0] == 0 and info[3] == 0
+    assert info[1] == 3
+    assert info[2] == 201
+    st, host = ctx.kfac_check_info(4, dev(info.astype(np.int32)))
+    assert st == 2 and host == [0, 3, 201, 0]
+    assert inv_residual(good, 0.5, host64(X_d[0])) <= TOL_INVERSE        # the others are still valid
+
+
+# ------------------------------------------------------------------------------ precondition
+@pytest.mark.parametrize("dG,dA", [(32, 65), (1, 1), (10, 129), (130, 300), (257, 64), (64, 577)])
+def test_precondition(ctx, dG, dA):
+    import torch
+    rng = np.random.default_rng(dG * 1000 + dA)
+    XG = rng.standard_normal((dG, dG)); XG = XG @ XG.T / dG + np.eye(dG)
+    XA = rng.standard_normal((dA, dA)); XA = XA @ XA.T / dA + np.eye(dA)
+    V = (1e-2 * rng.standard_normal((dG, dA)))
+    XG_d, XA_d, V_d = dev(XG.astype(np.float32)), dev(XA.astype(np.float32)), dev(V.astype(np.float32))
+    out = torch.full((dG, dA), float("nan"), device="cuda")
+    ctx.kfac_precondition([dG], [dA], [XG_d], [XA_d], [V_d], [out])
+    torch.cuda.synchronize()
+    want = oracle.precondition(host64(XG_d), host64(XA_d), host64(V_d))
+    assert rel_fro(host64(out), want) <= 1e-5
+    # in place
+    ctx.kfac_precondition([dG], [dA], [XG_d], [XA_d], [V_d], [V_d])
+    torch.cuda.synchronize()
+    assert np.array_equal(host64(V_d), host64(out))
+
+
+def test_precondition_nonsymmetric_inverse_is_used_as_stored(ctx):
+    import torch
+    rng = np.random.default_rng(9)
+    XG, XA, V = rng.standard_normal((40, 40)), rng.standard_normal((70, 70)), rng.standard_normal((40, 70))
+    out = torch.empty((40, 70), device="cuda")
+    t = [dev(x.astype(np.float32)) for x in (XG, XA, V)]
+    ctx.kfac_precondition([40], [70], [t[0]], [t[1]], [t[2]], [out])
+    torch.cuda.synchronize()
+    assert rel_fro(host64(out), oracle.precondition(host64(t[0]), host64(t[1]), host64(t[2]))) <= 1e-5
+
+
+# ------------------------------------------------------------------------------ whole steps
+def run_config_steps(ctx, name, steps, batch=None):
+    import torch
+    hp = shapes.config_hparams(name)
+    layers = shapes.config_layers(name, batch)
+    A_ref = [np.eye(l.dA) for l in layers]
+    G_ref = [np.eye(l.dG) for l in layers]
+    A_d = [dev(np.eye(l.dA, dtype=np.float32)) for l in layers]
+    G_d = [dev(np.eye(l.dG, dtype=np.float32)) for l in layers]
+    XA_d = [torch.empty_like(t) for t in A_d]
+    XG_d = [torch.empty_like(t) for t in G_d]
+    n = len(layers)
+    info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
+    worst = dict(factor=0.0, inverse=0.0, precond=0.0)
+    for step in range(steps):
+        ins = [inputs.layer_inputs(l, hp["cid"], step, i, hp["relu"]) for i, l in enumerate(layers)]
+        acts, gouts, grads = zip(*ins)
+        a_d, g_d, v_d = [dev(x) for x in acts], [dev(x) for x in gouts], [dev(x) for x in grads]
+        P_d = [torch.empty_like(v) for v in v_d]
+        ctx.kfac_update_factors(layers, a_d, g_d, A_d, G_d, hp["xi"])
+        ctx.kfac_invert_batch([l.dA for l in layers] + [l.dG for l in layers], A_d + G_d, XA_d + XG_d, hp["gamma"], info)
+        ctx.kfac_precondition([l.dG for l in layers], [l.dA for l in layers], XG_d, XA_d, v_d, P_d)
+        torch.cuda.synchronize()
+        assert int(info.abs().sum()) == 0
+        A_ref, G_ref, XA_ref, XG_ref, P_ref = oracle.kfac_step(layers, acts, gouts, grads, A_ref, G_ref, hp["xi"], hp["gamma"])
+        for i in range(n):
+            worst["factor"] = max(worst["factor"], check_factor(A_d[i], A_ref[i], f"step {step} A[{i}]"),
+                                  check_factor(G_d[i], G_ref[i], f"step {step} G[{i}]"))
+            for X_t, F_ref in ((XA_d[i], A_ref[i]), (XG_d[i], G_ref[i])):
+                X = host64(X_t)
+                assert np.array_equal(X, X.T)
+                res = inv_residual(F_ref, hp["gamma"], X)
+                assert res <= TOL_INVERSE, f"step {step} layer {i}: inverse residual {res:.3e}"
+                worst["inverse"] = max(worst["inverse"], res)
+            e = rel_fro(host64(P_d[i]), P_ref[i])
+            assert e <= TOL_PRECOND, f"step {step} layer {i}: preconditioned gradient rel err {e:.3e}"
+            worst["precond"] = max(worst["precond"], e)
+    return worst
+
+
+def test_fc_config_three_steps(ctx):
+    print(run_config_steps(ctx, "fc", 3))
+
+
+def test_cnn_config(ctx):
+    print(run_config_steps(ctx, "cnn", 2))
+
+
+def test_empty_calls_are_noops(ctx):
+    assert ctx.kfac_update_factors([], None, None, None, None, 0.95) == 0
+    assert ctx.kfac_invert_batch([], None, None, 0.03) == 0
+    assert ctx.kfac_precondition([], [], None, None, None, None) == 0
