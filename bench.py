@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the K-FAC hot path on one MI355X.
+
+One "step" = kfac_update_factors + kfac_invert_batch + kfac_precondition over the whole
+ResNet-50-shaped layer set (54 layers, 108 factor matrices, batch 32, 224x224), all inputs
+resident in HBM.  Prints ONE JSON line with the step time, the algorithmic TFLOP/s, the
+roofline position of the dominant kernel (measured with HIP events inside the library on the
+stream the kernels run on) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CUs x 256 flop/clk x 2.4 GHz
+WORKLOAD_NAMES = {
+    "fc": "fc: single fully-connected layer 64->32, 32 rows",
+    "cnn": "cnn: 4 conv3x3 + FC, batch 32, 32x32 input",
+    "r50": "r50: ResNet-50-shaped layer set, batch 32, 224x224 input (54 layers, 108 factor matrices)",
+    "r152": "r152: ResNet-152-shaped layer set, batch 32, 224x224 input (156 layers, 312 factor matrices)",
+    "bertl": "bertl: BERT-large linear layers, 24 blocks, 4096 tokens (144 layers, 288 factor matrices)",
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="r50", choices=list(WORKLOAD_NAMES))
+    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
+    ap.add_argument("--no-breakdown", action="store_true", help="skip the extra per-kernel timing pass")
+    return ap.parse_args()
+
+
+def make_inputs(layers, hp):
+    from synth import inputs
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        return list(ex.map(lambda il: inputs.layer_inputs(il[1], hp["cid"], 0, il[0], hp["relu"]), enumerate(layers)))
+
+
+def cpu_baseline(layers, hp, budget_s, flops_total):
+    """Time the fp64 oracle on whole layers (largest shape classes first) until the budget is
+    spent; scale to a full step by algorithmic flops."""
+    import numpy as np
+    import oracle
+    from synth import inputs, shapes
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    classes = {}
+    for i, l in enumerate(layers):
+        key = (l.kind, l.dA, l.dG, l.R, l.kh, l.stride)
+        classes.setdefault(key, []).append(i)
+    order = sorted(classes.values(), key=lambda idx: -shapes.flops([layers[idx[0]]])["total"])
+    spent, done_flops, used = 0.0, 0, []
+    for idx in order:
+        i = idx[0]
+        l = layers[i]
+        a, g, v = inputs.layer_inputs(l, hp["cid"], 0, i, hp["relu"])
+        t0 = time.perf_counter()
+        oracle.kfac_step([l], [a], [g], [v], [np.eye(l.dA)], [np.eye(l.dG)], hp["xi"], hp["gamma"])
+        spent += time.perf_counter() - t0
+        done_flops += shapes.flops([l])["total"]
+        used.append(l.name or str(i))
+        if spent >= budget_s:
+            break
+    est_ms = spent * 1e3 * flops_total / done_flops
+    return {
+        "value": round(est_ms, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
+        "sample": (f"fp64 NumPy oracle, whole step on {len(used)} of {len(layers)} layers (largest shape classes first: "
+                   f"{', '.join(used)}), {spent:.1f} s measured, {100.0 * done_flops / flops_total:.1f}% of the step's "
+                   f"algorithmic flops, scaled to the full step by flops"),
+        "measured_s": round(spent, 2),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the hot path is one worker's share); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2107_06533_amd as pk
+    from synth import shapes
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    pk.load()                                      # fails loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+    hp = shapes.config_hparams(args.config)
+    layers = shapes.config_layers(args.config)
+    n = len(layers)
+    fl = shapes.flops(layers)
+
+    t0 = time.perf_counter()
+    ins = make_inputs(layers, hp)
+    up = lambda x: torch.from_numpy(x).cuda()
+    a_d = [up(x[0]) for x in ins]
+    g_d = [up(x[1]) for x in ins]
+    v_d = [up(x[2]) for x in ins]
+    del ins
+    A_d = [torch.eye(l.dA, device="cuda") for l in layers]
+    G_d = [torch.eye(l.dG, device="cuda") for l in layers]
+    XA_d = [torch.empty_like(t) for t in A_d]
+    XG_d = [torch.empty_like(t) for t in G_d]
+    P_d = [torch.empty_like(v) for v in v_d]
+    info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
+    dims = [l.dA for l in layers] + [l.dG for l in layers]
+    dG, dA = [l.dG for l in layers], [l.dA for l in layers]
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t0
+
+    ctx = pk.Context(0)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        ctx.kfac_update_factors(layers, a_d, g_d, A_d, G_d, hp["xi"], stream=stream)
+        ctx.kfac_invert_batch(dims, A_d + G_d, XA_d + XG_d, hp["gamma"], info, stream=stream)
+        ctx.kfac_precondition(dG, dA, XG_d, XA_d, v_d, P_d, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: K steps; the dominant kernel (grouped factor build) is bracketed by HIP events
+    ctx.timing_enable(["factor_tiles"])
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    call_ms = [0.0, 0.0, 0.0]
+    evs = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e[0].record(stream)
+        ctx.kfac_update_factors(layers, a_d, g_d, A_d, G_d, hp["xi"], stream=stream)
+        e[1].record(stream)
+        ctx.kfac_invert_batch(dims, A_d + G_d, XA_d + XG_d, hp["gamma"], info, stream=stream)
+        e[2].record(stream)
+        ctx.kfac_precondition(dG, dA, XG_d, XA_d, v_d, P_d, stream=stream)
+        e[3].record(stream)
+        evs.append(e)
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    ms_per_step = wall_s * 1e3 / args.steps
+    for e in evs:
+        for k in range(3):
+            call_ms[k] += e[k].elapsed_time(e[k + 1]) / args.steps
+    dom_ms, dom_n = ctx.timing_read("factor_tiles")
+    ctx.timing_enable([])
+    assert int(info.abs().sum()) == 0, "a factor was reported not positive definite"
+    assert dom_n == args.steps
+
+    # ---- per-kernel breakdown (extra, untimed pass with every kernel class bracketed)
+    breakdown = None
+    if not args.no_breakdown:
+        ctx.timing_enable(pk.KERNEL_CLASSES)
+        reps = 3
+        for _ in range(reps):
+            step()
+        torch.cuda.synchronize()
+        breakdown = {}
+        for k in pk.KERNEL_CLASSES:
+            ms, cnt = ctx.timing_read(k)
+            breakdown[k] = {"ms_per_step": round(ms / reps, 4), "launches_per_step": cnt // reps}
+        ctx.timing_enable([])
+
+    factor_flops = fl["factor_a"] + fl["factor_g"]
+    dom_avg_ms = dom_ms / dom_n
+    achieved = factor_flops / (dom_avg_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.config, {}).get("factor_tiles_bytes_per_launch")
+        except Exception:
+            traffic = None
+    out = {
+        "metric": "kfac_step_ms (factors + inverses + precondition)",
+        "value": round(ms_per_step, 4),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.config], "layers": n, "matrices": 2 * n,
+                   "xi": hp["xi"], "gamma": hp["gamma"], "setup_s": round(setup_s, 1)},
+        "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 2),
+        "frac_of_fp32_mfma_peak": round(fl["total"] / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+        "calls": {
+            "update_factors": {"ms": round(call_ms[0], 4), "tflops": round(factor_flops / call_ms[0] / 1e9, 2),
+                               "frac_peak": round(factor_flops / call_ms[0] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)},
+            "invert_batch": {"ms": round(call_ms[1], 4), "tflops": round(fl["inverse"] / call_ms[1] / 1e9, 2),
+                             "frac_peak": round(fl["inverse"] / call_ms[1] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)},
+            "precondition": {"ms": round(call_ms[2], 4), "tflops": round(fl["precondition"] / call_ms[2] / 1e9, 2),
+                             "frac_peak": round(fl["precondition"] / call_ms[2] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)},
+        },
+        "algorithmic_flops": fl,
+        "roofline": {
+            "kernel": "tile_any_kernel (grouped factor build, one launch per step)",
+            "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": traffic,
+            "avg_launch_ms": round(dom_avg_ms, 4), "flops_per_launch": factor_flops,
+        },
+    }
+    if breakdown is not None:
+        out["kernel_breakdown"] = breakdown
+    if args.cpu_budget > 0:
+        out["cpu_baseline"] = cpu_baseline(layers, hp, args.cpu_budget, fl["total"])
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -145,6 +145,28 @@ typedef struct {
 void kfac_get_plan_stats(const kfac_ctx* ctx, int which /*0 factors, 1 invert, 2 precondition*/,
                          kfac_plan_stats* out);
 
+/*
+ * Optional per-kernel timing for benchmarks.  While bit k of `class_mask` is set, every launch of
+ * kernel class k is bracketed by a pair of HIP events on the call's stream.  kfac_timing_read
+ * waits for the recorded events, returns the summed duration and launch count of one class and,
+ * if `reset` is non-zero, forgets that class's records.  Timing is off by default (mask 0).
+ */
+enum {
+  KFAC_K_FACTOR_TILES = 0,  /* grouped factor build (patch expansion + MFMA + running average) */
+  KFAC_K_FACTOR_REDUCE = 1, /* reduction of tiles whose row range was split                   */
+  KFAC_K_INV_SMALL = 2,     /* whole-matrix in-register inverse, d <= 128                      */
+  KFAC_K_INV_INIT = 3,
+  KFAC_K_INV_PIVOT = 4,
+  KFAC_K_INV_PANEL = 5,
+  KFAC_K_INV_UPDATE = 6,    /* rank-128 MFMA update of the lower triangle                      */
+  KFAC_K_INV_FINISH = 7,
+  KFAC_K_PRECOND_LEFT = 8,  /* Ginv . V                                                        */
+  KFAC_K_PRECOND_RIGHT = 9, /* (Ginv . V) . Ainv                                               */
+  KFAC_K_COUNT = 10
+};
+void kfac_timing_enable(kfac_ctx* ctx, uint32_t class_mask);
+kfac_status kfac_timing_read(kfac_ctx* ctx, int kclass, double* total_ms, int64_t* n_launches, int reset);
+
 #ifdef __cplusplus
 }
 #endif

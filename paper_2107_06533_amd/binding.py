@@ -15,8 +15,11 @@ EXPORTS = [
     "kfac_layer_dA", "kfac_layer_dG", "kfac_layer_rows",
     "kfac_workspace_bytes_factors", "kfac_workspace_bytes_invert", "kfac_workspace_bytes_precondition",
     "kfac_update_factors", "kfac_invert_batch", "kfac_check_info", "kfac_precondition",
-    "kfac_get_plan_stats",
+    "kfac_get_plan_stats", "kfac_timing_enable", "kfac_timing_read",
 ]
+
+KERNEL_CLASSES = ["factor_tiles", "factor_reduce", "inv_small", "inv_init", "inv_pivot", "inv_panel",
+                  "inv_update", "inv_finish", "precond_left", "precond_right"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -85,6 +88,10 @@ def load():
     lib.kfac_precondition.restype = C.c_int
     lib.kfac_get_plan_stats.argtypes = [vp, C.c_int, C.POINTER(plan_stats)]
     lib.kfac_get_plan_stats.restype = None
+    lib.kfac_timing_enable.argtypes = [vp, C.c_uint32]
+    lib.kfac_timing_enable.restype = None
+    lib.kfac_timing_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+    lib.kfac_timing_read.restype = C.c_int
     _LIB = lib
     return lib
 
@@ -201,6 +208,19 @@ class Context:
 
     def workspace_bytes_precondition(self, dG, dA) -> int:
         return int(self.lib.kfac_workspace_bytes_precondition(self.h, len(dG), _i32_array(dG), _i32_array(dA)))
+
+    def timing_enable(self, classes=()):
+        """classes: iterable of names from KERNEL_CLASSES (empty = timing off)."""
+        mask = 0
+        for c in classes:
+            mask |= 1 << KERNEL_CLASSES.index(c)
+        self.lib.kfac_timing_enable(self.h, mask)
+
+    def timing_read(self, kclass: str, reset: bool = True):
+        """(total milliseconds, launches) of one kernel class since the last reset."""
+        ms, n = C.c_double(), C.c_int64()
+        self._check(self.lib.kfac_timing_read(self.h, KERNEL_CLASSES.index(kclass), C.byref(ms), C.byref(n), int(reset)))
+        return ms.value, n.value
 
     def plan_stats(self, which: int) -> dict:
         s = plan_stats()

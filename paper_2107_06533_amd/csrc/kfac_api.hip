@@ -77,7 +77,14 @@ struct PrecondPlan {
 
 }  // namespace
 
+struct TimingRec {
+  hipEvent_t a, b;
+  int kclass;
+};
+
 struct kfac_ctx {
+  uint32_t timing_mask = 0;
+  std::vector<TimingRec> timing;
   int device = -1;
   bool host_only = true;
   std::string err;
@@ -97,6 +104,26 @@ kfac_status fail(kfac_ctx* ctx, kfac_status st, const std::string& msg) {
   if (ctx) ctx->err = msg; else g_noctx_err = msg;
   return st;
 }
+
+// Brackets the launches issued during its lifetime with a pair of events (when the class is enabled).
+struct ScopedTiming {
+  kfac_ctx* c;
+  hipStream_t s;
+  TimingRec r{};
+  bool on = false;
+  ScopedTiming(kfac_ctx* ctx, int kclass, hipStream_t stream) : c(ctx), s(stream) {
+    if (!(ctx->timing_mask & (1u << kclass))) return;
+    if (hipEventCreate(&r.a) != hipSuccess) return;
+    if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+    r.kclass = kclass;
+    on = hipEventRecord(r.a, s) == hipSuccess;
+  }
+  ~ScopedTiming() {
+    if (!on) return;
+    (void)hipEventRecord(r.b, s);
+    c->timing.push_back(r);
+  }
+};
 
 #define HIP_TRY(ctx, expr)                                                                   \
   do {                                                                                       \
@@ -487,6 +514,7 @@ void kfac_destroy(kfac_ctx* ctx) {
     (void)hipDeviceSynchronize();
     release(ctx->fp); release(ctx->ip); release(ctx->pp);
     free_dev(ctx->ws);
+    for (const TimingRec& r : ctx->timing) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   }
   delete ctx;
 }
@@ -526,6 +554,33 @@ void kfac_get_plan_stats(const kfac_ctx* ctx, int which, kfac_plan_stats* out) {
   if (which == 0) *out = ctx->fp.stats;
   else if (which == 1) *out = ctx->ip.stats;
   else if (which == 2) *out = ctx->pp.stats;
+}
+
+void kfac_timing_enable(kfac_ctx* ctx, uint32_t class_mask) {
+  if (ctx) ctx->timing_mask = class_mask;
+}
+
+kfac_status kfac_timing_read(kfac_ctx* ctx, int kclass, double* total_ms, int64_t* n_launches, int reset) {
+  if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_timing_read: ctx is NULL");
+  if (kclass < 0 || kclass >= KFAC_K_COUNT) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_timing_read: unknown kernel class");
+  double sum = 0.0;
+  int64_t cnt = 0;
+  DeviceGuard guard(ctx);
+  std::vector<TimingRec> keep;
+  for (const TimingRec& r : ctx->timing) {
+    if (r.kclass != kclass) { keep.push_back(r); continue; }
+    HIP_TRY(ctx, hipEventSynchronize(r.b));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, r.a, r.b));
+    sum += ms;
+    ++cnt;
+    if (reset) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    else keep.push_back(r);
+  }
+  ctx->timing.swap(keep);
+  if (total_ms) *total_ms = sum;
+  if (n_launches) *n_launches = cnt;
+  return KFAC_OK;
 }
 
 // ----------------------------------------------------------------------------------- factors
@@ -605,8 +660,14 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
   st = sync_table(ctx, P.tab, P.descs.data(), P.descs.size() * sizeof(TileDesc), s);
   if (st != KFAC_OK) return st;
   const TileDesc* d_descs = static_cast<const TileDesc*>(P.tab.dev);
-  launch_tile_any(d_descs, static_cast<const TileJob*>(P.d_jobs), P.njobs, 0, s);
-  launch_tile_reduce(d_descs, static_cast<const ReduceJob*>(P.d_rjobs), P.nrjobs, s);
+  {
+    ScopedTiming tm(ctx, KFAC_K_FACTOR_TILES, s);
+    launch_tile_any(d_descs, static_cast<const TileJob*>(P.d_jobs), P.njobs, 0, s);
+  }
+  if (P.nrjobs) {
+    ScopedTiming tm(ctx, KFAC_K_FACTOR_REDUCE, s);
+    launch_tile_reduce(d_descs, static_cast<const ReduceJob*>(P.d_rjobs), P.nrjobs, s);
+  }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
 }
@@ -690,16 +751,32 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   const InvMat* d_mats = static_cast<const InvMat*>(P.tab.dev);
   const TileDesc* d_descs = reinterpret_cast<const TileDesc*>(static_cast<const unsigned char*>(P.tab.dev) + mats_bytes);
 
-  launch_gj_pivot(d_mats, P.n_large, P.n_small, 0, gamma, 1, s);
+  if (P.n_small) {
+    ScopedTiming tm(ctx, KFAC_K_INV_SMALL, s);
+    launch_gj_pivot(d_mats, P.n_large, P.n_small, 0, gamma, 1, s);
+  }
   if (P.n_large) {
-    launch_gj_init(d_mats, P.d_init, P.n_init, gamma, s);
-    for (int step = 0; step < P.nsteps; ++step) {
-      launch_gj_pivot(d_mats, 0, P.active[step], step, gamma, 0, s);
-      launch_gj_panel(d_mats, static_cast<const MatJobH*>(P.d_panel) + P.panel_off[step],
-                      P.panel_off[step + 1] - P.panel_off[step], step, s);
-      launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_upd) + P.upd_off[step],
-                       P.upd_off[step + 1] - P.upd_off[step], 0, s);
+    {
+      ScopedTiming tm(ctx, KFAC_K_INV_INIT, s);
+      launch_gj_init(d_mats, P.d_init, P.n_init, gamma, s);
     }
+    for (int step = 0; step < P.nsteps; ++step) {
+      {
+        ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, s);
+        launch_gj_pivot(d_mats, 0, P.active[step], step, gamma, 0, s);
+      }
+      {
+        ScopedTiming tm(ctx, KFAC_K_INV_PANEL, s);
+        launch_gj_panel(d_mats, static_cast<const MatJobH*>(P.d_panel) + P.panel_off[step],
+                        P.panel_off[step + 1] - P.panel_off[step], step, s);
+      }
+      {
+        ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, s);
+        launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_upd) + P.upd_off[step],
+                         P.upd_off[step + 1] - P.upd_off[step], 0, s);
+      }
+    }
+    ScopedTiming tm(ctx, KFAC_K_INV_FINISH, s);
     launch_gj_finish(d_mats, P.d_finish, P.n_finish, s);
   }
   HIP_TRY(ctx, hipGetLastError());
@@ -788,8 +865,14 @@ kfac_status kfac_precondition(kfac_ctx* ctx, int n, const int32_t* dG, const int
   st = sync_table(ctx, P.tab, descs.data(), descs.size() * sizeof(TileDesc), s);
   if (st != KFAC_OK) return st;
   const TileDesc* d_descs = static_cast<const TileDesc*>(P.tab.dev);
-  launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_jobs1), P.njobs1, 0, s);
-  launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_jobs2), P.njobs2, 0, s);
+  {
+    ScopedTiming tm(ctx, KFAC_K_PRECOND_LEFT, s);
+    launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_jobs1), P.njobs1, 0, s);
+  }
+  {
+    ScopedTiming tm(ctx, KFAC_K_PRECOND_RIGHT, s);
+    launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_jobs2), P.njobs2, 0, s);
+  }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
 }
