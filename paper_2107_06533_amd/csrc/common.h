@@ -37,7 +37,7 @@ constexpr int KC = 32;    // contraction depth staged in LDS per step
 constexpr int NT = 256;   // threads per workgroup (4 wavefronts, 2x2, 64x64 outputs each)
 constexpr int PITCH = 129;              // LDS row pitch in floats (odd: conflict-free column writes)
 constexpr int PANEL = KC * PITCH;       // floats of one staged operand panel
-constexpr int ACC_FLUSH = 64;           // k-tiles between flushes of the MFMA accumulator (2048 rows)
+constexpr int MAX_JOB_ROWS = 8192;       // longest run one job accumulates in its fp32 accumulator
 
 // ---- a GEMM operand seen as a [K x M] matrix, k = contraction index ------------------------
 enum : int32_t {
@@ -55,6 +55,7 @@ struct Operand {
   int32_t M;        // free extent, including the ones column when bias = 1
   int32_t bias;     // 1: column M-1 is an implicit column of ones
   int32_t ld;       // OP_KMAJOR: row pitch in elements
+  uint32_t bytes;   // size of the tensor behind ptr (buffer-load range check); < 2 GiB
   // convolution view: k = (n*OH + oy)*OW + ox,  m = (c*KH + i)*KW + j
   int32_t C, H, W, OH, OW, stride, pad, KH, KW;
   FastDiv dOW, dOHW;

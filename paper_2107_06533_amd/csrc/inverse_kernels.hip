@@ -152,6 +152,8 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
     for (int b = 0; b < 2; ++b)
       if (wm * 64 + a * 32 < kb && i0 + wn * 64 + b * 32 < d) mask |= 1u << (a * 2 + b);
 
+  const unsigned pat = cover_pattern(mask);
+  mask = pat;   // blocks the pattern adds hold exact zeros (zero-padded operands)
   Acc4 acc;
   acc_zero(acc);
   for (int kk0 = 0; kk0 < NB; kk0 += KC) {
@@ -185,10 +187,13 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < 16; ++u) Mx.Zt[(size_t)(kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[(kp + 2 * u) * PITCH + ml];
-    if (mask == 0xFu)
-      mma_ktile<false>(Qs, Zs, acc, wm, wn, lane, mask);
-    else if (mask)
-      mma_ktile<true>(Qs, Zs, acc, wm, wn, lane, mask);
+    switch (pat) {
+      case PAT_FULL: mma_ktile<PAT_FULL>(Qs, Zs, acc, wm, wn, lane); break;
+      case PAT_ROW1: mma_ktile<PAT_ROW1>(Qs, Zs, acc, wm, wn, lane); break;
+      case PAT_COL1: mma_ktile<PAT_COL1>(Qs, Zs, acc, wm, wn, lane); break;
+      case PAT_ONE: mma_ktile<PAT_ONE>(Qs, Zs, acc, wm, wn, lane); break;
+      default: break;
+    }
   }
 
   // acc(m, i) = W[i][m]: new panel entry for matrix row/col i0+i and pivot column k0+m

@@ -90,7 +90,7 @@ struct kfac_ctx {
   std::string err;
   void* ws = nullptr;
   size_t ws_cap = 0;
-  int kjob = 8192;                   // longest contraction run of one factor tile job (rows)
+  int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
   FactorPlan fp;
   InvertPlan ip;
   PrecondPlan pp;
@@ -208,12 +208,15 @@ bool layer_valid(const kfac_layer& L, std::string* why) {
   if (L.kind != 0 && L.kind != 1) return bad("layer.kind must be 0 (linear) or 1 (conv2d)");
   if (L.has_bias != 0 && L.has_bias != 1) return bad("layer.has_bias must be 0 or 1");
   if (L.c_in < 1 || L.c_out < 1) return bad("layer.c_in and layer.c_out must be positive");
+  const int64_t max_elems = (int64_t(1) << 28);   // operands are addressed with 32-bit byte offsets, at most 1 GiB each
   if (L.kind == 0) {
     if (L.rows < 1) return bad("linear layer needs rows >= 1");
+    if (int64_t(L.rows) * L.c_in > max_elems || int64_t(L.rows) * L.c_out > max_elems)
+      return bad("linear layer tensor exceeds 1 GiB");
     return true;
   }
   if (L.n < 1 || L.h < 1 || L.w < 1) return bad("conv layer needs n, h, w >= 1");
-  if (L.kh < 1 || L.kw < 1 || L.kh > 127 || L.kw > 127) return bad("conv kernel size must be in 1..127");
+  if (L.kh < 1 || L.kw < 1 || int64_t(L.kh) * L.kw > 63) return bad("conv window must have 1..63 taps");
   if (L.stride < 1) return bad("conv stride must be >= 1");
   if (L.pad < 0 || L.pad > 127) return bad("conv pad must be in 0..127");
   if (L.h + 2 * L.pad < L.kh || L.w + 2 * L.pad < L.kw) return bad("conv output is empty");
@@ -222,6 +225,8 @@ bool layer_valid(const kfac_layer& L, std::string* why) {
   if (int64_t(L.n) * oh * ow > lim) return bad("conv rows n*oh*ow exceed 2^31-1");
   if (int64_t(L.c_in) * L.h * L.w > lim || int64_t(L.c_out) * oh * ow > lim) return bad("one sample exceeds 2^31-1 elements");
   if (int64_t(L.c_in) * L.kh * L.kw + 1 > (1 << 20)) return bad("factor dimension exceeds 2^20");
+  if (int64_t(L.n) * L.c_in * L.h * L.w > max_elems || int64_t(L.n) * L.c_out * oh * ow > max_elems)
+    return bad("conv layer tensor exceeds 1 GiB");
   return true;
 }
 
@@ -238,8 +243,10 @@ Operand act_operand(const kfac_layer& L) {
   if (L.kind == 0) {
     o.type = OP_KMAJOR;
     o.ld = L.c_in;
+    o.bytes = uint32_t(int64_t(L.rows) * L.c_in * 4);
     return o;
   }
+  o.bytes = uint32_t(int64_t(L.n) * L.c_in * L.h * L.w * 4);
   if (L.kh == 1 && L.kw == 1 && L.pad == 0) o.type = OP_CONV11;
   else if (L.kh == 3 && L.kw == 3) o.type = OP_CONV33;
   else if (L.kh == 7 && L.kw == 7) o.type = OP_CONV77;
@@ -259,8 +266,10 @@ Operand gout_operand(const kfac_layer& L) {
   if (L.kind == 0) {
     o.type = OP_KMAJOR;
     o.ld = L.c_out;
+    o.bytes = uint32_t(int64_t(L.rows) * L.c_out * 4);
     return o;
   }
+  o.bytes = uint32_t(o.K * int64_t(L.c_out) * 4);
   o.type = OP_CONV11;   // [n, c_out, oh, ow] read through a 1x1 window: k = (n, oy, ox), m = channel
   o.C = L.c_out; o.H = conv_oh(L); o.W = conv_ow(L); o.OH = o.H; o.OW = o.W;
   o.stride = 1; o.pad = 0; o.KH = 1; o.KW = 1;
@@ -272,12 +281,14 @@ Operand gout_operand(const kfac_layer& L) {
 Operand rowmajor_operand(const float* p, int K, int M, int ld) {   // element (k, m) at p[k*ld + m]
   Operand o{};
   o.ptr = p; o.type = OP_KMAJOR; o.K = K; o.M = M; o.bias = 0; o.ld = ld;
+  o.bytes = uint32_t(int64_t(K) * ld * 4);
   return o;
 }
 
 Operand transposed_operand(const float* p, int K, int M) {   // element (k, m) at p[m*K + k]
   Operand o{};
   o.ptr = p; o.type = OP_CONV11; o.K = K; o.M = M; o.bias = 0;
+  o.bytes = uint32_t(int64_t(K) * M * 4);
   o.C = M; o.H = 1; o.W = K; o.OH = 1; o.OW = K; o.stride = 1; o.pad = 0; o.KH = 1; o.KW = 1;
   o.dOW = make_fastdiv(uint32_t(K));
   o.dOHW = make_fastdiv(uint32_t(K));
@@ -493,7 +504,7 @@ kfac_status kfac_create(kfac_ctx** out, int device) {
   c->host_only = device < 0;
   if (const char* e = std::getenv("KFAC_KJOB")) {
     const int v = std::atoi(e);
-    if (v >= KC) c->kjob = v;
+    if (v >= KC) c->kjob = std::min(v, MAX_JOB_ROWS);
   }
   if (!c->host_only) {
     int count = 0;
@@ -681,7 +692,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   if (!dims || !F || !X) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: dims, F or X is NULL");
   if (!(gamma >= 0.f) || std::isinf(gamma)) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: gamma must be finite and >= 0");
   for (int i = 0; i < n; ++i) {
-    if (dims[i] < 1 || dims[i] > (1 << 20))
+    if (dims[i] < 1 || dims[i] > 16384)   // sweep panels are addressed with 32-bit byte offsets (1 GiB)
       return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: dims[" + std::to_string(i) + "] out of range");
     if (!F[i] || !X[i]) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: NULL matrix pointer at " + std::to_string(i));
     if (F[i] == X[i]) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: X must not alias F at " + std::to_string(i));
@@ -811,7 +822,7 @@ kfac_status kfac_precondition(kfac_ctx* ctx, int n, const int32_t* dG, const int
     return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition: NULL array argument");
   for (int l = 0; l < n; ++l) {
     if (dG[l] < 1 || dA[l] < 1 || dG[l] > (1 << 20) || dA[l] > (1 << 20) ||
-        int64_t(dG[l]) * std::max(dG[l], dA[l]) > (int64_t(1) << 31) - 1)
+        int64_t(std::max(dG[l], dA[l])) * std::max(dG[l], dA[l]) > (int64_t(1) << 28))
       return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition: dimension out of range at layer " + std::to_string(l));
     if (!Ginv[l] || !Ainv[l] || !gradW[l] || !out[l])
       return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition: NULL matrix pointer at layer " + std::to_string(l));

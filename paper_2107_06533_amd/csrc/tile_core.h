@@ -5,9 +5,10 @@
 // v_mfma_f32_32x32x2_f32 blocks) computes  acc[i][j] = sum_k a(k, i0+i) * b(k, j0+j)
 // over a k-range.  Operands are staged as [k][m] panels in LDS (double-buffered, one
 // barrier per 32-deep k step); the next panel's global loads are in flight while the
-// current one is multiplied.  Every 2048 contraction rows the MFMA accumulator is
-// flushed into a second register set, so long sums of non-negative products (ReLU
-// activations over 10^5 rows) keep fp32-level relative error.
+// current one is multiplied.  One job accumulates at most MAX_JOB_ROWS contraction rows in
+// its fp32 MFMA accumulator; longer reductions (ReLU activations over 10^5 rows are sums of
+// non-negative products, whose rounding error grows with the run length) are split into
+// several jobs whose partial tiles are added in a fixed order by the reduce kernel.
 #pragma once
 #include "common.h"
 
@@ -33,131 +34,208 @@ __device__ __forceinline__ void acc_add(Acc4& t, const Acc4& x) {
 
 // ------------------------------------------------------------------------------ loaders
 // Each loader owns the per-thread part of moving one [KC x 128] operand panel:
-//   load(k0, r)  : global -> 16 registers (predicated; out-of-range elements are 0)
+//   load(k0, r)  : global -> 16 registers (out-of-range elements read 0)
 //   store(lds, r): registers -> LDS panel laid out [k][m] with row pitch PITCH
 
-// (k, m) at ptr[k*ld + m]: consecutive threads read consecutive m.
-struct KMajorLoader {
-  const float* colp;
-  size_t ld;
-  int kend, ml, kp;
-  bool mvalid, isbias;
+// Pointers that live in descriptor tables reach the kernels as generic pointers; casting them to
+// the global address space lets the compiler emit global_load / global_store (vmcnt only).  A
+// generic (flat) access also counts on lgkmcnt, which serialises it against every LDS access.
+typedef const float __attribute__((address_space(1)))* gcf_ptr;
+typedef float __attribute__((address_space(1)))* gf_ptr;
+__device__ __forceinline__ gcf_ptr as_global(const float* p) { return (gcf_ptr)p; }
+__device__ __forceinline__ gf_ptr as_global(float* p) { return (gf_ptr)p; }
 
-  __device__ __forceinline__ void init(const Operand& op, int m0, int kend_, int2* /*qtab*/, int t) {
+// Operand panels are read with raw buffer loads: a 128-bit resource (base, size in bytes) in
+// scalar registers plus one 32-bit byte offset per lane.  The hardware range check returns 0 for
+// any offset at or beyond the size, so an out-of-range element (ragged tile edge, image border,
+// row beyond the job's k range) is just the offset OOB_OFFSET: no branches, no address selects,
+// and the 16 loads of a panel issue back to back.  Operands are limited to 2 GiB.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t OOB_OFFSET = 0x80000000u;
+__device__ __forceinline__ rsrc_t make_rsrc(const float* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, uint32_t byte_off) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
+}
+
+// (k, m) at ptr[k*ld + m]: consecutive threads read consecutive m.  The resource is cut at the
+// job's last row, so rows at or beyond kend read 0 without a per-load test; one add per load.
+struct KMajorLoader {
+  rsrc_t rs;
+  uint32_t ld4, moff;   // row pitch / column offset in bytes (moff = OOB_OFFSET beyond the matrix)
+  int kend, ml, kp, kcur;
+  bool isbias, tile_bias;
+
+  __device__ __forceinline__ void init(const Operand& op, int m0, int kend_, int t) {
     ml = t & (BM - 1);
     kp = t >> 7;
     const int m = m0 + ml;
     const int mreal = op.M - op.bias;
-    mvalid = m < mreal;
     isbias = op.bias && m == mreal;
-    colp = op.ptr + (mvalid ? m : 0);
-    ld = (size_t)op.ld;
+    tile_bias = op.bias && m0 + BM > mreal && m0 <= mreal;
+    moff = m < mreal ? (uint32_t)m * 4u : OOB_OFFSET;
+    ld4 = (uint32_t)op.ld * 4u;
+    const uint32_t cut = (uint32_t)kend_ * ld4;
+    rs = make_rsrc(op.ptr, cut < op.bytes ? cut : op.bytes);
     kend = kend_;
+    kcur = 0;
   }
-  __device__ __forceinline__ void load(int k0, float (&r)[16]) const {
+  __device__ __forceinline__ void load(int k0, float (&r)[16]) {
+    kcur = k0;
+    const uint32_t base = (uint32_t)(k0 + kp) * ld4 + moff;   // stays >= OOB_OFFSET for invalid columns
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int k = k0 + kp + 2 * u;
-      const bool ok = k < kend;
-      float v = (isbias && ok) ? 1.f : 0.f;
-      if (ok && mvalid) v = colp[(size_t)k * ld];
-      r[u] = v;
-    }
+    for (int u = 0; u < 16; ++u) r[u] = buf_load(rs, base + (uint32_t)(2 * u) * ld4);
   }
   __device__ __forceinline__ void store(float* lds, const float (&r)[16]) const {
+    if (tile_bias) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) lds[(kp + 2 * u) * PITCH + ml] = r[u];
+      for (int u = 0; u < 16; ++u)
+        lds[(kp + 2 * u) * PITCH + ml] = (isbias && kcur + kp + 2 * u < kend) ? 1.f : r[u];
+    } else {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) lds[(kp + 2 * u) * PITCH + ml] = r[u];
+    }
   }
 };
 
 // NCHW tensor viewed through a KH x KW window: k = output pixel (n, oy, ox), m = (c, i, j).
-// Consecutive threads read consecutive k (contiguous along ox for stride 1).
-// KH_ = KW_ = 0 selects run-time window sizes.  KH_ = KW_ = 1 assumes pad = 0.
+// Consecutive threads read consecutive k (contiguous along ox for stride 1).  A thread keeps its
+// 16 columns for the whole tile: their byte offsets c*H*W + i*W + j and their tap numbers i*KW + j
+// live in registers.  Per k step it computes, for its one pixel, the window origin and a bit mask
+// of the taps that fall outside the image; a load is then  origin + column offset, with the
+// "outside" bit moved into bit 31 of the offset (out of range, reads 0): four VALU operations.
+// Tap TAP_NEVER is never inside: it marks columns beyond the matrix and the ones column.
+// KH_ = KW_ = 0 selects run-time window sizes (up to 63 taps, 64-bit tap mask).
 template <int KH_, int KW_>
 struct ConvLoader {
-  const float* base;
-  const int2* q;
-  size_t CHW;
-  int kend, H, W, OHW, OW, stride, kl, mg;
+  static constexpr bool TAP64 = (KH_ * KW_ == 0) || (KH_ * KW_ > 31);
+  static constexpr int TAP_NEVER = TAP64 ? 63 : 31;
+  rsrc_t rs;
+  uint32_t qoff4[16];
+  uint32_t taps[4];      // 8 bits per column
+  uint32_t CHW4;
+  int kend, H, W, OHW, OW, stride, pad, KH, KW, kl, mg;
+  unsigned biasmask;
+  bool okcur, tile_bias;
   FastDiv dOW, dOHW;
 
-  __device__ __forceinline__ void init(const Operand& op, int m0, int kend_, int2* qtab, int t) {
-    const int KH = KH_ ? KH_ : op.KH, KW = KW_ ? KW_ : op.KW;
-    if (t < BM) {
-      const int m = m0 + t;
-      const int mreal = op.M - op.bias;
-      int2 e;
+  __device__ __forceinline__ void init(const Operand& op, int m0, int kend_, int t) {
+    KH = KH_ ? KH_ : op.KH;
+    KW = KW_ ? KW_ : op.KW;
+    kl = t & 31;
+    mg = t >> 5;
+    const int mreal = op.M - op.bias;
+    tile_bias = op.bias && m0 + BM > mreal && m0 <= mreal;
+    biasmask = 0;
+#pragma unroll
+    for (int w4 = 0; w4 < 4; ++w4) taps[w4] = 0;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int m = m0 + mg + 8 * u;
+      uint32_t off = 0, tap = TAP_NEVER;
       if (m < mreal) {
         const int c = m / (KH * KW);
         const int rem = m - c * (KH * KW);
         const int i = rem / KW, j = rem - i * KW;
-        const int dy = i - op.pad, dx = j - op.pad;
-        e.x = c * op.H * op.W + dy * op.W + dx;
-        e.y = ((dy + 128) & 0xff) | (((dx + 128) & 0xff) << 8);
+        off = (uint32_t)(c * op.H * op.W + i * op.W + j) * 4u;
+        tap = (uint32_t)rem;
       } else if (op.bias && m == mreal) {
-        e.x = 0;
-        e.y = 1 << 16;   // ones column
-      } else {
-        e.x = 0;
-        e.y = 2 << 16;   // beyond the matrix: zero
+        biasmask |= 1u << u;
       }
-      qtab[t] = e;
+      qoff4[u] = off;
+      taps[u >> 2] |= tap << (8 * (u & 3));
     }
-    base = op.ptr;
-    q = qtab;
-    CHW = (size_t)op.C * op.H * op.W;
+    rs = make_rsrc(op.ptr, op.bytes);
+    CHW4 = (uint32_t)(op.C * op.H * op.W) * 4u;
     kend = kend_;
-    H = op.H; W = op.W; OW = op.OW; OHW = op.OH * op.OW; stride = op.stride;
+    H = op.H; W = op.W; OW = op.OW; OHW = op.OH * op.OW; stride = op.stride; pad = op.pad;
     dOW = op.dOW; dOHW = op.dOHW;
-    kl = t & 31;
-    mg = t >> 5;
+    okcur = false;
   }
-  __device__ __forceinline__ void load(int k0, float (&r)[16]) const {
+  __device__ __forceinline__ void load(int k0, float (&r)[16]) {
     const int k = k0 + kl;
     const bool ok = k < kend;
+    okcur = ok;
     const uint32_t kk = ok ? (uint32_t)k : 0u;
     const uint32_t n = fast_div(kk, dOHW);
     const uint32_t rem = kk - n * (uint32_t)OHW;
     const uint32_t oy = fast_div(rem, dOW);
     const uint32_t ox = rem - oy * (uint32_t)OW;
-    const int y0 = (int)oy * stride, x0 = (int)ox * stride;
-    const float* pn = base + (size_t)n * CHW + (y0 * W + x0);
+    const int y0 = (int)oy * stride - pad, x0 = (int)ox * stride - pad;   // window origin (may be < 0)
+    const uint32_t pix4 = n * CHW4 + (uint32_t)(y0 * W + x0) * 4u;
+    if (!TAP64) {
+      uint32_t colbits = 0, inside = 0;
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int2 e = q[mg + 8 * u];
-      const int kind = e.y >> 16;
-      float v = (kind == 1 && ok) ? 1.f : 0.f;
-      bool in = ok && kind == 0;
-      if (!(KH_ == 1 && KW_ == 1)) {
-        const int dy = (e.y & 0xff) - 128, dx = ((e.y >> 8) & 0xff) - 128;
-        in = in && (unsigned)(y0 + dy) < (unsigned)H && (unsigned)(x0 + dx) < (unsigned)W;
+      for (int j = 0; j < (KW_ ? KW_ : 1); ++j) colbits |= ((unsigned)(x0 + j) < (unsigned)W ? 1u : 0u) << j;
+#pragma unroll
+      for (int i = 0; i < (KH_ ? KH_ : 1); ++i)
+        inside |= ((unsigned)(y0 + i) < (unsigned)H ? colbits : 0u) << (i * KW_);
+      const uint32_t outside = ok ? ~inside : 0xFFFFFFFFu;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const uint32_t tap = (taps[u >> 2] >> (8 * (u & 3))) & 0xffu;
+        const uint32_t bad = (outside >> tap) & 1u;
+        r[u] = buf_load(rs, (pix4 + qoff4[u]) | (bad << 31));
       }
-      if (in) v = pn[e.x];
-      r[u] = v;
+    } else {
+      uint64_t colbits = 0, inside = 0;
+      for (int j = 0; j < KW; ++j) colbits |= (uint64_t)((unsigned)(x0 + j) < (unsigned)W ? 1u : 0u) << j;
+      for (int i = 0; i < KH; ++i) inside |= ((unsigned)(y0 + i) < (unsigned)H ? colbits : 0ull) << (i * KW);
+      const uint64_t outside = ok ? ~inside : ~0ull;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const uint32_t tap = (taps[u >> 2] >> (8 * (u & 3))) & 0xffu;
+        const uint32_t bad = (uint32_t)(outside >> tap) & 1u;
+        r[u] = buf_load(rs, (pix4 + qoff4[u]) | (bad << 31));
+      }
     }
   }
   __device__ __forceinline__ void store(float* lds, const float (&r)[16]) const {
+    if (tile_bias) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) lds[kl * PITCH + mg + 8 * u] = r[u];
+      for (int u = 0; u < 16; ++u)
+        lds[kl * PITCH + mg + 8 * u] = (((biasmask >> u) & 1u) && okcur) ? 1.f : r[u];
+    } else {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) lds[kl * PITCH + mg + 8 * u] = r[u];
+    }
   }
 };
 
 // ------------------------------------------------------------------------------ MFMA step
 // One staged k step (KC deep).  Lane l supplies a(k = l/32, i = l%32) and b(k = l/32, j = l%32).
-template <bool MASKED>
+// PAT is the compile-time set of the wave's 32x32 blocks that are computed (bit a*2+b): the
+// MFMA sequence is straight-line code for every pattern.
+constexpr unsigned PAT_FULL = 0xF, PAT_ROW1 = 0x3, PAT_COL1 = 0x5, PAT_ONE = 0x1, PAT_TRI = 0xD, PAT_NONE = 0;
+
+template <unsigned PAT>
 __device__ __forceinline__ void mma_ktile(const float* __restrict__ As, const float* __restrict__ Bs,
-                                          Acc4& acc, int wm, int wn, int lane, unsigned mask) {
+                                          Acc4& acc, int wm, int wn, int lane) {
+  if (PAT == PAT_NONE) return;
   const float* ap = As + (lane >> 5) * PITCH + wm * 64 + (lane & 31);
   const float* bp = Bs + (lane >> 5) * PITCH + wn * 64 + (lane & 31);
 #pragma unroll
   for (int ks = 0; ks < KC / 2; ++ks) {
-    const float a0 = ap[ks * 2 * PITCH], a1 = ap[ks * 2 * PITCH + 32];
-    const float b0 = bp[ks * 2 * PITCH], b1 = bp[ks * 2 * PITCH + 32];
-    if (!MASKED || (mask & 1u)) acc.c[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc.c[0], 0, 0, 0);
-    if (!MASKED || (mask & 2u)) acc.c[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc.c[1], 0, 0, 0);
-    if (!MASKED || (mask & 4u)) acc.c[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc.c[2], 0, 0, 0);
-    if (!MASKED || (mask & 8u)) acc.c[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc.c[3], 0, 0, 0);
+    float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
+    if (PAT & 0x3) a0 = ap[ks * 2 * PITCH];
+    if (PAT & 0xC) a1 = ap[ks * 2 * PITCH + 32];
+    if (PAT & 0x5) b0 = bp[ks * 2 * PITCH];
+    if (PAT & 0xA) b1 = bp[ks * 2 * PITCH + 32];
+    if (PAT & 1u) acc.c[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc.c[0], 0, 0, 0);
+    if (PAT & 2u) acc.c[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc.c[1], 0, 0, 0);
+    if (PAT & 4u) acc.c[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc.c[2], 0, 0, 0);
+    if (PAT & 8u) acc.c[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc.c[3], 0, 0, 0);
   }
+}
+
+// Smallest supported pattern that covers a block mask (valid rows/columns are prefixes, and a
+// diagonal wave of a symmetric diagonal tile needs only its lower triangle of blocks).
+__device__ __forceinline__ unsigned cover_pattern(unsigned mask) {
+  if (mask == 0) return PAT_NONE;
+  if (mask == PAT_TRI) return PAT_TRI;
+  const bool rows2 = mask & 0xC, cols2 = mask & 0xA;
+  return rows2 ? (cols2 ? PAT_FULL : PAT_COL1) : (cols2 ? PAT_ROW1 : PAT_ONE);
 }
 
 // Row / column of register v of a 32x32 MFMA result held by `lane`.
@@ -180,8 +258,39 @@ __device__ __forceinline__ unsigned block_mask(const TileDesc& D, int bi, int bj
   return mask;
 }
 
-// LDS floats needed by run_tile: 2 operands x 2 buffers + two 128-entry int2 tables
-constexpr int TILE_LDS_FLOATS = 4 * PANEL + 4 * BM;
+// LDS floats needed by run_tile: 2 operands x 2 buffers
+constexpr int TILE_LDS_FLOATS = 4 * PANEL;
+
+// The k loop of one tile: stage panel kt+1 (global -> registers -> LDS buffer cur^1) around the
+// MFMA work on panel kt (LDS buffer cur); one barrier per k step.  Every wave of the workgroup
+// runs the same number of steps whatever its pattern.
+template <unsigned PAT, class LA, class LB>
+__device__ __forceinline__ void main_loop(LA& la, LB& lb, bool share, float* As, float* Bs, Acc4& tot,
+                                          int kbeg, int nkt, int wm, int wn, int lane) {
+  float ra[16], rb[16];
+  if (nkt > 0) {
+    la.load(kbeg, ra);
+    if (!share) lb.load(kbeg, rb);
+    la.store(As, ra);
+    if (!share) lb.store(Bs, rb);
+  }
+  __syncthreads();
+  int cur = 0;
+  for (int kt = 0; kt < nkt; ++kt) {
+    const bool more = kt + 1 < nkt;
+    if (more) {
+      la.load(kbeg + (kt + 1) * KC, ra);
+      if (!share) lb.load(kbeg + (kt + 1) * KC, rb);
+    }
+    mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
+    if (more) {
+      la.store(As + (cur ^ 1) * PANEL, ra);
+      if (!share) lb.store(Bs + (cur ^ 1) * PANEL, rb);
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+}
 
 template <class LA, class LB>
 __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, float* smem) {
@@ -191,56 +300,29 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   const bool share = diag && D.a.ptr == D.b.ptr;   // a == b on a diagonal tile: stage one panel only
   float* As = smem;
   float* Bs = share ? As : smem + 2 * PANEL;
-  int2* qA = reinterpret_cast<int2*>(smem + 4 * PANEL);
-  int2* qB = qA + BM;
 
   LA la;
   LB lb;
-  la.init(D.a, i0, J.kend, qA, t);
-  if (!share) lb.init(D.b, j0, J.kend, qB, t);
-  __syncthreads();
+  la.init(D.a, i0, J.kend, t);
+  lb.init(D.b, j0, J.kend, t);
 
   const unsigned mask = block_mask(D, J.bi, J.bj, wm, wn);
 
-  Acc4 acc, tot;
-  acc_zero(acc);
+  Acc4 tot;
   acc_zero(tot);
-  float ra[16], rb[16];
   const int nkt = (J.kend - J.kbeg + KC - 1) / KC;
-  if (nkt > 0) {
-    la.load(J.kbeg, ra);
-    if (!share) lb.load(J.kbeg, rb);
-    la.store(As, ra);
-    if (!share) lb.store(Bs, rb);
+  switch (cover_pattern(mask)) {
+    case PAT_FULL: main_loop<PAT_FULL>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ROW1: main_loop<PAT_ROW1>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_COL1: main_loop<PAT_COL1>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ONE: main_loop<PAT_ONE>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_TRI: main_loop<PAT_TRI>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    default: main_loop<PAT_NONE>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
   }
-  __syncthreads();
-  int cur = 0;
-  for (int kt = 0; kt < nkt; ++kt) {
-    const bool more = kt + 1 < nkt;
-    if (more) {
-      la.load(J.kbeg + (kt + 1) * KC, ra);
-      if (!share) lb.load(J.kbeg + (kt + 1) * KC, rb);
-    }
-    if (mask == 0xFu)
-      mma_ktile<false>(As + cur * PANEL, Bs + cur * PANEL, acc, wm, wn, lane, mask);
-    else if (mask)
-      mma_ktile<true>(As + cur * PANEL, Bs + cur * PANEL, acc, wm, wn, lane, mask);
-    if (more) {
-      la.store(As + (cur ^ 1) * PANEL, ra);
-      if (!share) lb.store(Bs + (cur ^ 1) * PANEL, rb);
-    }
-    __syncthreads();
-    cur ^= 1;
-    if ((kt % ACC_FLUSH) == ACC_FLUSH - 1) {
-      acc_add(tot, acc);
-      acc_zero(acc);
-    }
-  }
-  acc_add(tot, acc);
 
   // ---- epilogue
   if (J.part >= 0) {
-    float* P = D.partial + (size_t)J.part * (BM * BN);
+    gf_ptr P = as_global(D.partial) + (size_t)J.part * (BM * BN);
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd) {
       if (!(mask & (1u << qd))) continue;
@@ -251,6 +333,7 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
     return;
   }
   const float alpha = D.alpha, beta = D.beta;
+  gf_ptr out = as_global(D.out);
   const bool mirror = D.mirror == MIRROR_ALL || (D.mirror == MIRROR_DIAG_TILE && diag);
 #pragma unroll
   for (int qd = 0; qd < 4; ++qd) {
@@ -261,11 +344,11 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
     for (int v = 0; v < 16; ++v) {
       const int gi = rb0 + mfma_row(v, lane);
       if (gi < D.M && gj < D.N && (!D.sym || gi >= gj)) {
-        float* o = D.out + (size_t)gi * D.ldo + gj;
+        gf_ptr o = out + (size_t)gi * D.ldo + gj;
         float val = alpha * tot.c[qd][v];
         if (beta != 0.f) val += beta * *o;
         *o = val;
-        if (mirror && gi != gj) D.out[(size_t)gj * D.ldo + gi] = val;
+        if (mirror && gi != gj) out[(size_t)gj * D.ldo + gi] = val;
       }
     }
   }
