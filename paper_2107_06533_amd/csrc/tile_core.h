@@ -58,6 +58,10 @@ __device__ __forceinline__ rsrc_t make_rsrc(const float* p, uint32_t bytes) {
 __device__ __forceinline__ float buf_load(rsrc_t r, uint32_t byte_off) {
   return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
 }
+// Stores at or beyond the resource size are dropped by the same range check.
+__device__ __forceinline__ void buf_store(rsrc_t r, uint32_t byte_off, float v) {
+  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)byte_off, 0, 0);
+}
 
 // (k, m) at ptr[k*ld + m]: consecutive threads read consecutive m.  The resource is cut at the
 // job's last row, so rows at or beyond kend read 0 without a per-load test; one add per load.
@@ -308,6 +312,30 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
 
   const unsigned mask = block_mask(D, J.bi, J.bj, wm, wn);
 
+  // Byte offset of output element (block qd, register v) of this lane, OOB_OFFSET when the element
+  // is outside the matrix, above the diagonal of a symmetric output, or in a block that is not computed.
+  const uint32_t ldo4 = (uint32_t)D.ldo * 4u;
+  auto out_offset = [&](int qd, int v) -> uint32_t {
+    const int gi = i0 + wm * 64 + (qd >> 1) * 32 + mfma_row(v, lane);
+    const int gj = j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane);
+    const bool ok = ((mask >> qd) & 1u) && gi < D.M && gj < D.N && (!D.sym || gi >= gj);
+    return ok ? (uint32_t)gi * ldo4 + (uint32_t)gj * 4u : OOB_OFFSET;
+  };
+  const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * ldo4);
+  const float alpha = D.alpha, beta = D.beta;
+  const bool direct = J.part < 0;
+
+  // Old output values (running average, sweep update) are fetched before the k loop so that their
+  // latency is covered by the MFMA work; they are all in registers before anything is stored.
+  Acc4 old;
+  acc_zero(old);
+  if (direct && beta != 0.f) {
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) old.c[qd][v] = buf_load(ro, out_offset(qd, v));
+  }
+
   Acc4 tot;
   acc_zero(tot);
   const int nkt = (J.kend - J.kbeg + KC - 1) / KC;
@@ -321,7 +349,7 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   }
 
   // ---- epilogue
-  if (J.part >= 0) {
+  if (!direct) {
     gf_ptr P = as_global(D.partial) + (size_t)J.part * (BM * BN);
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd) {
@@ -332,23 +360,18 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
     }
     return;
   }
-  const float alpha = D.alpha, beta = D.beta;
-  gf_ptr out = as_global(D.out);
   const bool mirror = D.mirror == MIRROR_ALL || (D.mirror == MIRROR_DIAG_TILE && diag);
 #pragma unroll
   for (int qd = 0; qd < 4; ++qd) {
-    if (!(mask & (1u << qd))) continue;
-    const int rb0 = i0 + wm * 64 + (qd >> 1) * 32, cb0 = j0 + wn * 64 + (qd & 1) * 32;
-    const int gj = cb0 + mfma_col(lane);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int gi = rb0 + mfma_row(v, lane);
-      if (gi < D.M && gj < D.N && (!D.sym || gi >= gj)) {
-        gf_ptr o = out + (size_t)gi * D.ldo + gj;
-        float val = alpha * tot.c[qd][v];
-        if (beta != 0.f) val += beta * *o;
-        *o = val;
-        if (mirror && gi != gj) out[(size_t)gj * D.ldo + gi] = val;
+      const float val = alpha * tot.c[qd][v] + beta * old.c[qd][v];
+      const uint32_t off = out_offset(qd, v);
+      buf_store(ro, off, val);
+      if (mirror) {
+        const int gi = i0 + wm * 64 + (qd >> 1) * 32 + mfma_row(v, lane);
+        const int gj = j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane);
+        buf_store(ro, (off != OOB_OFFSET && gi != gj) ? (uint32_t)gj * ldo4 + (uint32_t)gi * 4u : OOB_OFFSET, val);
       }
     }
   }
