@@ -21,7 +21,7 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
+def build(verbose: bool = True, extra_flags=tuple(os.environ.get("KFAC_EXTRA_FLAGS", "").split())) -> str:
     """Compile every HIP source and link libkfac_hip.so next to this file."""
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)

@@ -35,20 +35,24 @@ __global__ __launch_bounds__(NT) void gj_init_kernel(const InvMat* __restrict__ 
 }
 
 // ---- pivot block: in-register symmetric sweep of an n x n (n <= 128) SPD block ------------------
-// 256 threads as 16 x 16; thread (ty, tx) holds elements (ty + 16a, tx + 16b), a, b = 0..7.
+// 256 threads as 16 x 16; thread (ty, tx) holds elements (ty + 16a, tx + 16b) for a >= b only: the
+// sweep keeps the lower triangle and mirrors it at the end, so the result is exactly symmetric.
+// Step k broadcasts column k of the symmetric matrix through LDS (rows >= k from column k, rows < k
+// from row k), then every element does one fused multiply-add  m_ij -= (c_i / p) * c_j.
 // small = 1: block = F + gamma I (whole matrix, d <= NB), result written to X as +inverse.
 // small = 0: block = diagonal block `step` of X; writes Q = +inverse (zero padded to NB x NB)
 //            and the swept block (-inverse) back into X.
 __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__ mats, int mat0, int step,
                                                       float gamma, int small) {
   __shared__ float col[2][NB];
+  __shared__ float tileT[NB][NB + 1];   // mirror staging
   __shared__ int bad;
   const InvMat Mx = mats[mat0 + blockIdx.x];
   const int t = threadIdx.x, ty = t >> 4, tx = t & 15;
   const int d = Mx.d;
   const int k0 = small ? 0 : step * NB;
   const int n = small ? d : (d - k0 < NB ? d - k0 : NB);
-  const float* src = small ? Mx.F : Mx.X;
+  gcf_ptr src = as_global(small ? Mx.F : Mx.X);
   const float damp = small ? gamma : 0.f;
 
   float m[8][8];
@@ -56,11 +60,11 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
   for (int a = 0; a < 8; ++a)
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
+      if (b > a) continue;
       const int i = ty + 16 * a, j = tx + 16 * b;
       float v = (i == j) ? 1.f : 0.f;
-      if (i < n && j < n) {
-        const int hi = i > j ? i : j, lo = i > j ? j : i;
-        v = src[(size_t)(k0 + hi) * d + k0 + lo];
+      if (i < n && j < n && i >= j) {
+        v = src[(size_t)(k0 + i) * d + k0 + j];
         if (i == j) v += damp;
       }
       m[a][b] = v;
@@ -75,54 +79,71 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
       for (int kk = 0; kk < kk_end; ++kk) {
         const int k = kb * 16 + kk;
         float* cb = col[k & 1];
-        if (tx == kk) {
+        if (tx == kk) {            // rows i >= k of column k
 #pragma unroll
-          for (int a = 0; a < 8; ++a) cb[ty + 16 * a] = m[a][kb];
+          for (int a = kb; a < 8; ++a)
+            if (a > kb || ty >= kk) cb[ty + 16 * a] = m[a][kb];
+        }
+        if (ty == kk) {            // rows i < k come from row k
+#pragma unroll
+          for (int b = 0; b <= kb; ++b)
+            if (b < kb || tx < kk) cb[tx + 16 * b] = m[kb][b];
         }
         __syncthreads();
         const float p = cb[k];
         if (!(p > 0.f) && t == 0 && bad == 0) bad = k + 1;
         const float ip = 1.f / p;
-        float ci[8], cj[8];
+        float wi[8], cj[8];
 #pragma unroll
-        for (int a = 0; a < 8; ++a) ci[a] = cb[ty + 16 * a];
+        for (int a = 0; a < 8; ++a) wi[a] = cb[ty + 16 * a] * ip;
 #pragma unroll
         for (int b = 0; b < 8; ++b) cj[b] = cb[tx + 16 * b];
 #pragma unroll
         for (int a = 0; a < 8; ++a)
 #pragma unroll
-          for (int b = 0; b < 8; ++b) m[a][b] = fmaf(-(ci[a] * cj[b]), ip, m[a][b]);
-        if (tx == kk) {
+          for (int b = 0; b <= a; ++b) m[a][b] = fmaf(-wi[a], cj[b], m[a][b]);
+        if (tx == kk) {            // column k: m_ik = c_i / p
 #pragma unroll
-          for (int a = 0; a < 8; ++a) m[a][kb] = ci[a] * ip;
+          for (int a = kb; a < 8; ++a) m[a][kb] = wi[a];
         }
-        if (ty == kk) {
+        if (ty == kk) {            // row k: m_kj = c_j / p
 #pragma unroll
-          for (int b = 0; b < 8; ++b) m[kb][b] = cj[b] * ip;
+          for (int b = 0; b <= kb; ++b) m[kb][b] = cj[b] * ip;
         }
         if (tx == kk && ty == kk) m[kb][kb] = -ip;
       }
     }
   }
-  __syncthreads();
   if (t == 0 && Mx.info) {
     if (small) *Mx.info = bad;                                // whole matrix: sole writer
     else if (bad && *Mx.info == 0) *Mx.info = k0 + bad;       // first failing sweep wins (zeroed by the init kernel)
   }
 
+  // mirror the lower triangle through LDS, then write rows contiguously
 #pragma unroll
   for (int a = 0; a < 8; ++a)
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
+    for (int b = 0; b <= a; ++b) {
       const int i = ty + 16 * a, j = tx + 16 * b;
-      const bool in = i < n && j < n;
-      if (small) {
-        if (in) Mx.X[(size_t)i * d + j] = -m[a][b];
-      } else {
-        Mx.Q[i * NB + j] = in ? -m[a][b] : 0.f;
-        if (in) Mx.X[(size_t)(k0 + i) * d + k0 + j] = m[a][b];
+      if (i >= j) {
+        tileT[i][j] = m[a][b];
+        tileT[j][i] = m[a][b];
       }
     }
+  __syncthreads();
+  gf_ptr X = as_global(Mx.X);
+  gf_ptr Q = as_global(Mx.Q);
+  for (int e = t; e < NB * NB; e += NT) {
+    const int i = e >> 7, j = e & (NB - 1);
+    const bool in = i < n && j < n;
+    const float v = tileT[i][j];
+    if (small) {
+      if (in) X[(size_t)i * d + j] = -v;
+    } else {
+      Q[i * NB + j] = in ? -v : 0.f;
+      if (in) X[(size_t)(k0 + i) * d + k0 + j] = v;
+    }
+  }
 }
 
 // ---- panel: Zt = old block column `step` (as [NB][ldp], k-major), Wt = Q * Zt, X panel <- W -----

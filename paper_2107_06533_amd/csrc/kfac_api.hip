@@ -47,19 +47,26 @@ struct FactorPlan {
   kfac_plan_stats stats{};
 };
 
-struct InvertPlan {
-  bool valid = false;
-  std::vector<int32_t> dims;
-  std::vector<int> order;            // sorted position -> caller index (large first, descending d)
+// One group of matrices that is swept in lockstep on its own stream.
+struct InvertGroup {
+  std::vector<int> idx;              // caller indices of the group's matrices
+  std::vector<int> order;            // sorted position -> position in idx (large first, descending d)
   int n_large = 0, n_small = 0, nsteps = 0;
   std::vector<int> active;           // [step] number of large matrices still being swept
   std::vector<int> panel_off, upd_off;
-  std::vector<size_t> ws_off;        // per large matrix: float offset of its workspace
+  std::vector<size_t> ws_off;        // per large matrix: float offset of its workspace inside the group's region
   void* d_init = nullptr; int n_init = 0;
   void* d_finish = nullptr; int n_finish = 0;
   void* d_panel = nullptr;
   void* d_upd = nullptr;
   DynTable tab;                      // [InvMat x n][TileDesc x n_large]
+  size_t ws_floats = 0, ws_base = 0;
+};
+
+struct InvertPlan {
+  bool valid = false;
+  std::vector<int32_t> dims;
+  std::vector<InvertGroup> groups;
   size_t ws_floats = 0;
   kfac_plan_stats stats{};
 };
@@ -77,6 +84,8 @@ struct PrecondPlan {
 
 }  // namespace
 
+constexpr int MAX_INV_GROUPS = 4;
+
 struct TimingRec {
   hipEvent_t a, b;
   int kclass;
@@ -91,6 +100,9 @@ struct kfac_ctx {
   void* ws = nullptr;
   size_t ws_cap = 0;
   int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
+  int inv_groups = 3;                     // matrix groups swept concurrently (one internal stream each)
+  hipStream_t inv_stream[MAX_INV_GROUPS] = {};
+  hipEvent_t inv_fork = nullptr, inv_join[MAX_INV_GROUPS] = {};
   FactorPlan fp;
   InvertPlan ip;
   PrecondPlan pp;
@@ -312,7 +324,9 @@ void release(FactorPlan& p) {
   p = FactorPlan{};
 }
 void release(InvertPlan& p) {
-  free_dev(p.d_init); free_dev(p.d_finish); free_dev(p.d_panel); free_dev(p.d_upd); free_table(p.tab);
+  for (InvertGroup& g : p.groups) {
+    free_dev(g.d_init); free_dev(g.d_finish); free_dev(g.d_panel); free_dev(g.d_upd); free_table(g.tab);
+  }
   p = InvertPlan{};
 }
 void release(PrecondPlan& p) {
@@ -502,6 +516,10 @@ kfac_status kfac_create(kfac_ctx** out, int device) {
   kfac_ctx* c = new kfac_ctx();
   c->device = device;
   c->host_only = device < 0;
+  if (const char* e = std::getenv("KFAC_INV_GROUPS")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= MAX_INV_GROUPS) c->inv_groups = v;
+  }
   if (const char* e = std::getenv("KFAC_KJOB")) {
     const int v = std::atoi(e);
     if (v >= KC) c->kjob = std::min(v, MAX_JOB_ROWS);
@@ -526,6 +544,11 @@ void kfac_destroy(kfac_ctx* ctx) {
     release(ctx->fp); release(ctx->ip); release(ctx->pp);
     free_dev(ctx->ws);
     for (const TimingRec& r : ctx->timing) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (int g = 0; g < MAX_INV_GROUPS; ++g) {
+      if (ctx->inv_stream[g]) (void)hipStreamDestroy(ctx->inv_stream[g]);
+      if (ctx->inv_join[g]) (void)hipEventDestroy(ctx->inv_join[g]);
+    }
+    if (ctx->inv_fork) (void)hipEventDestroy(ctx->inv_fork);
   }
   delete ctx;
 }
@@ -548,7 +571,7 @@ size_t kfac_workspace_bytes_invert(const kfac_ctx*, int n, const int32_t* dims) 
   if (n <= 0 || !dims) return 0;
   for (int i = 0; i < n; ++i)
     if (dims[i] < 1) return 0;
-  return size_t(schedule_invert(n, dims).stats.ws_bytes);
+  return size_t(schedule_invert(n, dims).stats.ws_bytes);   // independent of how the matrices are grouped
 }
 
 size_t kfac_workspace_bytes_precondition(const kfac_ctx*, int n, const int32_t* dG, const int32_t* dA) {
@@ -702,7 +725,6 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   const bool same = P.valid && int(P.dims.size()) == n && std::memcmp(P.dims.data(), dims, sizeof(int32_t) * n) == 0;
   DeviceGuard guard(ctx);
   if (!same) {
-    InvertSchedule S = schedule_invert(n, dims);
     if (!ctx->host_only) {
       HIP_TRY(ctx, hipDeviceSynchronize());
       release(P);
@@ -710,17 +732,44 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       P = InvertPlan{};
     }
     P.dims.assign(dims, dims + n);
-    P.order = S.order; P.n_large = S.n_large; P.n_small = S.n_small; P.nsteps = S.nsteps;
-    P.active = S.active; P.panel_off = S.panel_off; P.upd_off = S.upd_off; P.ws_off = S.ws_off;
-    P.n_init = int(S.init.size()); P.n_finish = int(S.finish.size());
-    P.ws_floats = S.ws_floats;
-    P.stats = S.stats;
-    if (!ctx->host_only) {
-      kfac_status st;
-      if ((st = upload_static(ctx, &P.d_init, S.init.data(), S.init.size() * sizeof(MatJobH))) != KFAC_OK) return st;
-      if ((st = upload_static(ctx, &P.d_finish, S.finish.data(), S.finish.size() * sizeof(MatJobH))) != KFAC_OK) return st;
-      if ((st = upload_static(ctx, &P.d_panel, S.panel.data(), S.panel.size() * sizeof(MatJobH))) != KFAC_OK) return st;
-      if ((st = upload_static(ctx, &P.d_upd, S.upd.data(), S.upd.size() * sizeof(TileJob))) != KFAC_OK) return st;
+    // Load-balanced placement of the matrices on the groups (the paper's Algorithm 1 without its
+    // communication term, weighted by the true cost d^3): largest first, each to the lightest group.
+    // Matrices that fit one pivot block (d <= NB) need a single launch and all go to group 0.
+    std::vector<int> by_size(n);
+    for (int i = 0; i < n; ++i) by_size[i] = i;
+    std::stable_sort(by_size.begin(), by_size.end(), [&](int a, int b) { return dims[a] > dims[b]; });
+    int n_large = 0;
+    for (int i = 0; i < n; ++i) n_large += dims[i] > NB;
+    const int G = std::max(1, std::min(ctx->inv_groups, n_large));
+    P.groups.assign(G, InvertGroup{});
+    std::vector<double> load(G, 0.0);
+    for (int i : by_size) {
+      int g = 0;
+      if (dims[i] > NB) g = int(std::min_element(load.begin(), load.end()) - load.begin());
+      P.groups[g].idx.push_back(i);
+      load[g] += double(dims[i]) * dims[i] * dims[i];
+    }
+    P.ws_floats = 0;
+    P.stats = kfac_plan_stats{};
+    for (InvertGroup& Gp : P.groups) {
+      std::vector<int32_t> gd;
+      for (int i : Gp.idx) gd.push_back(dims[i]);
+      InvertSchedule S = schedule_invert(int(gd.size()), gd.data());
+      Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.nsteps = S.nsteps;
+      Gp.active = S.active; Gp.panel_off = S.panel_off; Gp.upd_off = S.upd_off; Gp.ws_off = S.ws_off;
+      Gp.n_init = int(S.init.size()); Gp.n_finish = int(S.finish.size());
+      Gp.ws_floats = S.ws_floats;
+      Gp.ws_base = P.ws_floats;
+      P.ws_floats += S.ws_floats;
+      P.stats.n_jobs += S.stats.n_jobs; P.stats.n_launches += S.stats.n_launches;
+      P.stats.mfma_flops += S.stats.mfma_flops; P.stats.ws_bytes += S.stats.ws_bytes;
+      if (!ctx->host_only) {
+        kfac_status st;
+        if ((st = upload_static(ctx, &Gp.d_init, S.init.data(), S.init.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = upload_static(ctx, &Gp.d_finish, S.finish.data(), S.finish.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = upload_static(ctx, &Gp.d_panel, S.panel.data(), S.panel.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = upload_static(ctx, &Gp.d_upd, S.upd.data(), S.upd.size() * sizeof(TileJob))) != KFAC_OK) return st;
+      }
     }
     P.valid = true;
   }
@@ -729,67 +778,105 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   kfac_status st = ensure_ws(ctx, P.ws_floats * sizeof(float));
   if (st != KFAC_OK) return st;
+  const int G = int(P.groups.size());
 
-  // per-call tables: [InvMat x n] then [TileDesc x n_large]
-  const size_t mats_bytes = sizeof(InvMat) * size_t(n);
-  const size_t tab_bytes = mats_bytes + sizeof(TileDesc) * size_t(P.n_large);
-  std::vector<unsigned char> img(tab_bytes, 0);
-  InvMat* hm = reinterpret_cast<InvMat*>(img.data());
-  TileDesc* hd = reinterpret_cast<TileDesc*>(img.data() + mats_bytes);
+  // With more than one group, every group runs on an internal stream (default priority) that is
+  // forked from and joined back into the caller's stream with events.
+  if (G > 1) {
+    if (!ctx->inv_fork) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->inv_fork, hipEventDisableTiming));
+    for (int g = 0; g < G; ++g) {
+      if (!ctx->inv_stream[g]) HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->inv_stream[g], hipStreamNonBlocking));
+      if (!ctx->inv_join[g]) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->inv_join[g], hipEventDisableTiming));
+    }
+    HIP_TRY(ctx, hipEventRecord(ctx->inv_fork, s));
+    for (int g = 0; g < G; ++g) HIP_TRY(ctx, hipStreamWaitEvent(ctx->inv_stream[g], ctx->inv_fork, 0));
+  }
+  auto gstream = [&](int g) { return G > 1 ? ctx->inv_stream[g] : s; };
+
+  // per-call tables of every group: [InvMat x n_g] then [TileDesc x n_large_g]
+  std::vector<const InvMat*> d_mats(G);
+  std::vector<const TileDesc*> d_descs(G);
   float* wsf = static_cast<float*>(ctx->ws);
-  for (int m = 0; m < n; ++m) {
-    const int o = P.order[m];
-    InvMat& M = hm[m];
-    M.F = F[o]; M.X = X[o]; M.d = dims[o];
-    M.info = info_dev ? info_dev + o : nullptr;
-    if (m < P.n_large) {
-      M.nblk = ceil_div(M.d, NB);
-      M.ldp = M.nblk * NB;
-      M.Wt = wsf + P.ws_off[m];
-      M.Zt = M.Wt + size_t(NB) * M.ldp;
-      M.Q = M.Zt + size_t(NB) * M.ldp;
-      TileDesc& D = hd[m];
-      D.a = rowmajor_operand(M.Wt, NB, M.ldp, M.ldp);
-      D.b = rowmajor_operand(M.Zt, NB, M.ldp, M.ldp);
-      D.out = M.X; D.ldo = M.d; D.M = D.N = M.d;
-      D.sym = 1; D.mirror = MIRROR_DIAG_TILE; D.alpha = -1.f; D.beta = 1.f;
-    } else {
-      M.nblk = 1; M.ldp = NB;
+  for (int g = 0; g < G; ++g) {
+    InvertGroup& Gp = P.groups[g];
+    const int ng = int(Gp.idx.size());
+    const size_t mats_bytes = sizeof(InvMat) * size_t(ng);
+    const size_t tab_bytes = mats_bytes + sizeof(TileDesc) * size_t(Gp.n_large);
+    std::vector<unsigned char> img(tab_bytes, 0);
+    InvMat* hm = reinterpret_cast<InvMat*>(img.data());
+    TileDesc* hd = reinterpret_cast<TileDesc*>(img.data() + mats_bytes);
+    for (int m = 0; m < ng; ++m) {
+      const int o = Gp.idx[Gp.order[m]];
+      InvMat& M = hm[m];
+      M.F = F[o]; M.X = X[o]; M.d = dims[o];
+      M.info = info_dev ? info_dev + o : nullptr;
+      if (m < Gp.n_large) {
+        M.nblk = ceil_div(M.d, NB);
+        M.ldp = M.nblk * NB;
+        M.Wt = wsf + Gp.ws_base + Gp.ws_off[m];
+        M.Zt = M.Wt + size_t(NB) * M.ldp;
+        M.Q = M.Zt + size_t(NB) * M.ldp;
+        TileDesc& D = hd[m];
+        D.a = rowmajor_operand(M.Wt, NB, M.ldp, M.ldp);
+        D.b = rowmajor_operand(M.Zt, NB, M.ldp, M.ldp);
+        D.out = M.X; D.ldo = M.d; D.M = D.N = M.d;
+        D.sym = 1; D.mirror = MIRROR_DIAG_TILE; D.alpha = -1.f; D.beta = 1.f;
+      } else {
+        M.nblk = 1; M.ldp = NB;
+      }
     }
+    st = sync_table(ctx, Gp.tab, img.data(), tab_bytes, gstream(g));
+    if (st != KFAC_OK) return st;
+    d_mats[g] = static_cast<const InvMat*>(Gp.tab.dev);
+    d_descs[g] = reinterpret_cast<const TileDesc*>(static_cast<const unsigned char*>(Gp.tab.dev) + mats_bytes);
   }
-  st = sync_table(ctx, P.tab, img.data(), tab_bytes, s);
-  if (st != KFAC_OK) return st;
-  const InvMat* d_mats = static_cast<const InvMat*>(P.tab.dev);
-  const TileDesc* d_descs = reinterpret_cast<const TileDesc*>(static_cast<const unsigned char*>(P.tab.dev) + mats_bytes);
 
-  if (P.n_small) {
-    ScopedTiming tm(ctx, KFAC_K_INV_SMALL, s);
-    launch_gj_pivot(d_mats, P.n_large, P.n_small, 0, gamma, 1, s);
-  }
-  if (P.n_large) {
-    {
-      ScopedTiming tm(ctx, KFAC_K_INV_INIT, s);
-      launch_gj_init(d_mats, P.d_init, P.n_init, gamma, s);
+  int max_steps = 0;
+  for (int g = 0; g < G; ++g) {
+    InvertGroup& Gp = P.groups[g];
+    hipStream_t gs = gstream(g);
+    max_steps = std::max(max_steps, Gp.nsteps);
+    if (Gp.n_small) {
+      ScopedTiming tm(ctx, KFAC_K_INV_SMALL, gs);
+      launch_gj_pivot(d_mats[g], Gp.n_large, Gp.n_small, 0, gamma, 1, gs);
     }
-    for (int step = 0; step < P.nsteps; ++step) {
+    if (Gp.n_large) {
+      ScopedTiming tm(ctx, KFAC_K_INV_INIT, gs);
+      launch_gj_init(d_mats[g], Gp.d_init, Gp.n_init, gamma, gs);
+    }
+  }
+  // the groups' sweeps are issued step by step so that their kernels interleave in time
+  for (int step = 0; step < max_steps; ++step)
+    for (int g = 0; g < G; ++g) {
+      InvertGroup& Gp = P.groups[g];
+      if (step >= Gp.nsteps) continue;
+      hipStream_t gs = gstream(g);
       {
-        ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, s);
-        launch_gj_pivot(d_mats, 0, P.active[step], step, gamma, 0, s);
+        ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
+        launch_gj_pivot(d_mats[g], 0, Gp.active[step], step, gamma, 0, gs);
       }
       {
-        ScopedTiming tm(ctx, KFAC_K_INV_PANEL, s);
-        launch_gj_panel(d_mats, static_cast<const MatJobH*>(P.d_panel) + P.panel_off[step],
-                        P.panel_off[step + 1] - P.panel_off[step], step, s);
+        ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
+        launch_gj_panel(d_mats[g], static_cast<const MatJobH*>(Gp.d_panel) + Gp.panel_off[step],
+                        Gp.panel_off[step + 1] - Gp.panel_off[step], step, gs);
       }
       {
-        ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, s);
-        launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_upd) + P.upd_off[step],
-                         P.upd_off[step + 1] - P.upd_off[step], 0, s);
+        ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, gs);
+        launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_upd) + Gp.upd_off[step],
+                         Gp.upd_off[step + 1] - Gp.upd_off[step], 0, gs);
       }
     }
-    ScopedTiming tm(ctx, KFAC_K_INV_FINISH, s);
-    launch_gj_finish(d_mats, P.d_finish, P.n_finish, s);
+  for (int g = 0; g < G; ++g) {
+    InvertGroup& Gp = P.groups[g];
+    if (!Gp.n_large) continue;
+    ScopedTiming tm(ctx, KFAC_K_INV_FINISH, gstream(g));
+    launch_gj_finish(d_mats[g], Gp.d_finish, Gp.n_finish, gstream(g));
   }
+  if (G > 1)
+    for (int g = 0; g < G; ++g) {
+      HIP_TRY(ctx, hipEventRecord(ctx->inv_join[g], ctx->inv_stream[g]));
+      HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->inv_join[g], 0));
+    }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
 }

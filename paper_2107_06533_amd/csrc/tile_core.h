@@ -10,6 +10,8 @@
 // non-negative products, whose rounding error grows with the run length) are split into
 // several jobs whose partial tiles are added in a fixed order by the reduce kernel.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 
 namespace kfac {
@@ -68,6 +70,7 @@ __device__ __forceinline__ void buf_store(rsrc_t r, uint32_t byte_off, float v) 
 struct KMajorLoader {
   rsrc_t rs;
   uint32_t ld4, moff;   // row pitch / column offset in bytes (moff = OOB_OFFSET beyond the matrix)
+  uint32_t base;
   int kend, ml, kp, kcur;
   bool isbias, tile_bias;
 
@@ -85,21 +88,23 @@ struct KMajorLoader {
     kend = kend_;
     kcur = 0;
   }
-  __device__ __forceinline__ void load(int k0, float (&r)[16]) {
+  // begin(k0) prepares a k step; load_one(u, r) issues the load of register u.
+  __device__ __forceinline__ void begin(int k0) {
     kcur = k0;
-    const uint32_t base = (uint32_t)(k0 + kp) * ld4 + moff;   // stays >= OOB_OFFSET for invalid columns
+    base = (uint32_t)(k0 + kp) * ld4 + moff;   // stays >= OOB_OFFSET for invalid columns
+  }
+  __device__ __forceinline__ void load_one(int u, float (&r)[16]) const {
+    r[u] = buf_load(rs, base + (uint32_t)(2 * u) * ld4);
+  }
+  __device__ __forceinline__ void load(int k0, float (&r)[16]) {
+    begin(k0);
 #pragma unroll
-    for (int u = 0; u < 16; ++u) r[u] = buf_load(rs, base + (uint32_t)(2 * u) * ld4);
+    for (int u = 0; u < 16; ++u) load_one(u, r);
   }
   __device__ __forceinline__ void store(float* lds, const float (&r)[16]) const {
-    if (tile_bias) {
 #pragma unroll
-      for (int u = 0; u < 16; ++u)
-        lds[(kp + 2 * u) * PITCH + ml] = (isbias && kcur + kp + 2 * u < kend) ? 1.f : r[u];
-    } else {
-#pragma unroll
-      for (int u = 0; u < 16; ++u) lds[(kp + 2 * u) * PITCH + ml] = r[u];
-    }
+    for (int u = 0; u < 16; ++u)
+      lds[(kp + 2 * u) * PITCH + ml] = (isbias && kcur + kp + 2 * u < kend) ? 1.f : r[u];
   }
 };
 
@@ -118,7 +123,8 @@ struct ConvLoader {
   rsrc_t rs;
   uint32_t qoff4[16];
   uint32_t taps[4];      // 8 bits per column
-  uint32_t CHW4;
+  uint32_t CHW4, pix4;
+  typename std::conditional<TAP64, uint64_t, uint32_t>::type outside;
   int kend, H, W, OHW, OW, stride, pad, KH, KW, kl, mg;
   unsigned biasmask;
   bool okcur, tile_bias;
@@ -157,7 +163,7 @@ struct ConvLoader {
     dOW = op.dOW; dOHW = op.dOHW;
     okcur = false;
   }
-  __device__ __forceinline__ void load(int k0, float (&r)[16]) {
+  __device__ __forceinline__ void begin(int k0) {
     const int k = k0 + kl;
     const bool ok = k < kend;
     okcur = ok;
@@ -167,7 +173,7 @@ struct ConvLoader {
     const uint32_t oy = fast_div(rem, dOW);
     const uint32_t ox = rem - oy * (uint32_t)OW;
     const int y0 = (int)oy * stride - pad, x0 = (int)ox * stride - pad;   // window origin (may be < 0)
-    const uint32_t pix4 = n * CHW4 + (uint32_t)(y0 * W + x0) * 4u;
+    pix4 = n * CHW4 + (uint32_t)(y0 * W + x0) * 4u;
     if (!TAP64) {
       uint32_t colbits = 0, inside = 0;
 #pragma unroll
@@ -175,35 +181,28 @@ struct ConvLoader {
 #pragma unroll
       for (int i = 0; i < (KH_ ? KH_ : 1); ++i)
         inside |= ((unsigned)(y0 + i) < (unsigned)H ? colbits : 0u) << (i * KW_);
-      const uint32_t outside = ok ? ~inside : 0xFFFFFFFFu;
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const uint32_t tap = (taps[u >> 2] >> (8 * (u & 3))) & 0xffu;
-        const uint32_t bad = (outside >> tap) & 1u;
-        r[u] = buf_load(rs, (pix4 + qoff4[u]) | (bad << 31));
-      }
+      outside = ok ? ~inside : 0xFFFFFFFFu;
     } else {
       uint64_t colbits = 0, inside = 0;
       for (int j = 0; j < KW; ++j) colbits |= (uint64_t)((unsigned)(x0 + j) < (unsigned)W ? 1u : 0u) << j;
       for (int i = 0; i < KH; ++i) inside |= ((unsigned)(y0 + i) < (unsigned)H ? colbits : 0ull) << (i * KW);
-      const uint64_t outside = ok ? ~inside : ~0ull;
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const uint32_t tap = (taps[u >> 2] >> (8 * (u & 3))) & 0xffu;
-        const uint32_t bad = (uint32_t)(outside >> tap) & 1u;
-        r[u] = buf_load(rs, (pix4 + qoff4[u]) | (bad << 31));
-      }
+      outside = ok ? ~inside : ~0ull;
     }
   }
+  __device__ __forceinline__ void load_one(int u, float (&r)[16]) const {
+    const uint32_t tap = (taps[u >> 2] >> (8 * (u & 3))) & 0xffu;
+    const uint32_t bad = (uint32_t)(outside >> tap) & 1u;
+    r[u] = buf_load(rs, (pix4 + qoff4[u]) | (bad << 31));
+  }
+  __device__ __forceinline__ void load(int k0, float (&r)[16]) {
+    begin(k0);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) load_one(u, r);
+  }
   __device__ __forceinline__ void store(float* lds, const float (&r)[16]) const {
-    if (tile_bias) {
+    const unsigned ones = okcur ? biasmask : 0u;
 #pragma unroll
-      for (int u = 0; u < 16; ++u)
-        lds[kl * PITCH + mg + 8 * u] = (((biasmask >> u) & 1u) && okcur) ? 1.f : r[u];
-    } else {
-#pragma unroll
-      for (int u = 0; u < 16; ++u) lds[kl * PITCH + mg + 8 * u] = r[u];
-    }
+    for (int u = 0; u < 16; ++u) lds[kl * PITCH + mg + 8 * u] = ((ones >> u) & 1u) ? 1.f : r[u];
   }
 };
 
@@ -266,34 +265,72 @@ __device__ __forceinline__ unsigned block_mask(const TileDesc& D, int bi, int bj
 constexpr int TILE_LDS_FLOATS = 4 * PANEL;
 
 // The k loop of one tile: stage panel kt+1 (global -> registers -> LDS buffer cur^1) around the
-// MFMA work on panel kt (LDS buffer cur); one barrier per k step.  Every wave of the workgroup
-// runs the same number of steps whatever its pattern.
-template <unsigned PAT, class LA, class LB>
-__device__ __forceinline__ void main_loop(LA& la, LB& lb, bool share, float* As, float* Bs, Acc4& tot,
+// MFMA work on panel kt (LDS buffer cur); one barrier per k step.  The steady-state body has no
+// branches (SHARE and PAT are compile-time), so address arithmetic, buffer loads and LDS traffic
+// can be scheduled between the MFMAs.  Every wave of the workgroup runs the same number of steps
+// whatever its pattern.
+template <unsigned PAT, bool SHARE, class LA, class LB>
+__device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, Acc4& tot,
                                           int kbeg, int nkt, int wm, int wn, int lane) {
+  if (nkt <= 0) return;
   float ra[16], rb[16];
-  if (nkt > 0) {
-    la.load(kbeg, ra);
-    if (!share) lb.load(kbeg, rb);
-    la.store(As, ra);
-    if (!share) lb.store(Bs, rb);
-  }
+  la.load(kbeg, ra);
+  if (!SHARE) lb.load(kbeg, rb);
+  la.store(As, ra);
+  if (!SHARE) lb.store(Bs, rb);
   __syncthreads();
   int cur = 0;
-  for (int kt = 0; kt < nkt; ++kt) {
-    const bool more = kt + 1 < nkt;
-    if (more) {
-      la.load(kbeg + (kt + 1) * KC, ra);
-      if (!share) lb.load(kbeg + (kt + 1) * KC, rb);
+  for (int kt = 1; kt < nkt; ++kt) {
+#ifdef KFAC_FUSED_STEP
+    la.begin(kbeg + kt * KC);
+    if (!SHARE) lb.begin(kbeg + kt * KC);
+    {
+      // one buffer load per operand is issued behind every group of MFMAs of a k step, so address
+      // arithmetic and loads run in the shadow of the matrix pipe
+      const float* ap = As + cur * PANEL + (lane >> 5) * PITCH + wm * 64 + (lane & 31);
+      const float* bp = Bs + cur * PANEL + (lane >> 5) * PITCH + wn * 64 + (lane & 31);
+      float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
+      if (PAT & 0x3) a0 = ap[0];
+      if (PAT & 0xC) a1 = ap[32];
+      if (PAT & 0x5) b0 = bp[0];
+      if (PAT & 0xA) b1 = bp[32];
+#pragma unroll
+      for (int ks = 0; ks < KC / 2; ++ks) {
+        float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+        if (ks + 1 < KC / 2) {
+          if (PAT & 0x3) na0 = ap[(ks + 1) * 2 * PITCH];
+          if (PAT & 0xC) na1 = ap[(ks + 1) * 2 * PITCH + 32];
+          if (PAT & 0x5) nb0 = bp[(ks + 1) * 2 * PITCH];
+          if (PAT & 0xA) nb1 = bp[(ks + 1) * 2 * PITCH + 32];
+        }
+        if (PAT & 1u) tot.c[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, tot.c[0], 0, 0, 0);
+        if (PAT & 2u) tot.c[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, tot.c[1], 0, 0, 0);
+        if (PAT & 4u) tot.c[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, tot.c[2], 0, 0, 0);
+        if (PAT & 8u) tot.c[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, tot.c[3], 0, 0, 0);
+        la.load_one(ks, ra);
+        if (!SHARE) lb.load_one(ks, rb);
+        __builtin_amdgcn_sched_barrier(0);
+        a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+      }
     }
+#else
+    la.load(kbeg + kt * KC, ra);
+    if (!SHARE) lb.load(kbeg + kt * KC, rb);
     mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
-    if (more) {
-      la.store(As + (cur ^ 1) * PANEL, ra);
-      if (!share) lb.store(Bs + (cur ^ 1) * PANEL, rb);
-    }
+#endif
+    la.store(As + (cur ^ 1) * PANEL, ra);
+    if (!SHARE) lb.store(Bs + (cur ^ 1) * PANEL, rb);
     __syncthreads();
     cur ^= 1;
   }
+  mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
+}
+
+template <unsigned PAT, class LA, class LB>
+__device__ __forceinline__ void main_loop_any(LA& la, LB& lb, bool share, float* As, float* Bs, Acc4& tot,
+                                              int kbeg, int nkt, int wm, int wn, int lane) {
+  if (share) main_loop<PAT, true>(la, lb, As, As, tot, kbeg, nkt, wm, wn, lane);
+  else main_loop<PAT, false>(la, lb, As, Bs, tot, kbeg, nkt, wm, wn, lane);
 }
 
 template <class LA, class LB>
@@ -340,12 +377,12 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   acc_zero(tot);
   const int nkt = (J.kend - J.kbeg + KC - 1) / KC;
   switch (cover_pattern(mask)) {
-    case PAT_FULL: main_loop<PAT_FULL>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ROW1: main_loop<PAT_ROW1>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_COL1: main_loop<PAT_COL1>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ONE: main_loop<PAT_ONE>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_TRI: main_loop<PAT_TRI>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    default: main_loop<PAT_NONE>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_FULL: main_loop_any<PAT_FULL>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ROW1: main_loop_any<PAT_ROW1>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_COL1: main_loop_any<PAT_COL1>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ONE: main_loop_any<PAT_ONE>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_TRI: main_loop_any<PAT_TRI>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    default: main_loop_any<PAT_NONE>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
   }
 
   // ---- epilogue

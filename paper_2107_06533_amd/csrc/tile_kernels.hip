@@ -42,26 +42,55 @@ __global__ __launch_bounds__(NT, 2) void tile_gemm_kernel(const TileDesc* __rest
 }
 
 // out = beta*out + alpha * (partial[part0] + partial[part0+1] + ...) in slot order (deterministic).
+// Four workgroups per tile; a thread owns four float4 pieces and keeps all their loads in flight.
 __global__ __launch_bounds__(NT) void tile_reduce_kernel(const TileDesc* __restrict__ descs,
                                                          const ReduceJob* __restrict__ jobs, int njobs) {
-  const int g = blockIdx.x;
+  const int g = blockIdx.x >> 2, quarter = blockIdx.x & 3;
   if (g >= njobs) return;
   const ReduceJob J = jobs[g];
   const TileDesc& D = descs[J.desc];
   const bool diag = D.sym && J.bi == J.bj;
   const bool mirror = D.mirror == MIRROR_ALL || (D.mirror == MIRROR_DIAG_TILE && diag);
-  const float* P = D.partial + (size_t)J.part0 * (BM * BN);
-  for (int e = threadIdx.x; e < BM * BN; e += NT) {
-    const int li = e >> 7, lj = e & (BN - 1);
-    const int gi = J.bi * BM + li, gj = J.bj * BN + lj;
-    if (gi >= D.M || gj >= D.N || (D.sym && gi < gj)) continue;
-    float s = 0.f;
-    for (int k = 0; k < J.nsplit; ++k) s += P[(size_t)k * (BM * BN) + e];
-    float* o = D.out + (size_t)gi * D.ldo + gj;
-    float val = D.alpha * s;
-    if (D.beta != 0.f) val += D.beta * *o;
-    *o = val;
-    if (mirror && gi != gj) D.out[(size_t)gj * D.ldo + gi] = val;
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  typedef const f32x4 __attribute__((address_space(1)))* gc4_ptr;
+  gc4_ptr P = (gc4_ptr)(D.partial + (size_t)J.part0 * (BM * BN));
+  const uint32_t ldo4 = (uint32_t)D.ldo * 4u;
+  const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * ldo4);
+  f32x4 acc[4];
+  float old[4][4];
+  uint32_t off[4][4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int e = (quarter * 1024 + u * NT + (int)threadIdx.x) * 4;
+    const int gi = J.bi * BM + (e >> 7);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int gj = J.bj * BN + (e & (BN - 1)) + c;
+      const bool ok = gi < D.M && gj < D.N && (!D.sym || gi >= gj);
+      off[u][c] = ok ? (uint32_t)gi * ldo4 + (uint32_t)gj * 4u : OOB_OFFSET;
+      old[u][c] = D.beta != 0.f ? buf_load(ro, off[u][c]) : 0.f;
+    }
+  }
+  for (int k = 0; k < J.nsplit; ++k) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      acc[u] += P[(size_t)k * (BM * BN / 4) + quarter * 1024 + u * NT + threadIdx.x];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const float a4[4] = {acc[u][0], acc[u][1], acc[u][2], acc[u][3]};
+    const int e = (quarter * 1024 + u * NT + (int)threadIdx.x) * 4;
+    const int gi = J.bi * BM + (e >> 7);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int gj = J.bj * BN + (e & (BN - 1)) + c;
+      const float val = D.alpha * a4[c] + D.beta * old[u][c];
+      buf_store(ro, off[u][c], val);
+      if (mirror)
+        buf_store(ro, (off[u][c] != OOB_OFFSET && gi != gj) ? (uint32_t)gj * ldo4 + (uint32_t)gi * 4u : OOB_OFFSET, val);
+    }
   }
 }
 
@@ -79,7 +108,7 @@ void launch_tile_gemm(const TileDesc* descs, const TileJob* jobs, int njobs, int
 
 void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs, hipStream_t s) {
   if (njobs <= 0) return;
-  hipLaunchKernelGGL(tile_reduce_kernel, dim3(njobs), dim3(NT), 0, s, descs, jobs, njobs);
+  hipLaunchKernelGGL(tile_reduce_kernel, dim3(njobs * 4), dim3(NT), 0, s, descs, jobs, njobs);
 }
 
 }  // namespace kfac
