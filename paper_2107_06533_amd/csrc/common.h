@@ -33,10 +33,13 @@ __host__ __device__ inline uint32_t fast_div(uint32_t n, FastDiv f) {
 // ---- tile geometry -------------------------------------------------------------------------
 constexpr int BM = 128;   // output tile rows
 constexpr int BN = 128;   // output tile columns
-constexpr int KC = 32;    // contraction depth staged in LDS per step
+#ifndef KFAC_KC
+#define KFAC_KC 32
+#endif
+constexpr int KC = KFAC_KC;    // contraction depth staged in LDS per step
 constexpr int NT = 256;   // threads per workgroup (4 wavefronts, 2x2, 64x64 outputs each)
-constexpr int PITCH = 129;              // LDS row pitch in floats (odd: conflict-free column writes)
-constexpr int PANEL = KC * PITCH;       // floats of one staged operand panel
+constexpr int PK = KC + 4;                // LDS row pitch in floats: one row per operand column, 16-byte aligned
+constexpr int PANEL = BM * PK;            // floats of one staged operand panel
 constexpr int MAX_JOB_ROWS = 8192;       // longest run one job accumulates in its fp32 accumulator
 
 // ---- a GEMM operand seen as a [K x M] matrix, k = contraction index ------------------------

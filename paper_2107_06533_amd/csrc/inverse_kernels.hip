@@ -164,7 +164,7 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
   const int kb = d - k0 < NB ? d - k0 : NB;
   const bool above = it < step;
   const int ml = t & 127, kp = t >> 7;   // row-contiguous mapping
-  const int kl = t & 31, mg = t >> 5;    // column-contiguous mapping
+  const int kl = t & (KC - 1), mg = t / KC;    // column-contiguous mapping
 
   unsigned mask = 0;
 #pragma unroll
@@ -178,36 +178,36 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
   Acc4 acc;
   acc_zero(acc);
   for (int kk0 = 0; kk0 < NB; kk0 += KC) {
-    float rq[16], rz[16];
+    float rq[NU], rz[NU];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) rq[u] = Mx.Q[(kk0 + kp + 2 * u) * NB + ml];
+    for (int u = 0; u < NU; ++u) rq[u] = Mx.Q[(kk0 + kp + 2 * u) * NB + ml];
     if (above) {
 #pragma unroll
-      for (int u = 0; u < 16; ++u) {
+      for (int u = 0; u < NU; ++u) {
         const int kk = kk0 + kp + 2 * u;
         rz[u] = (kk < kb) ? Mx.X[(size_t)(k0 + kk) * d + i0 + ml] : 0.f;
       }
     } else {
       const int kk = kk0 + kl;
 #pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int i = i0 + mg + 8 * u;
+      for (int u = 0; u < NU; ++u) {
+        const int i = i0 + mg + MG * u;
         rz[u] = (kk < kb && i < d) ? Mx.X[(size_t)i * d + k0 + kk] : 0.f;
       }
     }
     __syncthreads();   // previous chunk fully consumed
 #pragma unroll
-    for (int u = 0; u < 16; ++u) Qs[(kp + 2 * u) * PITCH + ml] = rq[u];
+    for (int u = 0; u < NU; ++u) Qs[lds_idx(ml, kp + 2 * u)] = rq[u];
     if (above) {
 #pragma unroll
-      for (int u = 0; u < 16; ++u) Zs[(kp + 2 * u) * PITCH + ml] = rz[u];
+      for (int u = 0; u < NU; ++u) Zs[lds_idx(ml, kp + 2 * u)] = rz[u];
     } else {
 #pragma unroll
-      for (int u = 0; u < 16; ++u) Zs[kl * PITCH + mg + 8 * u] = rz[u];
+      for (int u = 0; u < NU; ++u) Zs[lds_idx(mg + MG * u, kl)] = rz[u];
     }
     __syncthreads();
 #pragma unroll
-    for (int u = 0; u < 16; ++u) Mx.Zt[(size_t)(kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[(kp + 2 * u) * PITCH + ml];
+    for (int u = 0; u < NU; ++u) Mx.Zt[(size_t)(kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[lds_idx(ml, kp + 2 * u)];
     switch (pat) {
       case PAT_FULL: mma_ktile<PAT_FULL>(Qs, Zs, acc, wm, wn, lane); break;
       case PAT_ROW1: mma_ktile<PAT_ROW1>(Qs, Zs, acc, wm, wn, lane); break;

@@ -318,6 +318,37 @@ int active_blocks(int M, int N, int bi, int bj, bool sym) {
   return c;
 }
 
+// XCD-aware arrangement of a grouped launch.  Workgroup g runs on XCD g % 8 (each XCD has its own
+// L2) and the kernels map it to job (g % 8) * ceil(n / 8) + g / 8, i.e. XCD x walks segment x of the
+// list in order.  Every group (one layer / one matrix, jobs in locality order, heaviest groups first)
+// is cut into 8 contiguous pieces, one per XCD: the XCDs get equal work, and the jobs that run
+// together on one XCD are neighbouring tiles of the same operand, which they then share in L2.
+// Segments are padded to equal length with no-op jobs (desc = -1).
+std::vector<TileJob> xcd_arrange(const std::vector<std::vector<TileJob>>& groups) {
+  std::vector<TileJob> seg[8];
+  for (const auto& g : groups) {
+    const size_t L = g.size();
+    for (int x = 0; x < 8; ++x)
+      for (size_t i = x * L / 8; i < (x + 1) * L / 8; ++i) seg[x].push_back(g[i]);
+  }
+  size_t per = 0;
+  for (int x = 0; x < 8; ++x) per = std::max(per, seg[x].size());
+  TileJob nop{};
+  nop.desc = -1;
+  std::vector<TileJob> out;
+  out.reserve(per * 8);
+  for (int x = 0; x < 8; ++x) {
+    out.insert(out.end(), seg[x].begin(), seg[x].end());
+    out.insert(out.end(), per - seg[x].size(), nop);
+  }
+  return out;
+}
+
+bool xcd_enabled() {
+  static const bool on = !(std::getenv("KFAC_XCD") && std::atoi(std::getenv("KFAC_XCD")) == 0);
+  return on;
+}
+
 // ------------------------------------------------------------------------------- factor plan
 void release(FactorPlan& p) {
   free_dev(p.d_jobs); free_dev(p.d_rjobs); free_table(p.tab);
@@ -358,39 +389,51 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
       S.desc_of[2 * l + which] = int(S.descs.size());
       S.descs.push_back(D);
     }
-  struct Tmp { TileJob j; int64_t cost; };
-  std::vector<Tmp> tmp;
+  struct Group { std::vector<TileJob> jobs; int64_t job_cost; };
+  std::vector<Group> groups;
   for (size_t di = 0; di < S.descs.size(); ++di) {
     const TileDesc& D = S.descs[di];
     const int d = D.M, R = D.a.K, T = ceil_div(d, BM);
     int nsplit = ceil_div(R, kjob);
     int chunk = ceil_div(ceil_div(R, nsplit), KC) * KC;
     nsplit = ceil_div(R, chunk);
-    for (int bi = 0; bi < T; ++bi)
-      for (int bj = 0; bj <= bi; ++bj) {
-        const int ab = active_blocks(d, d, bi, bj, true);
-        if (nsplit > 1) {
-          ReduceJob rj{};
-          rj.desc = int(di); rj.bi = bi; rj.bj = bj; rj.part0 = int(S.nslots); rj.nsplit = nsplit;
-          S.rjobs.push_back(rj);
-          S.stats.n_split++;
-        }
-        for (int s = 0; s < nsplit; ++s) {
+    const int ntile = T * (T + 1) / 2;
+    const size_t slot0 = S.nslots;
+    if (nsplit > 1) S.nslots += size_t(ntile) * nsplit;
+    Group G;
+    G.job_cost = int64_t(std::min(R, chunk)) * 16;
+    // row chunk outermost: the jobs that run side by side read the same rows of the activations
+    for (int sidx = 0; sidx < nsplit; ++sidx) {
+      int tile = 0;
+      for (int bi = 0; bi < T; ++bi)
+        for (int bj = 0; bj <= bi; ++bj, ++tile) {
+          const int ab = active_blocks(d, d, bi, bj, true);
+          if (nsplit > 1 && sidx == 0) {
+            ReduceJob rj{};
+            rj.desc = int(di); rj.bi = bi; rj.bj = bj; rj.part0 = int(slot0 + size_t(tile) * nsplit); rj.nsplit = nsplit;
+            S.rjobs.push_back(rj);
+            S.stats.n_split++;
+          }
           TileJob j{};
           j.desc = int(di); j.bi = bi; j.bj = bj;
-          j.kbeg = s * chunk; j.kend = std::min(R, (s + 1) * chunk);
-          j.part = nsplit > 1 ? int(S.nslots++) : -1;
-          const int64_t c = int64_t(j.kend - j.kbeg) * ab;
-          tmp.push_back({j, c});
-          S.stats.mfma_flops += c * 32 * 32 * 2;
+          j.kbeg = sidx * chunk; j.kend = std::min(R, (sidx + 1) * chunk);
+          j.part = nsplit > 1 ? int(slot0 + size_t(tile) * nsplit + sidx) : -1;
+          G.jobs.push_back(j);
+          S.stats.mfma_flops += int64_t(j.kend - j.kbeg) * ab * 32 * 32 * 2;
         }
-      }
+    }
+    groups.push_back(std::move(G));
   }
-  // longest jobs first: the hardware dispatches workgroups in index order, so this is the
-  // list-scheduling (largest-first) rule applied to compute units
-  std::stable_sort(tmp.begin(), tmp.end(), [](const Tmp& x, const Tmp& y) { return x.cost > y.cost; });
-  S.jobs.reserve(tmp.size());
-  for (auto& t : tmp) S.jobs.push_back(t.j);
+  // longest jobs first: workgroups are dispatched in index order, so this is the list-scheduling
+  // (largest-first) rule applied to compute units
+  std::stable_sort(groups.begin(), groups.end(), [](const Group& x, const Group& y) { return x.job_cost > y.job_cost; });
+  std::vector<std::vector<TileJob>> lists;
+  for (auto& g : groups) lists.push_back(std::move(g.jobs));
+  if (xcd_enabled()) {
+    S.jobs = xcd_arrange(lists);
+  } else {
+    for (auto& l : lists) S.jobs.insert(S.jobs.end(), l.begin(), l.end());
+  }
   S.stats.n_jobs = int64_t(S.jobs.size() + S.rjobs.size());
   S.stats.n_launches = 1 + (S.rjobs.empty() ? 0 : 1);
   S.stats.ws_bytes = int64_t(S.nslots * size_t(BM) * BN * sizeof(float));
@@ -696,7 +739,7 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
   const TileDesc* d_descs = static_cast<const TileDesc*>(P.tab.dev);
   {
     ScopedTiming tm(ctx, KFAC_K_FACTOR_TILES, s);
-    launch_tile_any(d_descs, static_cast<const TileJob*>(P.d_jobs), P.njobs, 0, s);
+    launch_tile_any(d_descs, static_cast<const TileJob*>(P.d_jobs), P.njobs, xcd_enabled() ? 1 : 0, s);
   }
   if (P.nrjobs) {
     ScopedTiming tm(ctx, KFAC_K_FACTOR_REDUCE, s);

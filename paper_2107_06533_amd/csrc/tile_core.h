@@ -3,9 +3,12 @@
 //
 // One workgroup of 256 threads (4 wavefronts as 2x2, 64x64 outputs each, built from
 // v_mfma_f32_32x32x2_f32 blocks) computes  acc[i][j] = sum_k a(k, i0+i) * b(k, j0+j)
-// over a k-range.  Operands are staged as [k][m] panels in LDS (double-buffered, one
-// barrier per 32-deep k step); the next panel's global loads are in flight while the
-// current one is multiplied.  One job accumulates at most MAX_JOB_ROWS contraction rows in
+// over a k-range.  Operands are staged in LDS as [m][k] panels (double-buffered, one barrier
+// per 32-deep k step) with k permuted inside groups of 8 so that the four values a lane feeds to
+// four consecutive MFMAs are one 16-byte LDS read; the next panel's global loads are in flight
+// while the current one is multiplied.  fp32 MFMA shares the vector ALUs (it does not overlap
+// with VALU instructions of any wave on the SIMD), so the k loop is written to need as few
+// VALU instructions per MFMA as possible.  One job accumulates at most MAX_JOB_ROWS contraction rows in
 // its fp32 MFMA accumulator; longer reductions (ReLU activations over 10^5 rows are sums of
 // non-negative products, whose rounding error grows with the run length) are split into
 // several jobs whose partial tiles are added in a fixed order by the reduce kernel.
@@ -17,6 +20,16 @@
 namespace kfac {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Position of contraction index k inside an LDS row: MFMA lane half h = k & 1 reads the four
+// values k = 8g + 2s + h, s = 0..3, which sit at 8g + 4h + s.
+__host__ __device__ constexpr int lds_pos(int k) { return (k & ~7) | ((k & 1) << 2) | ((k >> 1) & 3); }
+__host__ __device__ constexpr int lds_idx(int m, int k) { return m * PK + lds_pos(k); }
+
+constexpr int NU = KC / 2;        // elements of one operand panel a thread moves per k step (KC*128/256)
+constexpr int MG = NT / KC;       // column groups of the k-contiguous thread mapping
 
 struct Acc4 {
   f32x16 c[4];   // block (a, b) of the wave's 2x2 grid of 32x32 blocks at index a*2+b
@@ -37,7 +50,7 @@ __device__ __forceinline__ void acc_add(Acc4& t, const Acc4& x) {
 // ------------------------------------------------------------------------------ loaders
 // Each loader owns the per-thread part of moving one [KC x 128] operand panel:
 //   load(k0, r)  : global -> 16 registers (out-of-range elements read 0)
-//   store(lds, r): registers -> LDS panel laid out [k][m] with row pitch PITCH
+//   store(lds, r): registers -> LDS panel laid out [m][lds_pos(k)] with row pitch PK
 
 // Pointers that live in descriptor tables reach the kernels as generic pointers; casting them to
 // the global address space lets the compiler emit global_load / global_store (vmcnt only).  A
@@ -93,18 +106,25 @@ struct KMajorLoader {
     kcur = k0;
     base = (uint32_t)(k0 + kp) * ld4 + moff;   // stays >= OOB_OFFSET for invalid columns
   }
-  __device__ __forceinline__ void load_one(int u, float (&r)[16]) const {
+  __device__ __forceinline__ void load_one(int u, float (&r)[NU]) const {
     r[u] = buf_load(rs, base + (uint32_t)(2 * u) * ld4);
   }
-  __device__ __forceinline__ void load(int k0, float (&r)[16]) {
+  __device__ __forceinline__ void load(int k0, float (&r)[NU]) {
     begin(k0);
 #pragma unroll
-    for (int u = 0; u < 16; ++u) load_one(u, r);
+    for (int u = 0; u < NU; ++u) load_one(u, r);
   }
-  __device__ __forceinline__ void store(float* lds, const float (&r)[16]) const {
+  __device__ __forceinline__ void store(float* lds, const float (&r)[NU]) const {
+    // rows kp + 2u, u = 4g .. 4g+3, are the contiguous positions 8g + 4kp .. +3 of row ml
 #pragma unroll
-    for (int u = 0; u < 16; ++u)
-      lds[(kp + 2 * u) * PITCH + ml] = (isbias && kcur + kp + 2 * u < kend) ? 1.f : r[u];
+    for (int g = 0; g < NU / 4; ++g)
+      *reinterpret_cast<f32x4*>(lds + ml * PK + 8 * g + 4 * kp) = f32x4{r[4 * g], r[4 * g + 1], r[4 * g + 2], r[4 * g + 3]};
+    if (tile_bias) {   // the ones column lives in one thread column of one tile per operand
+      if (isbias) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) lds[lds_idx(ml, kp + 2 * u)] = (kcur + kp + 2 * u < kend) ? 1.f : 0.f;
+      }
+    }
   }
 };
 
@@ -121,8 +141,8 @@ struct ConvLoader {
   static constexpr bool TAP64 = (KH_ * KW_ == 0) || (KH_ * KW_ > 31);
   static constexpr int TAP_NEVER = TAP64 ? 63 : 31;
   rsrc_t rs;
-  uint32_t qoff4[16];
-  uint32_t taps[4];      // 8 bits per column
+  uint32_t qoff4[NU];
+  uint32_t taps[(NU + 3) / 4];      // 8 bits per column
   uint32_t CHW4, pix4;
   typename std::conditional<TAP64, uint64_t, uint32_t>::type outside;
   int kend, H, W, OHW, OW, stride, pad, KH, KW, kl, mg;
@@ -133,16 +153,16 @@ struct ConvLoader {
   __device__ __forceinline__ void init(const Operand& op, int m0, int kend_, int t) {
     KH = KH_ ? KH_ : op.KH;
     KW = KW_ ? KW_ : op.KW;
-    kl = t & 31;
-    mg = t >> 5;
+    kl = t & (KC - 1);
+    mg = t / KC;
     const int mreal = op.M - op.bias;
     tile_bias = op.bias && m0 + BM > mreal && m0 <= mreal;
     biasmask = 0;
 #pragma unroll
-    for (int w4 = 0; w4 < 4; ++w4) taps[w4] = 0;
+    for (int w4 = 0; w4 < (NU + 3) / 4; ++w4) taps[w4] = 0;
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int m = m0 + mg + 8 * u;
+    for (int u = 0; u < NU; ++u) {
+      const int m = m0 + mg + MG * u;
       uint32_t off = 0, tap = TAP_NEVER;
       if (m < mreal) {
         const int c = m / (KH * KW);
@@ -189,20 +209,25 @@ struct ConvLoader {
       outside = ok ? ~inside : ~0ull;
     }
   }
-  __device__ __forceinline__ void load_one(int u, float (&r)[16]) const {
+  __device__ __forceinline__ void load_one(int u, float (&r)[NU]) const {
     const uint32_t tap = (taps[u >> 2] >> (8 * (u & 3))) & 0xffu;
     const uint32_t bad = (uint32_t)(outside >> tap) & 1u;
     r[u] = buf_load(rs, (pix4 + qoff4[u]) | (bad << 31));
   }
-  __device__ __forceinline__ void load(int k0, float (&r)[16]) {
+  __device__ __forceinline__ void load(int k0, float (&r)[NU]) {
     begin(k0);
 #pragma unroll
-    for (int u = 0; u < 16; ++u) load_one(u, r);
+    for (int u = 0; u < NU; ++u) load_one(u, r);
   }
-  __device__ __forceinline__ void store(float* lds, const float (&r)[16]) const {
-    const unsigned ones = okcur ? biasmask : 0u;
+  __device__ __forceinline__ void store(float* lds, const float (&r)[NU]) const {
+    const int pk = lds_pos(kl);
 #pragma unroll
-    for (int u = 0; u < 16; ++u) lds[kl * PITCH + mg + 8 * u] = ((ones >> u) & 1u) ? 1.f : r[u];
+    for (int u = 0; u < NU; ++u) lds[(mg + MG * u) * PK + pk] = r[u];
+    if (tile_bias) {
+#pragma unroll
+      for (int u = 0; u < NU; ++u)
+        if ((biasmask >> u) & 1u) lds[(mg + MG * u) * PK + pk] = okcur ? 1.f : 0.f;
+    }
   }
 };
 
@@ -216,19 +241,32 @@ template <unsigned PAT>
 __device__ __forceinline__ void mma_ktile(const float* __restrict__ As, const float* __restrict__ Bs,
                                           Acc4& acc, int wm, int wn, int lane) {
   if (PAT == PAT_NONE) return;
-  const float* ap = As + (lane >> 5) * PITCH + wm * 64 + (lane & 31);
-  const float* bp = Bs + (lane >> 5) * PITCH + wn * 64 + (lane & 31);
+  // lane l feeds a(k, i = l%32) and b(k, j = l%32) with k = 8g + 2s + l/32 for MFMA s of group g
+  const float* ap = As + (wm * 64 + (lane & 31)) * PK + 4 * (lane >> 5);
+  const float* bp = Bs + (wn * 64 + (lane & 31)) * PK + 4 * (lane >> 5);
+  const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+  f32x4 a0 = z, a1 = z, b0 = z, b1 = z;
+  if (PAT & 0x3) a0 = *reinterpret_cast<const f32x4*>(ap);
+  if (PAT & 0xC) a1 = *reinterpret_cast<const f32x4*>(ap + 32 * PK);
+  if (PAT & 0x5) b0 = *reinterpret_cast<const f32x4*>(bp);
+  if (PAT & 0xA) b1 = *reinterpret_cast<const f32x4*>(bp + 32 * PK);
 #pragma unroll
-  for (int ks = 0; ks < KC / 2; ++ks) {
-    float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
-    if (PAT & 0x3) a0 = ap[ks * 2 * PITCH];
-    if (PAT & 0xC) a1 = ap[ks * 2 * PITCH + 32];
-    if (PAT & 0x5) b0 = bp[ks * 2 * PITCH];
-    if (PAT & 0xA) b1 = bp[ks * 2 * PITCH + 32];
-    if (PAT & 1u) acc.c[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc.c[0], 0, 0, 0);
-    if (PAT & 2u) acc.c[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc.c[1], 0, 0, 0);
-    if (PAT & 4u) acc.c[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc.c[2], 0, 0, 0);
-    if (PAT & 8u) acc.c[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc.c[3], 0, 0, 0);
+  for (int g = 0; g < KC / 8; ++g) {
+    f32x4 na0 = z, na1 = z, nb0 = z, nb1 = z;
+    if (g + 1 < KC / 8) {   // next group's fragments are requested before this group's MFMAs
+      if (PAT & 0x3) na0 = *reinterpret_cast<const f32x4*>(ap + 8 * (g + 1));
+      if (PAT & 0xC) na1 = *reinterpret_cast<const f32x4*>(ap + 32 * PK + 8 * (g + 1));
+      if (PAT & 0x5) nb0 = *reinterpret_cast<const f32x4*>(bp + 8 * (g + 1));
+      if (PAT & 0xA) nb1 = *reinterpret_cast<const f32x4*>(bp + 32 * PK + 8 * (g + 1));
+    }
+#pragma unroll
+    for (int sidx = 0; sidx < 4; ++sidx) {
+      if (PAT & 1u) acc.c[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[sidx], b0[sidx], acc.c[0], 0, 0, 0);
+      if (PAT & 2u) acc.c[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[sidx], b1[sidx], acc.c[1], 0, 0, 0);
+      if (PAT & 4u) acc.c[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[sidx], b0[sidx], acc.c[2], 0, 0, 0);
+      if (PAT & 8u) acc.c[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[sidx], b1[sidx], acc.c[3], 0, 0, 0);
+    }
+    a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
   }
 }
 
@@ -273,7 +311,7 @@ template <unsigned PAT, bool SHARE, class LA, class LB>
 __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, Acc4& tot,
                                           int kbeg, int nkt, int wm, int wn, int lane) {
   if (nkt <= 0) return;
-  float ra[16], rb[16];
+  float ra[NU], rb[NU];
   la.load(kbeg, ra);
   if (!SHARE) lb.load(kbeg, rb);
   la.store(As, ra);
@@ -281,38 +319,23 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
   __syncthreads();
   int cur = 0;
   for (int kt = 1; kt < nkt; ++kt) {
-#ifdef KFAC_FUSED_STEP
-    la.begin(kbeg + kt * KC);
-    if (!SHARE) lb.begin(kbeg + kt * KC);
-    {
-      // one buffer load per operand is issued behind every group of MFMAs of a k step, so address
-      // arithmetic and loads run in the shadow of the matrix pipe
-      const float* ap = As + cur * PANEL + (lane >> 5) * PITCH + wm * 64 + (lane & 31);
-      const float* bp = Bs + cur * PANEL + (lane >> 5) * PITCH + wn * 64 + (lane & 31);
-      float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
-      if (PAT & 0x3) a0 = ap[0];
-      if (PAT & 0xC) a1 = ap[32];
-      if (PAT & 0x5) b0 = bp[0];
-      if (PAT & 0xA) b1 = bp[32];
-#pragma unroll
-      for (int ks = 0; ks < KC / 2; ++ks) {
-        float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
-        if (ks + 1 < KC / 2) {
-          if (PAT & 0x3) na0 = ap[(ks + 1) * 2 * PITCH];
-          if (PAT & 0xC) na1 = ap[(ks + 1) * 2 * PITCH + 32];
-          if (PAT & 0x5) nb0 = bp[(ks + 1) * 2 * PITCH];
-          if (PAT & 0xA) nb1 = bp[(ks + 1) * 2 * PITCH + 32];
-        }
-        if (PAT & 1u) tot.c[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, tot.c[0], 0, 0, 0);
-        if (PAT & 2u) tot.c[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, tot.c[1], 0, 0, 0);
-        if (PAT & 4u) tot.c[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, tot.c[2], 0, 0, 0);
-        if (PAT & 8u) tot.c[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, tot.c[3], 0, 0, 0);
-        la.load_one(ks, ra);
-        if (!SHARE) lb.load_one(ks, rb);
-        __builtin_amdgcn_sched_barrier(0);
-        a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
-      }
-    }
+#if defined(KFAC_EXP)
+    // timing experiments only (results are wrong): 1 = no global loads / LDS stores, 2 = also no
+    // barrier, 3 = loads, stores and barrier but no MFMA work
+#if KFAC_EXP == 1 || KFAC_EXP == 2
+    mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
+#if KFAC_EXP == 1
+    __syncthreads();
+#endif
+#else
+    la.load(kbeg + kt * KC, ra);
+    if (!SHARE) lb.load(kbeg + kt * KC, rb);
+    la.store(As + (cur ^ 1) * PANEL, ra);
+    if (!SHARE) lb.store(Bs + (cur ^ 1) * PANEL, rb);
+    __syncthreads();
+#endif
+    cur ^= 1;
+    continue;
 #else
     la.load(kbeg + kt * KC, ra);
     if (!SHARE) lb.load(kbeg + kt * KC, rb);
@@ -333,7 +356,9 @@ __device__ __forceinline__ void main_loop_any(LA& la, LB& lb, bool share, float*
   else main_loop<PAT, false>(la, lb, As, Bs, tot, kbeg, nkt, wm, wn, lane);
 }
 
-template <class LA, class LB>
+// PREFETCH_OLD: fetch the old output values before the k loop (worth 64 registers when the k loop is
+// short, as in the rank-128 sweep updates) instead of after it.
+template <class LA, class LB, bool PREFETCH_OLD = false>
 __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, float* smem) {
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int i0 = J.bi * BM, j0 = J.bj * BN;
@@ -366,7 +391,7 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   // latency is covered by the MFMA work; they are all in registers before anything is stored.
   Acc4 old;
   acc_zero(old);
-  if (direct && beta != 0.f) {
+  if (PREFETCH_OLD && direct && beta != 0.f) {
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd)
 #pragma unroll
@@ -398,6 +423,12 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
     return;
   }
   const bool mirror = D.mirror == MIRROR_ALL || (D.mirror == MIRROR_DIAG_TILE && diag);
+  if (!PREFETCH_OLD && beta != 0.f) {
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) old.c[qd][v] = buf_load(ro, out_offset(qd, v));
+  }
 #pragma unroll
   for (int qd = 0; qd < 4; ++qd) {
 #pragma unroll

@@ -13,7 +13,10 @@ __device__ __forceinline__ int xcd_job_index(int g, int n) {
   return (g & 7) * per + (g >> 3);
 }
 
-__global__ __launch_bounds__(NT, 2) void tile_any_kernel(const TileDesc* __restrict__ descs,
+#ifndef KFAC_WAVES
+#define KFAC_WAVES 2
+#endif
+__global__ __launch_bounds__(NT, KFAC_WAVES) void tile_any_kernel(const TileDesc* __restrict__ descs,
                                                          const TileJob* __restrict__ jobs, int njobs,
                                                          int xcd_order) {
   __shared__ float smem[TILE_LDS_FLOATS];
@@ -21,6 +24,7 @@ __global__ __launch_bounds__(NT, 2) void tile_any_kernel(const TileDesc* __restr
   if (xcd_order) g = xcd_job_index(g, njobs);
   if (g >= njobs) return;
   const TileJob J = jobs[g];
+  if (J.desc < 0) return;   // padding of an XCD segment
   const TileDesc& D = descs[J.desc];
   run_tile_any(D, J, smem);
 }
@@ -34,11 +38,12 @@ __global__ __launch_bounds__(NT, 2) void tile_gemm_kernel(const TileDesc* __rest
   if (xcd_order) g = xcd_job_index(g, njobs);
   if (g >= njobs) return;
   const TileJob J = jobs[g];
+  if (J.desc < 0) return;   // padding of an XCD segment
   const TileDesc& D = descs[J.desc];
   if (D.a.type == OP_KMAJOR)
-    run_tile<KMajorLoader, KMajorLoader>(D, J, smem);
+    run_tile<KMajorLoader, KMajorLoader, true>(D, J, smem);
   else
-    run_tile<ConvLoader<1, 1>, KMajorLoader>(D, J, smem);
+    run_tile<ConvLoader<1, 1>, KMajorLoader, true>(D, J, smem);
 }
 
 // out = beta*out + alpha * (partial[part0] + partial[part0+1] + ...) in slot order (deterministic).
