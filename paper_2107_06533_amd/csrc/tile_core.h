@@ -109,6 +109,14 @@ struct KMajorLoader {
   __device__ __forceinline__ void load_one(int u, float (&r)[NU]) const {
     r[u] = buf_load(rs, base + (uint32_t)(2 * u) * ld4);
   }
+  // Both operands of a symmetric product read the same matrix: reuse its resource and row state.
+  __device__ __forceinline__ void share_geometry(const KMajorLoader& o) { rs = o.rs; ld4 = o.ld4; kend = o.kend; }
+  __device__ __forceinline__ void load_shared(const KMajorLoader& o, float (&r)[NU]) {
+    kcur = o.kcur;
+    base = o.base - o.moff + moff;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) load_one(u, r);
+  }
   __device__ __forceinline__ void load(int k0, float (&r)[NU]) {
     begin(k0);
 #pragma unroll
@@ -209,6 +217,17 @@ struct ConvLoader {
       outside = ok ? ~inside : ~0ull;
     }
   }
+  // Both operands of a symmetric product read the same tensor: the geometry and the per-step pixel
+  // decomposition (window origin, outside-tap mask) are computed once and shared.
+  __device__ __forceinline__ void share_geometry(const ConvLoader& o) {
+    rs = o.rs; CHW4 = o.CHW4; kend = o.kend; H = o.H; W = o.W; OHW = o.OHW; OW = o.OW;
+    stride = o.stride; pad = o.pad; KH = o.KH; KW = o.KW; dOW = o.dOW; dOHW = o.dOHW;
+  }
+  __device__ __forceinline__ void load_shared(const ConvLoader& o, float (&r)[NU]) {
+    okcur = o.okcur; pix4 = o.pix4; outside = o.outside;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) load_one(u, r);
+  }
   __device__ __forceinline__ void load_one(int u, float (&r)[NU]) const {
     const uint32_t tap = (taps[u >> 2] >> (8 * (u & 3))) & 0xffu;
     const uint32_t bad = (uint32_t)(outside >> tap) & 1u;
@@ -307,13 +326,21 @@ constexpr int TILE_LDS_FLOATS = 4 * PANEL;
 // branches (SHARE and PAT are compile-time), so address arithmetic, buffer loads and LDS traffic
 // can be scheduled between the MFMAs.  Every wave of the workgroup runs the same number of steps
 // whatever its pattern.
-template <unsigned PAT, bool SHARE, class LA, class LB>
+// SAME: both operands view the same tensor (symmetric products), so loader b reuses loader a's
+// per-step state; SHARE: additionally the same columns (diagonal tile), one panel is staged.
+template <class LA, class LB, bool SAME>
+__device__ __forceinline__ void load_b(LA& la, LB& lb, int k0, float (&rb)[NU]) {
+  if constexpr (SAME && std::is_same<LA, LB>::value) lb.load_shared(la, rb);
+  else lb.load(k0, rb);
+}
+
+template <unsigned PAT, bool SHARE, bool SAME, class LA, class LB>
 __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, Acc4& tot,
                                           int kbeg, int nkt, int wm, int wn, int lane) {
   if (nkt <= 0) return;
   float ra[NU], rb[NU];
   la.load(kbeg, ra);
-  if (!SHARE) lb.load(kbeg, rb);
+  if (!SHARE) load_b<LA, LB, SAME>(la, lb, kbeg, rb);
   la.store(As, ra);
   if (!SHARE) lb.store(Bs, rb);
   __syncthreads();
@@ -329,7 +356,7 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
 #endif
 #else
     la.load(kbeg + kt * KC, ra);
-    if (!SHARE) lb.load(kbeg + kt * KC, rb);
+    if (!SHARE) load_b<LA, LB, SAME>(la, lb, kbeg + kt * KC, rb);
     la.store(As + (cur ^ 1) * PANEL, ra);
     if (!SHARE) lb.store(Bs + (cur ^ 1) * PANEL, rb);
     __syncthreads();
@@ -338,7 +365,7 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
     continue;
 #else
     la.load(kbeg + kt * KC, ra);
-    if (!SHARE) lb.load(kbeg + kt * KC, rb);
+    if (!SHARE) load_b<LA, LB, SAME>(la, lb, kbeg + kt * KC, rb);
     mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
 #endif
     la.store(As + (cur ^ 1) * PANEL, ra);
@@ -349,28 +376,30 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
   mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
 }
 
-template <unsigned PAT, class LA, class LB>
+template <unsigned PAT, bool SAME, class LA, class LB>
 __device__ __forceinline__ void main_loop_any(LA& la, LB& lb, bool share, float* As, float* Bs, Acc4& tot,
                                               int kbeg, int nkt, int wm, int wn, int lane) {
-  if (share) main_loop<PAT, true>(la, lb, As, As, tot, kbeg, nkt, wm, wn, lane);
-  else main_loop<PAT, false>(la, lb, As, Bs, tot, kbeg, nkt, wm, wn, lane);
+  if (SAME && share) main_loop<PAT, true, true>(la, lb, As, As, tot, kbeg, nkt, wm, wn, lane);
+  else main_loop<PAT, false, SAME>(la, lb, As, Bs, tot, kbeg, nkt, wm, wn, lane);
 }
 
 // PREFETCH_OLD: fetch the old output values before the k loop (worth 64 registers when the k loop is
 // short, as in the rank-128 sweep updates) instead of after it.
-template <class LA, class LB, bool PREFETCH_OLD = false>
+// SAME: the descriptor's two operands are the same tensor (every factor build).
+template <class LA, class LB, bool PREFETCH_OLD = false, bool SAME = false>
 __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, float* smem) {
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int i0 = J.bi * BM, j0 = J.bj * BN;
   const bool diag = D.sym && (J.bi == J.bj);
-  const bool share = diag && D.a.ptr == D.b.ptr;   // a == b on a diagonal tile: stage one panel only
+  const bool share = SAME && diag;   // a == b on a diagonal tile: stage one panel only
   float* As = smem;
   float* Bs = share ? As : smem + 2 * PANEL;
 
   LA la;
   LB lb;
   la.init(D.a, i0, J.kend, t);
-  lb.init(D.b, j0, J.kend, t);
+  lb.init(SAME ? D.a : D.b, j0, J.kend, t);
+  if constexpr (SAME && std::is_same<LA, LB>::value) lb.share_geometry(la);
 
   const unsigned mask = block_mask(D, J.bi, J.bj, wm, wn);
 
@@ -402,12 +431,12 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   acc_zero(tot);
   const int nkt = (J.kend - J.kbeg + KC - 1) / KC;
   switch (cover_pattern(mask)) {
-    case PAT_FULL: main_loop_any<PAT_FULL>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ROW1: main_loop_any<PAT_ROW1>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_COL1: main_loop_any<PAT_COL1>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ONE: main_loop_any<PAT_ONE>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_TRI: main_loop_any<PAT_TRI>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    default: main_loop_any<PAT_NONE>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_FULL: main_loop_any<PAT_FULL, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ROW1: main_loop_any<PAT_ROW1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_COL1: main_loop_any<PAT_COL1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ONE: main_loop_any<PAT_ONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_TRI: main_loop_any<PAT_TRI, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    default: main_loop_any<PAT_NONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
   }
 
   // ---- epilogue
@@ -445,15 +474,14 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   }
 }
 
-// Dispatch on the operand pair of a descriptor (wave-uniform).
-__device__ __forceinline__ void run_tile_any(const TileDesc& D, const TileJob& J, float* smem) {
-  const int ta = D.a.type, tb = D.b.type;
-  if (ta == OP_KMAJOR && tb == OP_KMAJOR) run_tile<KMajorLoader, KMajorLoader>(D, J, smem);
-  else if (ta == OP_CONV11 && tb == OP_CONV11) run_tile<ConvLoader<1, 1>, ConvLoader<1, 1>>(D, J, smem);
-  else if (ta == OP_CONV33 && tb == OP_CONV33) run_tile<ConvLoader<3, 3>, ConvLoader<3, 3>>(D, J, smem);
-  else if (ta == OP_CONV77 && tb == OP_CONV77) run_tile<ConvLoader<7, 7>, ConvLoader<7, 7>>(D, J, smem);
-  else if (ta == OP_CONV11 && tb == OP_KMAJOR) run_tile<ConvLoader<1, 1>, KMajorLoader>(D, J, smem);
-  else run_tile<ConvLoader<0, 0>, ConvLoader<0, 0>>(D, J, smem);
+// Dispatch on the operand type of a symmetric product a^T a (wave-uniform).
+__device__ __forceinline__ void run_tile_sym(const TileDesc& D, const TileJob& J, float* smem) {
+  const int ta = D.a.type;
+  if (ta == OP_KMAJOR) run_tile<KMajorLoader, KMajorLoader, false, true>(D, J, smem);
+  else if (ta == OP_CONV11) run_tile<ConvLoader<1, 1>, ConvLoader<1, 1>, false, true>(D, J, smem);
+  else if (ta == OP_CONV33) run_tile<ConvLoader<3, 3>, ConvLoader<3, 3>, false, true>(D, J, smem);
+  else if (ta == OP_CONV77) run_tile<ConvLoader<7, 7>, ConvLoader<7, 7>, false, true>(D, J, smem);
+  else run_tile<ConvLoader<0, 0>, ConvLoader<0, 0>, false, true>(D, J, smem);
 }
 
 }  // namespace kfac

@@ -26,7 +26,7 @@ __global__ __launch_bounds__(NT, KFAC_WAVES) void tile_any_kernel(const TileDesc
   const TileJob J = jobs[g];
   if (J.desc < 0) return;   // padding of an XCD segment
   const TileDesc& D = descs[J.desc];
-  run_tile_any(D, J, smem);
+  run_tile_sym(D, J, smem);
 }
 
 // Only row-major operands (preconditioning products, sweep updates): smaller code, same engine.
