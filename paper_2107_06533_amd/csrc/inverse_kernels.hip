@@ -175,26 +175,32 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
 
   const unsigned pat = cover_pattern(mask);
   mask = pat;   // blocks the pattern adds hold exact zeros (zero-padded operands)
-  Acc4 acc;
-  acc_zero(acc);
-  for (int kk0 = 0; kk0 < NB; kk0 += KC) {
-    float rq[NU], rz[NU];
+  // Buffer resources: Q is a dense 128 x 128 block; X is cut at the pivot block's last row when the
+  // panel tile is read along rows, so rows of a ragged last pivot block read 0.
+  const rsrc_t rs_q = make_rsrc(Mx.Q, NB * NB * 4u);
+  const rsrc_t rs_x = make_rsrc(Mx.X, (uint32_t)(above ? k0 + kb : d) * (uint32_t)d * 4u);
+  const uint32_t d4 = (uint32_t)d * 4u;
+  float rq[NU], rz[NU];
+  auto issue = [&](int kk0) {
 #pragma unroll
-    for (int u = 0; u < NU; ++u) rq[u] = Mx.Q[(kk0 + kp + 2 * u) * NB + ml];
+    for (int u = 0; u < NU; ++u) rq[u] = buf_load(rs_q, (uint32_t)((kk0 + kp + 2 * u) * NB + ml) * 4u);
     if (above) {
+      const uint32_t base = (uint32_t)(k0 + kk0 + kp) * d4 + (uint32_t)(i0 + ml) * 4u;
 #pragma unroll
-      for (int u = 0; u < NU; ++u) {
-        const int kk = kk0 + kp + 2 * u;
-        rz[u] = (kk < kb) ? Mx.X[(size_t)(k0 + kk) * d + i0 + ml] : 0.f;
-      }
+      for (int u = 0; u < NU; ++u) rz[u] = buf_load(rs_x, base + (uint32_t)(2 * u) * d4);
     } else {
       const int kk = kk0 + kl;
+      const uint32_t base = kk < kb ? (uint32_t)(k0 + kk) * 4u : OOB_OFFSET;   // rows i >= d fall off the end
 #pragma unroll
-      for (int u = 0; u < NU; ++u) {
-        const int i = i0 + mg + MG * u;
-        rz[u] = (kk < kb && i < d) ? Mx.X[(size_t)i * d + k0 + kk] : 0.f;
-      }
+      for (int u = 0; u < NU; ++u) rz[u] = buf_load(rs_x, base + (uint32_t)(i0 + mg + MG * u) * d4);
     }
+  };
+
+  Acc4 acc;
+  acc_zero(acc);
+  gf_ptr Zt = as_global(Mx.Zt);
+  issue(0);
+  for (int kk0 = 0; kk0 < NB; kk0 += KC) {
     __syncthreads();   // previous chunk fully consumed
 #pragma unroll
     for (int u = 0; u < NU; ++u) Qs[lds_idx(ml, kp + 2 * u)] = rq[u];
@@ -205,9 +211,10 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
 #pragma unroll
       for (int u = 0; u < NU; ++u) Zs[lds_idx(mg + MG * u, kl)] = rz[u];
     }
+    if (kk0 + KC < NB) issue(kk0 + KC);   // next chunk's loads fly during this chunk's MFMAs
     __syncthreads();
 #pragma unroll
-    for (int u = 0; u < NU; ++u) Mx.Zt[(size_t)(kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[lds_idx(ml, kp + 2 * u)];
+    for (int u = 0; u < NU; ++u) Zt[(size_t)(kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[lds_idx(ml, kp + 2 * u)];
     switch (pat) {
       case PAT_FULL: mma_ktile<PAT_FULL>(Qs, Zs, acc, wm, wn, lane); break;
       case PAT_ROW1: mma_ktile<PAT_ROW1>(Qs, Zs, acc, wm, wn, lane); break;
@@ -218,6 +225,8 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
   }
 
   // acc(m, i) = W[i][m]: new panel entry for matrix row/col i0+i and pivot column k0+m
+  gf_ptr Wt = as_global(Mx.Wt);
+  const rsrc_t rs_o = make_rsrc(Mx.X, (uint32_t)d * d4);
 #pragma unroll
   for (int qd = 0; qd < 4; ++qd) {
     const int mb0 = wm * 64 + (qd >> 1) * 32, ib0 = wn * 64 + (qd & 1) * 32;
@@ -226,11 +235,11 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
     for (int v = 0; v < 16; ++v) {
       const int mm = mb0 + mfma_row(v, lane);
       const float val = (mask & (1u << qd)) ? acc.c[qd][v] : 0.f;
-      Mx.Wt[(size_t)mm * ldp + i0 + i] = val;
-      if (mm < kb && i0 + i < d) {
-        if (above) Mx.X[(size_t)(k0 + mm) * d + i0 + i] = val;
-        else Mx.X[(size_t)(i0 + i) * d + k0 + mm] = val;
-      }
+      Wt[(size_t)mm * ldp + i0 + i] = val;
+      const bool in = mm < kb && i0 + i < d;
+      const uint32_t off = above ? (uint32_t)(k0 + mm) * d4 + (uint32_t)(i0 + i) * 4u
+                                 : (uint32_t)(i0 + i) * d4 + (uint32_t)(k0 + mm) * 4u;
+      buf_store(rs_o, in ? off : OOB_OFFSET, val);
     }
   }
 }
