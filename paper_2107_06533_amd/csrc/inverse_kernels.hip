@@ -157,7 +157,7 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
   if (g >= njobs) return;
   const MatJob J = jobs[g];
   const InvMat Mx = mats[J.mat];
-  const int it = J.bi;
+  const int it = J.bi, slot = J.aux;   // slot: which 128 rows of the aggregated panel buffers this sweep fills
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int d = Mx.d, ldp = Mx.ldp;
   const int k0 = step * NB, i0 = it * BM;
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
     if (kk0 + KC < NB) issue(kk0 + KC);   // next chunk's loads fly during this chunk's MFMAs
     __syncthreads();
 #pragma unroll
-    for (int u = 0; u < NU; ++u) Zt[(size_t)(kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[lds_idx(ml, kp + 2 * u)];
+    for (int u = 0; u < NU; ++u) Zt[(size_t)(slot * NB + kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[lds_idx(ml, kp + 2 * u)];
     switch (pat) {
       case PAT_FULL: mma_ktile<PAT_FULL>(Qs, Zs, acc, wm, wn, lane); break;
       case PAT_ROW1: mma_ktile<PAT_ROW1>(Qs, Zs, acc, wm, wn, lane); break;
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
     for (int v = 0; v < 16; ++v) {
       const int mm = mb0 + mfma_row(v, lane);
       const float val = (mask & (1u << qd)) ? acc.c[qd][v] : 0.f;
-      Wt[(size_t)mm * ldp + i0 + i] = val;
+      Wt[(size_t)(slot * NB + mm) * ldp + i0 + i] = val;
       const bool in = mm < kb && i0 + i < d;
       const uint32_t off = above ? (uint32_t)(k0 + mm) * d4 + (uint32_t)(i0 + i) * 4u
                                  : (uint32_t)(i0 + i) * d4 + (uint32_t)(k0 + mm) * 4u;

@@ -101,6 +101,7 @@ struct kfac_ctx {
   size_t ws_cap = 0;
   int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
   int inv_groups = 3;                     // matrix groups swept concurrently (one internal stream each)
+  int inv_agg = 4;                        // pivot blocks per aggregated (rank agg*128) update
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};
   hipEvent_t inv_fork = nullptr, inv_join[MAX_INV_GROUPS] = {};
   FactorPlan fp;
@@ -453,7 +454,7 @@ struct InvertSchedule {
   kfac_plan_stats stats{};
 };
 
-InvertSchedule schedule_invert(int n, const int32_t* dims) {
+InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
   InvertSchedule S;
   S.order.resize(n);
   for (int i = 0; i < n; ++i) S.order[i] = i;
@@ -465,7 +466,7 @@ InvertSchedule schedule_invert(int n, const int32_t* dims) {
     S.nblk[m] = ceil_div(d, NB);
     S.ldp[m] = S.nblk[m] * NB;
     S.ws_off[m] = S.ws_floats;
-    S.ws_floats += size_t(2) * NB * S.ldp[m] + size_t(NB) * NB;
+    S.ws_floats += size_t(2) * agg * NB * S.ldp[m] + size_t(NB) * NB;
     S.nsteps = std::max(S.nsteps, S.nblk[m]);
     for (int bi = 0; bi < S.nblk[m]; ++bi)
       for (int bj = 0; bj <= bi; ++bj) S.init.push_back({m, bi, bj, 0});
@@ -482,18 +483,33 @@ InvertSchedule schedule_invert(int n, const int32_t* dims) {
       S.active[s]++;
       const int d = dims[S.order[m]];
       const int kb = std::min(NB, d - s * NB);
+      // Sweeps are aggregated in outer blocks of `agg` pivot blocks: sweep s updates at once only
+      // the tiles in the block columns/rows of its outer block (rank 128); the rest of the triangle
+      // gets the whole outer block's panels in one rank-(agg*128) update after its last sweep.
+      const int slot = s % agg;
+      const int ob0 = (s / agg) * agg, ob1 = std::min(ob0 + agg, S.nblk[m]);   // outer block [ob0, ob1)
       for (int it = 0; it < S.nblk[m]; ++it)
-        if (it != s) S.panel.push_back({m, it, 0, 0});
-      for (int bi = 0; bi < S.nblk[m]; ++bi) {
-        if (bi == s) continue;
+        if (it != s) S.panel.push_back({m, it, 0, slot});
+      auto in_ob = [&](int b) { return b >= ob0 && b < ob1; };
+      const bool last_of_block = s == ob1 - 1;
+      const int kend_outer = (ob1 - 1 - ob0) * NB + std::min(NB, d - (ob1 - 1) * NB);
+      std::vector<TileJob> inner;
+      for (int bi = 0; bi < S.nblk[m]; ++bi)
         for (int bj = 0; bj <= bi; ++bj) {
-          if (bj == s) continue;
           TileJob j{};
-          j.desc = m; j.bi = bi; j.bj = bj; j.kbeg = 0; j.kend = kb; j.part = -1;
-          S.upd.push_back(j);
-          S.stats.mfma_flops += int64_t(ceil_div(kb, KC) * KC) * active_blocks(d, d, bi, bj, true) * 32 * 32 * 2;
+          j.desc = m; j.bi = bi; j.bj = bj; j.part = -1;
+          if (in_ob(bi) || in_ob(bj)) {
+            if (bi == s || bj == s) continue;
+            j.kbeg = slot * NB; j.kend = slot * NB + kb;
+            inner.push_back(j);
+          } else {
+            if (!last_of_block) continue;
+            j.kbeg = 0; j.kend = kend_outer;
+            S.upd.push_back(j);     // long jobs first
+          }
+          S.stats.mfma_flops += int64_t(ceil_div(j.kend - j.kbeg, KC) * KC) * active_blocks(d, d, bi, bj, true) * 32 * 32 * 2;
         }
-      }
+      S.upd.insert(S.upd.end(), inner.begin(), inner.end());
       S.stats.mfma_flops += int64_t(S.nblk[m] - 1) * NB * 16 * 32 * 32 * 2;   // panel products
     }
     S.panel_off[s + 1] = int(S.panel.size());
@@ -563,6 +579,10 @@ kfac_status kfac_create(kfac_ctx** out, int device) {
     const int v = std::atoi(e);
     if (v >= 1 && v <= MAX_INV_GROUPS) c->inv_groups = v;
   }
+  if (const char* e = std::getenv("KFAC_INV_AGG")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= 16) c->inv_agg = v;
+  }
   if (const char* e = std::getenv("KFAC_KJOB")) {
     const int v = std::atoi(e);
     if (v >= KC) c->kjob = std::min(v, MAX_JOB_ROWS);
@@ -610,11 +630,11 @@ size_t kfac_workspace_bytes_factors(const kfac_ctx* ctx, int n, const kfac_layer
   return size_t(schedule_factors(n, layers, present, ctx ? ctx->kjob : 8192).stats.ws_bytes);
 }
 
-size_t kfac_workspace_bytes_invert(const kfac_ctx*, int n, const int32_t* dims) {
+size_t kfac_workspace_bytes_invert(const kfac_ctx* ctx, int n, const int32_t* dims) {
   if (n <= 0 || !dims) return 0;
   for (int i = 0; i < n; ++i)
     if (dims[i] < 1) return 0;
-  return size_t(schedule_invert(n, dims).stats.ws_bytes);   // independent of how the matrices are grouped
+  return size_t(schedule_invert(n, dims, ctx ? ctx->inv_agg : 4).stats.ws_bytes);   // independent of how the matrices are grouped
 }
 
 size_t kfac_workspace_bytes_precondition(const kfac_ctx*, int n, const int32_t* dG, const int32_t* dA) {
@@ -797,7 +817,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     for (InvertGroup& Gp : P.groups) {
       std::vector<int32_t> gd;
       for (int i : Gp.idx) gd.push_back(dims[i]);
-      InvertSchedule S = schedule_invert(int(gd.size()), gd.data());
+      InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), ctx->inv_agg);
       Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.nsteps = S.nsteps;
       Gp.active = S.active; Gp.panel_off = S.panel_off; Gp.upd_off = S.upd_off; Gp.ws_off = S.ws_off;
       Gp.n_init = int(S.init.size()); Gp.n_finish = int(S.finish.size());
@@ -857,11 +877,11 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         M.nblk = ceil_div(M.d, NB);
         M.ldp = M.nblk * NB;
         M.Wt = wsf + Gp.ws_base + Gp.ws_off[m];
-        M.Zt = M.Wt + size_t(NB) * M.ldp;
-        M.Q = M.Zt + size_t(NB) * M.ldp;
+        M.Zt = M.Wt + size_t(ctx->inv_agg) * NB * M.ldp;
+        M.Q = M.Zt + size_t(ctx->inv_agg) * NB * M.ldp;
         TileDesc& D = hd[m];
-        D.a = rowmajor_operand(M.Wt, NB, M.ldp, M.ldp);
-        D.b = rowmajor_operand(M.Zt, NB, M.ldp, M.ldp);
+        D.a = rowmajor_operand(M.Wt, ctx->inv_agg * NB, M.ldp, M.ldp);
+        D.b = rowmajor_operand(M.Zt, ctx->inv_agg * NB, M.ldp, M.ldp);
         D.out = M.X; D.ldo = M.d; D.M = D.N = M.d;
         D.sym = 1; D.mirror = MIRROR_DIAG_TILE; D.alpha = -1.f; D.beta = 1.f;
       } else {
