@@ -1,0 +1,140 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times: one
+kfac_update_factors + kfac_invert_batch + kfac_precondition over the whole layer set, each a
+single call on the current stream with identity factors as the running-average start.
+
+ResNet-50 set: every output of every layer is compared with the fp64 oracle element by element.
+ResNet-152 and BERT-large sets: the oracle is run on one layer of every distinct shape class plus
+the last layer (whole step for those layers, compared element by element); every other output is
+covered by properties that hold at any size, evaluated in fp64 with torch on the device:
+exact symmetry, the damped-inverse residual against the factor the GPU produced, and the
+two-sided product recomputed from the GPU's own inverses.
+"""
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+import oracle
+from synth import shapes, inputs
+from gpu_util import host64, rel_fro, inv_residual, TOL_FACTOR, TOL_INVERSE, TOL_PRECOND
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+@pytest.fixture(scope="module")
+def ctx(kfac_lib):
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = kfac_lib.Context(0)
+    yield c
+    c.close()
+
+
+def gpu_step(ctx, name):
+    """Upload the seeded inputs of a whole configuration and run one step as bench.py does."""
+    import torch
+    hp = shapes.config_hparams(name)
+    layers = shapes.config_layers(name)
+    n = len(layers)
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        ins = list(ex.map(lambda il: inputs.layer_inputs(il[1], hp["cid"], 0, il[0], hp["relu"]), enumerate(layers)))
+    up = lambda x: torch.from_numpy(x).cuda()
+    a_d, g_d, v_d = [up(x[0]) for x in ins], [up(x[1]) for x in ins], [up(x[2]) for x in ins]
+    A_d = [torch.eye(l.dA, device="cuda") for l in layers]
+    G_d = [torch.eye(l.dG, device="cuda") for l in layers]
+    XA_d = [torch.empty_like(t) for t in A_d]
+    XG_d = [torch.empty_like(t) for t in G_d]
+    P_d = [torch.empty_like(v) for v in v_d]
+    info = torch.full((2 * n,), -1, dtype=torch.int32, device="cuda")
+    dims = [l.dA for l in layers] + [l.dG for l in layers]
+    stream = torch.cuda.current_stream()
+    ctx.kfac_update_factors(layers, a_d, g_d, A_d, G_d, hp["xi"], stream=stream)
+    ctx.kfac_invert_batch(dims, A_d + G_d, XA_d + XG_d, hp["gamma"], info, stream=stream)
+    ctx.kfac_precondition([l.dG for l in layers], [l.dA for l in layers], XG_d, XA_d, v_d, P_d, stream=stream)
+    torch.cuda.synchronize()
+    assert int(info.abs().sum()) == 0, "a factor was reported not positive definite"
+    return hp, layers, ins, dict(A=A_d, G=G_d, XA=XA_d, XG=XG_d, P=P_d, V=v_d)
+
+
+def check_layer_against_oracle(i, l, ins_i, hp, out):
+    """Whole step of one layer in the oracle, compared element by element."""
+    a, g, v = ins_i
+    A, G, XA, XG, P = oracle.kfac_step([l], [a], [g], [v], [np.eye(l.dA)], [np.eye(l.dG)], hp["xi"], hp["gamma"])
+    worst = {}
+    for key, ref in (("A", A[0]), ("G", G[0])):
+        got = host64(out[key][i])
+        assert np.array_equal(got, got.T), f"layer {i} {key}: not exactly symmetric"
+        e = rel_fro(got, ref)
+        assert e <= TOL_FACTOR, f"layer {i} ({l.name}) {key}: rel Frobenius {e:.3e}"
+        worst["factor"] = max(worst.get("factor", 0.0), e)
+    for key, F in (("XA", A[0]), ("XG", G[0])):
+        X = host64(out[key][i])
+        assert np.array_equal(X, X.T), f"layer {i} {key}: not exactly symmetric"
+        r = inv_residual(F, hp["gamma"], X)
+        assert r <= TOL_INVERSE, f"layer {i} ({l.name}) {key}: residual {r:.3e}"
+        worst["inverse"] = max(worst.get("inverse", 0.0), r)
+    e = rel_fro(host64(out["P"][i]), P[0])
+    assert e <= TOL_PRECOND, f"layer {i} ({l.name}) preconditioned gradient: rel err {e:.3e}"
+    worst["precond"] = e
+    return worst
+
+
+def check_layer_properties(i, l, hp, out):
+    """Size-independent properties in fp64 on the device (no oracle): symmetry, residual of the
+    inverse against the GPU's own factor, two-sided product from the GPU's own inverses."""
+    import torch
+    for fk, xk in (("A", "XA"), ("G", "XG")):
+        F, X = out[fk][i], out[xk][i]
+        assert torch.equal(F, F.T) and torch.equal(X, X.T), f"layer {i} {fk}/{xk}: not exactly symmetric"
+        d = F.shape[0]
+        M = F.double()
+        M.diagonal().add_(hp["gamma"])
+        R = M @ X.double()
+        R.diagonal().sub_(1.0)
+        r = float(torch.linalg.norm(R) / np.sqrt(d))
+        assert r <= TOL_INVERSE, f"layer {i} ({l.name}) {xk}: residual {r:.3e}"
+    want = out["XG"][i].double() @ out["V"][i].double() @ out["XA"][i].double()
+    e = float(torch.linalg.norm(out["P"][i].double() - want) / torch.linalg.norm(want))
+    assert e <= 1e-5, f"layer {i} ({l.name}): two-sided product differs from its fp64 recomputation by {e:.3e}"
+
+
+def merge(w, x):
+    for k, v in x.items():
+        w[k] = max(w.get(k, 0.0), v)
+
+
+def test_r50_every_layer_against_oracle(ctx):
+    t0 = time.perf_counter()
+    hp, layers, ins, out = gpu_step(ctx, "r50")
+    print(f"\nr50: inputs + GPU step {time.perf_counter() - t0:.1f} s", flush=True)
+    worst = {}
+    t0 = time.perf_counter()
+    for i, l in enumerate(layers):
+        merge(worst, check_layer_against_oracle(i, l, ins[i], hp, out))
+    print(f"r50: oracle over {len(layers)} layers {time.perf_counter() - t0:.1f} s, worst {worst}", flush=True)
+
+
+def sampled_layers(layers):
+    first = {}
+    for i, l in enumerate(layers):
+        first.setdefault((l.kind, l.dA, l.dG, l.R, l.kh, l.stride), i)
+    return sorted(set(first.values()) | {len(layers) - 1})
+
+
+@pytest.mark.parametrize("name", ["r152", "bertl"])
+def test_large_sets_sampled_against_oracle(ctx, name):
+    t0 = time.perf_counter()
+    hp, layers, ins, out = gpu_step(ctx, name)
+    print(f"\n{name}: inputs + GPU step {time.perf_counter() - t0:.1f} s", flush=True)
+    sample = sampled_layers(layers)
+    worst = {}
+    t0 = time.perf_counter()
+    for i in sample:
+        merge(worst, check_layer_against_oracle(i, layers[i], ins[i], hp, out))
+    print(f"{name}: oracle on layers {sample}: {time.perf_counter() - t0:.1f} s, worst {worst}", flush=True)
+    t0 = time.perf_counter()
+    for i, l in enumerate(layers):
+        if i not in sample:
+            check_layer_properties(i, l, hp, out)
+    print(f"{name}: properties of the other {len(layers) - len(sample)} layers {time.perf_counter() - t0:.1f} s", flush=True)
