@@ -34,109 +34,160 @@ __global__ __launch_bounds__(NT) void gj_init_kernel(const InvMat* __restrict__ 
   }
 }
 
-// ---- pivot block: in-register symmetric sweep of an n x n (n <= 128) SPD block ------------------
-// 256 threads as 16 x 16; thread (ty, tx) holds elements (ty + 16a, tx + 16b) for a >= b only: the
-// sweep keeps the lower triangle and mirrors it at the end, so the result is exactly symmetric.
-// Step k broadcasts column k of the symmetric matrix through LDS (rows >= k from column k, rows < k
-// from row k), then every element does one fused multiply-add  m_ij -= (c_i / p) * c_j.
+// ---- pivot block: symmetric sweep of an n x n (n <= 128) SPD block in one workgroup ---------------
+// The block lives in LDS as 4 x 4 sub-blocks of 32 x 32 and is swept sub-block by sub-block:
+//   (A) every wave inverts the 32 x 32 diagonal sub-block D in registers (redundantly, so no
+//       exchange is needed): lane (i, h) = i + 32 h holds D[i][2t + h], t = 0..15, which is exactly
+//       the operand layout of v_mfma_f32_32x32x2_f32; step k of the scalar sweep fetches row k with
+//       16 cross-lane reads and does 16 fused multiply-adds per lane;
+//   (B) wave w != kb owns sub-block row w:  W_w = Z_w D^-1  (Z_w = old sub-block (w, kb)), then
+//       S_wj -= W_w Z_j^T for j != kb, all on the matrix cores; after a barrier it stores W_w into
+//       sub-block (w, kb) and its transpose into (kb, w); wave kb stores -D^-1.
+// Sub-blocks past n are identity and are skipped.  The lower triangle is mirrored on the way out,
+// so the result is exactly symmetric.
 // small = 1: block = F + gamma I (whole matrix, d <= NB), result written to X as +inverse.
-// small = 0: block = diagonal block `step` of X; writes Q = +inverse (zero padded to NB x NB)
-//            and the swept block (-inverse) back into X.
+// small = 0: block = diagonal block `step` of X (lower triangle valid); writes Q = +inverse (zero
+//            padded to NB x NB) and the swept block (-inverse) back into X.
+constexpr int SB = 32;          // sub-block order
+constexpr int SP = NB + 1;      // LDS row pitch of the block (odd: conflict-free rows and columns)
+constexpr int WP = SB + 1;      // pitch of a wave's staging sub-block
+
+// In-register sweep of a 32 x 32 SPD sub-block held as r[t] = D[i][2t + h]; returns +D^-1 in the
+// same layout.  `bad` receives the 1-based index of the first non-positive pivot (0 if none).
+__device__ __forceinline__ void sweep32(float (&r)[16], int lane, int& bad) {
+  const int i = lane & 31, h = lane >> 5;
+  const int row_src = (h << 5) << 2;   // byte address of lane (0, h) for ds_bpermute
+#pragma unroll
+  for (int k = 0; k < SB; ++k) {
+    const int tk = k >> 1, hk = k & 1;
+    float c[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t)       // row k, columns 2t + h: held by lane (k, h)
+      c[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(row_src + (k << 2), __float_as_int(r[t])));
+    // column k, row i: held by lane (i, hk)
+    const float ci = __int_as_float(__builtin_amdgcn_ds_bpermute((i + (hk << 5)) << 2, __float_as_int(r[tk])));
+    const float p = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r[tk]), k + (hk << 5)));
+    if (!(p > 0.f) && bad == 0) bad = k + 1;
+    float ip = __builtin_amdgcn_rcpf(p);
+    ip = fmaf(fmaf(-p, ip, 1.f), ip, ip);   // one Newton step on the hardware reciprocal
+    const float wi = ci * ip;
+    // lane row k: r - (1 - 1/p) r = r / p, the swept pivot row
+    const float wu = (i == k) ? 1.f - ip : wi;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) r[t] = fmaf(-wu, c[t], r[t]);
+    if (h == hk) r[tk] = (i == k) ? -ip : wi;   // pivot column
+  }
+#pragma unroll
+  for (int t = 0; t < 16; ++t) r[t] = -r[t];
+}
+
 __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__ mats, int mat0, int step,
                                                       float gamma, int small) {
-  __shared__ float col[2][NB];
-  __shared__ float tileT[NB][NB + 1];   // mirror staging
-  __shared__ int bad;
+  __shared__ float S[NB * SP];
+  __shared__ float stage[4][SB * WP];
   const InvMat Mx = mats[mat0 + blockIdx.x];
-  const int t = threadIdx.x, ty = t >> 4, tx = t & 15;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int li = lane & 31, lh = lane >> 5;
   const int d = Mx.d;
   const int k0 = small ? 0 : step * NB;
   const int n = small ? d : (d - k0 < NB ? d - k0 : NB);
-  gcf_ptr src = as_global(small ? Mx.F : Mx.X);
+  const int nsb = (n + SB - 1) / SB;
   const float damp = small ? gamma : 0.f;
 
-  float m[8][8];
+  // lower triangle -> full symmetric block in LDS, identity past n.  Loads go out in batches of
+  // 32 per thread (range-checked buffer loads; skipped elements cost no memory traffic).
+  const rsrc_t rs_src = make_rsrc(small ? Mx.F : Mx.X, (uint32_t)d * (uint32_t)d * 4u);
 #pragma unroll
-  for (int a = 0; a < 8; ++a)
+  for (int b = 0; b < 2; ++b) {
+    float v[32];
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
-      if (b > a) continue;
-      const int i = ty + 16 * a, j = tx + 16 * b;
-      float v = (i == j) ? 1.f : 0.f;
-      if (i < n && j < n && i >= j) {
-        v = src[(size_t)(k0 + i) * d + k0 + j];
-        if (i == j) v += damp;
-      }
-      m[a][b] = v;
+    for (int u = 0; u < 32; ++u) {
+      const int i = (t >> 7) + 2 * (b * 32 + u), j = t & (NB - 1);
+      v[u] = buf_load(rs_src, (i < n && j <= i) ? ((uint32_t)(k0 + i) * (uint32_t)d + (uint32_t)(k0 + j)) * 4u : OOB_OFFSET);
     }
-  if (t == 0) bad = 0;
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      const int i = (t >> 7) + 2 * (b * 32 + u), j = t & (NB - 1);
+      if (j > i) continue;
+      float x = v[u];
+      if (i == j) x = i < n ? x + damp : 1.f;
+      S[i * SP + j] = x;
+      S[j * SP + i] = x;
+    }
+  }
   __syncthreads();
 
+  int bad = 0;
+  for (int kb = 0; kb < nsb; ++kb) {
+    // (A) inverse of the diagonal sub-block, in every wave
+    float dinv[16];
 #pragma unroll
-  for (int kb = 0; kb < 8; ++kb) {
-    if (kb * 16 < n) {
-      const int kk_end = (n - kb * 16 < 16) ? n - kb * 16 : 16;
-      for (int kk = 0; kk < kk_end; ++kk) {
-        const int k = kb * 16 + kk;
-        float* cb = col[k & 1];
-        if (tx == kk) {            // rows i >= k of column k
+    for (int q = 0; q < 16; ++q) dinv[q] = S[(kb * SB + li) * SP + kb * SB + 2 * q + lh];
+    int bad_k = 0;
+    sweep32(dinv, lane, bad_k);
+    if (bad_k && bad == 0) bad = kb * SB + bad_k;
+
+    // (B) panel and update of sub-block row w
+    f32x16 wacc;
 #pragma unroll
-          for (int a = kb; a < 8; ++a)
-            if (a > kb || ty >= kk) cb[ty + 16 * a] = m[a][kb];
-        }
-        if (ty == kk) {            // rows i < k come from row k
+    for (int v = 0; v < 16; ++v) wacc[v] = 0.f;
+    const bool work = (w != kb) && (w < nsb);
+    if (work) {
+      float z[16];
 #pragma unroll
-          for (int b = 0; b <= kb; ++b)
-            if (b < kb || tx < kk) cb[tx + 16 * b] = m[kb][b];
-        }
-        __syncthreads();
-        const float p = cb[k];
-        if (!(p > 0.f) && t == 0 && bad == 0) bad = k + 1;
-        const float ip = 1.f / p;
-        float wi[8], cj[8];
+      for (int q = 0; q < 16; ++q) z[q] = S[(w * SB + li) * SP + kb * SB + 2 * q + lh];
 #pragma unroll
-        for (int a = 0; a < 8; ++a) wi[a] = cb[ty + 16 * a] * ip;
+      for (int q = 0; q < 16; ++q) wacc = __builtin_amdgcn_mfma_f32_32x32x2f32(z[q], dinv[q], wacc, 0, 0, 0);
+      // accumulator layout -> operand layout through the wave's staging sub-block
+      float* st = stage[w];
 #pragma unroll
-        for (int b = 0; b < 8; ++b) cj[b] = cb[tx + 16 * b];
+      for (int v = 0; v < 16; ++v) st[mfma_row(v, lane) * WP + mfma_col(lane)] = wacc[v];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      float wn[16];
 #pragma unroll
-        for (int a = 0; a < 8; ++a)
+      for (int q = 0; q < 16; ++q) wn[q] = -st[li * WP + 2 * q + lh];
+      for (int j = 0; j < nsb; ++j) {
+        if (j == kb) continue;
+        float zj[16];
 #pragma unroll
-          for (int b = 0; b <= a; ++b) m[a][b] = fmaf(-wi[a], cj[b], m[a][b]);
-        if (tx == kk) {            // column k: m_ik = c_i / p
+        for (int q = 0; q < 16; ++q) zj[q] = S[(j * SB + li) * SP + kb * SB + 2 * q + lh];
+        f32x16 acc;
 #pragma unroll
-          for (int a = kb; a < 8; ++a) m[a][kb] = wi[a];
-        }
-        if (ty == kk) {            // row k: m_kj = c_j / p
+        for (int v = 0; v < 16; ++v) acc[v] = S[(w * SB + mfma_row(v, lane)) * SP + j * SB + mfma_col(lane)];
 #pragma unroll
-          for (int b = 0; b <= kb; ++b) m[kb][b] = cj[b] * ip;
-        }
-        if (tx == kk && ty == kk) m[kb][kb] = -ip;
+        for (int q = 0; q < 16; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wn[q], zj[q], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) S[(w * SB + mfma_row(v, lane)) * SP + j * SB + mfma_col(lane)] = acc[v];
       }
     }
+    __syncthreads();   // every read of the old sub-block column kb is done
+    if (work) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = mfma_row(v, lane), c = mfma_col(lane);
+        S[(w * SB + r) * SP + kb * SB + c] = wacc[v];
+        S[(kb * SB + c) * SP + w * SB + r] = wacc[v];
+      }
+    } else if (w == kb) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) S[(kb * SB + li) * SP + kb * SB + 2 * q + lh] = -dinv[q];
+    }
+    __syncthreads();
   }
   if (t == 0 && Mx.info) {
     if (small) *Mx.info = bad;                                // whole matrix: sole writer
     else if (bad && *Mx.info == 0) *Mx.info = k0 + bad;       // first failing sweep wins (zeroed by the init kernel)
   }
 
-  // mirror the lower triangle through LDS, then write rows contiguously
-#pragma unroll
-  for (int a = 0; a < 8; ++a)
-#pragma unroll
-    for (int b = 0; b <= a; ++b) {
-      const int i = ty + 16 * a, j = tx + 16 * b;
-      if (i >= j) {
-        tileT[i][j] = m[a][b];
-        tileT[j][i] = m[a][b];
-      }
-    }
-  __syncthreads();
   gf_ptr X = as_global(Mx.X);
   gf_ptr Q = as_global(Mx.Q);
+#pragma unroll 8
   for (int e = t; e < NB * NB; e += NT) {
     const int i = e >> 7, j = e & (NB - 1);
     const bool in = i < n && j < n;
-    const float v = tileT[i][j];
+    const float v = i >= j ? S[i * SP + j] : S[j * SP + i];
     if (small) {
       if (in) X[(size_t)i * d + j] = -v;
     } else {

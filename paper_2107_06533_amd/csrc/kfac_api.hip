@@ -21,6 +21,9 @@ struct MatJobH {
   int32_t mat, bi, bj, aux;
 };
 
+// The three update lists of a sweep step (see schedule_invert).
+enum { UPD_INNER = 0, UPD_AHEAD = 1, UPD_REST = 2 };
+
 inline int ceil_div(int64_t a, int64_t b) { return int((a + b - 1) / b); }
 
 // A device table that is re-uploaded whenever its host image changes.
@@ -53,12 +56,14 @@ struct InvertGroup {
   std::vector<int> order;            // sorted position -> position in idx (large first, descending d)
   int n_large = 0, n_small = 0, nsteps = 0;
   std::vector<int> active;           // [step] number of large matrices still being swept
-  std::vector<int> panel_off, upd_off;
+  std::vector<int> panel_off;
+  std::vector<int> upd_off[3];       // [UPD_INNER / UPD_AHEAD / UPD_REST][step]
   std::vector<size_t> ws_off;        // per large matrix: float offset of its workspace inside the group's region
   void* d_init = nullptr; int n_init = 0;
   void* d_finish = nullptr; int n_finish = 0;
   void* d_panel = nullptr;
-  void* d_upd = nullptr;
+  void* d_upd[3] = {nullptr, nullptr, nullptr};
+  std::vector<hipEvent_t> ev_panel, ev_rest;   // [step], created on first use
   DynTable tab;                      // [InvMat x n][TileDesc x n_large]
   size_t ws_floats = 0, ws_base = 0;
 };
@@ -100,9 +105,10 @@ struct kfac_ctx {
   void* ws = nullptr;
   size_t ws_cap = 0;
   int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
-  int inv_groups = 3;                     // matrix groups swept concurrently (one internal stream each)
+  int inv_groups = 1;                     // matrix groups swept concurrently
   int inv_agg = 4;                        // pivot blocks per aggregated (rank agg*128) update
-  hipStream_t inv_stream[MAX_INV_GROUPS] = {};
+  hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
+  hipStream_t inv_side[MAX_INV_GROUPS] = {};     // every group's side stream for the off-chain updates
   hipEvent_t inv_fork = nullptr, inv_join[MAX_INV_GROUPS] = {};
   FactorPlan fp;
   InvertPlan ip;
@@ -357,7 +363,10 @@ void release(FactorPlan& p) {
 }
 void release(InvertPlan& p) {
   for (InvertGroup& g : p.groups) {
-    free_dev(g.d_init); free_dev(g.d_finish); free_dev(g.d_panel); free_dev(g.d_upd); free_table(g.tab);
+    free_dev(g.d_init); free_dev(g.d_finish); free_dev(g.d_panel); free_table(g.tab);
+    for (int k = 0; k < 3; ++k) free_dev(g.d_upd[k]);
+    for (hipEvent_t e : g.ev_panel) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g.ev_rest) if (e) (void)hipEventDestroy(e);
   }
   p = InvertPlan{};
 }
@@ -442,14 +451,23 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
 }
 
 // ------------------------------------------------------------------------------- invert plan
+// Sweeps are aggregated in outer blocks of `agg` pivot blocks.  Sweep s updates at once only the
+// tiles in the block rows/columns of its own outer block (UPD_INNER, rank 128).  After the last
+// sweep of an outer block every other tile gets the whole block's panels in one rank-(agg*128)
+// update, split in two lists: the tiles in the rows/columns of the NEXT outer block (UPD_AHEAD),
+// which the next sweeps need at once, and all the others (UPD_REST), which nothing touches before
+// the next outer block ends and which therefore run beside the next sweeps on a second stream.
+// The panel buffers of consecutive outer blocks alternate between two halves of the workspace so
+// that the off-chain update can still read its panels while the next ones are written.
 struct InvertSchedule {
   std::vector<int> order;
   int n_large = 0, n_small = 0, nsteps = 0;
-  std::vector<int> active, panel_off, upd_off;
+  std::vector<int> active, panel_off;
+  std::vector<int> upd_off[3];
   std::vector<size_t> ws_off;
   std::vector<int> nblk, ldp;
   std::vector<MatJobH> init, finish, panel;
-  std::vector<TileJob> upd;
+  std::vector<TileJob> upd[3];
   size_t ws_floats = 0;
   kfac_plan_stats stats{};
 };
@@ -466,7 +484,7 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
     S.nblk[m] = ceil_div(d, NB);
     S.ldp[m] = S.nblk[m] * NB;
     S.ws_off[m] = S.ws_floats;
-    S.ws_floats += size_t(2) * agg * NB * S.ldp[m] + size_t(NB) * NB;
+    S.ws_floats += size_t(4) * agg * NB * S.ldp[m] + size_t(NB) * NB;   // Wt, Zt: two halves of agg panels each; Q
     S.nsteps = std::max(S.nsteps, S.nblk[m]);
     for (int bi = 0; bi < S.nblk[m]; ++bi)
       for (int bj = 0; bj <= bi; ++bj) S.init.push_back({m, bi, bj, 0});
@@ -476,24 +494,24 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
   }
   S.active.assign(S.nsteps, 0);
   S.panel_off.assign(S.nsteps + 1, 0);
-  S.upd_off.assign(S.nsteps + 1, 0);
+  for (int k = 0; k < 3; ++k) S.upd_off[k].assign(S.nsteps + 1, 0);
+  int n_upd_launches = 0;
   for (int s = 0; s < S.nsteps; ++s) {
     for (int m = 0; m < S.n_large; ++m) {
       if (S.nblk[m] <= s) continue;
       S.active[s]++;
       const int d = dims[S.order[m]];
       const int kb = std::min(NB, d - s * NB);
-      // Sweeps are aggregated in outer blocks of `agg` pivot blocks: sweep s updates at once only
-      // the tiles in the block columns/rows of its outer block (rank 128); the rest of the triangle
-      // gets the whole outer block's panels in one rank-(agg*128) update after its last sweep.
-      const int slot = s % agg;
+      const int half = (s / agg) & 1;                 // which half of the panel buffers this outer block fills
+      const int slot = half * agg + s % agg;
       const int ob0 = (s / agg) * agg, ob1 = std::min(ob0 + agg, S.nblk[m]);   // outer block [ob0, ob1)
+      const int nb1 = std::min(ob1 + agg, S.nblk[m]);                            // next outer block [ob1, nb1)
       for (int it = 0; it < S.nblk[m]; ++it)
         if (it != s) S.panel.push_back({m, it, 0, slot});
       auto in_ob = [&](int b) { return b >= ob0 && b < ob1; };
+      auto in_next = [&](int b) { return b >= ob1 && b < nb1; };
       const bool last_of_block = s == ob1 - 1;
       const int kend_outer = (ob1 - 1 - ob0) * NB + std::min(NB, d - (ob1 - 1) * NB);
-      std::vector<TileJob> inner;
       for (int bi = 0; bi < S.nblk[m]; ++bi)
         for (int bj = 0; bj <= bi; ++bj) {
           TileJob j{};
@@ -501,22 +519,25 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
           if (in_ob(bi) || in_ob(bj)) {
             if (bi == s || bj == s) continue;
             j.kbeg = slot * NB; j.kend = slot * NB + kb;
-            inner.push_back(j);
+            S.upd[UPD_INNER].push_back(j);
           } else {
             if (!last_of_block) continue;
-            j.kbeg = 0; j.kend = kend_outer;
-            S.upd.push_back(j);     // long jobs first
+            j.kbeg = half * agg * NB; j.kend = j.kbeg + kend_outer;
+            S.upd[(in_next(bi) || in_next(bj)) ? UPD_AHEAD : UPD_REST].push_back(j);
           }
           S.stats.mfma_flops += int64_t(ceil_div(j.kend - j.kbeg, KC) * KC) * active_blocks(d, d, bi, bj, true) * 32 * 32 * 2;
         }
-      S.upd.insert(S.upd.end(), inner.begin(), inner.end());
       S.stats.mfma_flops += int64_t(S.nblk[m] - 1) * NB * 16 * 32 * 32 * 2;   // panel products
     }
     S.panel_off[s + 1] = int(S.panel.size());
-    S.upd_off[s + 1] = int(S.upd.size());
+    for (int k = 0; k < 3; ++k) {
+      S.upd_off[k][s + 1] = int(S.upd[k].size());
+      n_upd_launches += S.upd_off[k][s + 1] > S.upd_off[k][s];
+    }
   }
-  S.stats.n_jobs = int64_t(S.init.size() + S.finish.size() + S.panel.size() + S.upd.size()) + S.n_small;
-  S.stats.n_launches = (S.n_small ? 1 : 0) + (S.n_large ? 2 + 3 * S.nsteps : 0);
+  S.stats.n_jobs = int64_t(S.init.size() + S.finish.size() + S.panel.size()) + S.n_small;
+  for (int k = 0; k < 3; ++k) S.stats.n_jobs += int64_t(S.upd[k].size());
+  S.stats.n_launches = (S.n_small ? 1 : 0) + (S.n_large ? 2 + 2 * S.nsteps + n_upd_launches : 0);
   S.stats.ws_bytes = int64_t(S.ws_floats * sizeof(float));
   return S;
 }
@@ -609,6 +630,7 @@ void kfac_destroy(kfac_ctx* ctx) {
     for (const TimingRec& r : ctx->timing) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (int g = 0; g < MAX_INV_GROUPS; ++g) {
       if (ctx->inv_stream[g]) (void)hipStreamDestroy(ctx->inv_stream[g]);
+      if (ctx->inv_side[g]) (void)hipStreamDestroy(ctx->inv_side[g]);
       if (ctx->inv_join[g]) (void)hipEventDestroy(ctx->inv_join[g]);
     }
     if (ctx->inv_fork) (void)hipEventDestroy(ctx->inv_fork);
@@ -819,7 +841,9 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       for (int i : Gp.idx) gd.push_back(dims[i]);
       InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), ctx->inv_agg);
       Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.nsteps = S.nsteps;
-      Gp.active = S.active; Gp.panel_off = S.panel_off; Gp.upd_off = S.upd_off; Gp.ws_off = S.ws_off;
+      Gp.active = S.active; Gp.panel_off = S.panel_off; Gp.ws_off = S.ws_off;
+      for (int k = 0; k < 3; ++k) Gp.upd_off[k] = S.upd_off[k];
+      Gp.ev_panel.assign(S.nsteps, nullptr); Gp.ev_rest.assign(S.nsteps, nullptr);
       Gp.n_init = int(S.init.size()); Gp.n_finish = int(S.finish.size());
       Gp.ws_floats = S.ws_floats;
       Gp.ws_base = P.ws_floats;
@@ -831,7 +855,8 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         if ((st = upload_static(ctx, &Gp.d_init, S.init.data(), S.init.size() * sizeof(MatJobH))) != KFAC_OK) return st;
         if ((st = upload_static(ctx, &Gp.d_finish, S.finish.data(), S.finish.size() * sizeof(MatJobH))) != KFAC_OK) return st;
         if ((st = upload_static(ctx, &Gp.d_panel, S.panel.data(), S.panel.size() * sizeof(MatJobH))) != KFAC_OK) return st;
-        if ((st = upload_static(ctx, &Gp.d_upd, S.upd.data(), S.upd.size() * sizeof(TileJob))) != KFAC_OK) return st;
+        for (int k = 0; k < 3; ++k)
+          if ((st = upload_static(ctx, &Gp.d_upd[k], S.upd[k].data(), S.upd[k].size() * sizeof(TileJob))) != KFAC_OK) return st;
       }
     }
     P.valid = true;
@@ -843,18 +868,20 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   if (st != KFAC_OK) return st;
   const int G = int(P.groups.size());
 
-  // With more than one group, every group runs on an internal stream (default priority) that is
-  // forked from and joined back into the caller's stream with events.
-  if (G > 1) {
-    if (!ctx->inv_fork) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->inv_fork, hipEventDisableTiming));
-    for (int g = 0; g < G; ++g) {
-      if (!ctx->inv_stream[g]) HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->inv_stream[g], hipStreamNonBlocking));
-      if (!ctx->inv_join[g]) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->inv_join[g], hipEventDisableTiming));
-    }
-    HIP_TRY(ctx, hipEventRecord(ctx->inv_fork, s));
-    for (int g = 0; g < G; ++g) HIP_TRY(ctx, hipStreamWaitEvent(ctx->inv_stream[g], ctx->inv_fork, 0));
+  // Group 0 sweeps on the caller's stream; every further group on an internal stream forked from
+  // it and joined back with events.  Each group also has a side stream for its off-chain updates.
+  // All internal streams have the default priority.
+  if (G > 1 && !ctx->inv_fork) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->inv_fork, hipEventDisableTiming));
+  for (int g = 0; g < G; ++g) {
+    if (g > 0 && !ctx->inv_stream[g]) HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->inv_stream[g], hipStreamNonBlocking));
+    if (g > 0 && !ctx->inv_join[g]) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->inv_join[g], hipEventDisableTiming));
+    if (!ctx->inv_side[g]) HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->inv_side[g], hipStreamNonBlocking));
   }
-  auto gstream = [&](int g) { return G > 1 ? ctx->inv_stream[g] : s; };
+  if (G > 1) {
+    HIP_TRY(ctx, hipEventRecord(ctx->inv_fork, s));
+    for (int g = 1; g < G; ++g) HIP_TRY(ctx, hipStreamWaitEvent(ctx->inv_stream[g], ctx->inv_fork, 0));
+  }
+  auto gstream = [&](int g) { return g > 0 ? ctx->inv_stream[g] : s; };
 
   // per-call tables of every group: [InvMat x n_g] then [TileDesc x n_large_g]
   std::vector<const InvMat*> d_mats(G);
@@ -877,11 +904,11 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         M.nblk = ceil_div(M.d, NB);
         M.ldp = M.nblk * NB;
         M.Wt = wsf + Gp.ws_base + Gp.ws_off[m];
-        M.Zt = M.Wt + size_t(ctx->inv_agg) * NB * M.ldp;
-        M.Q = M.Zt + size_t(ctx->inv_agg) * NB * M.ldp;
+        M.Zt = M.Wt + size_t(2 * ctx->inv_agg) * NB * M.ldp;
+        M.Q = M.Zt + size_t(2 * ctx->inv_agg) * NB * M.ldp;
         TileDesc& D = hd[m];
-        D.a = rowmajor_operand(M.Wt, ctx->inv_agg * NB, M.ldp, M.ldp);
-        D.b = rowmajor_operand(M.Zt, ctx->inv_agg * NB, M.ldp, M.ldp);
+        D.a = rowmajor_operand(M.Wt, 2 * ctx->inv_agg * NB, M.ldp, M.ldp);
+        D.b = rowmajor_operand(M.Zt, 2 * ctx->inv_agg * NB, M.ldp, M.ldp);
         D.out = M.X; D.ldo = M.d; D.M = D.N = M.d;
         D.sym = 1; D.mirror = MIRROR_DIAG_TILE; D.alpha = -1.f; D.beta = 1.f;
       } else {
@@ -908,12 +935,24 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       launch_gj_init(d_mats[g], Gp.d_init, Gp.n_init, gamma, gs);
     }
   }
-  // the groups' sweeps are issued step by step so that their kernels interleave in time
+  // The groups' sweeps are issued step by step so that their kernels interleave in time.
+  // Order on a group's chain: pivot, panel, inner update [, look-ahead update].  The off-chain
+  // update of an outer block is queued on the side stream behind that look-ahead update.
+  // It shares tiles and panel buffers only with the chain's NEXT look-ahead update and what
+  // follows it, so the chain waits for the previous off-chain update right before that launch.
+  std::vector<int> last_rest(G, -1);    // step of the group's latest off-chain update
+  auto upd_launch = [&](int g, int kind, int step, hipStream_t st) {
+    InvertGroup& Gp = P.groups[g];
+    const int o0 = Gp.upd_off[kind][step], cnt = Gp.upd_off[kind][step + 1] - o0;
+    if (cnt <= 0) return;
+    ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, st);
+    launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_upd[kind]) + o0, cnt, 0, st);
+  };
   for (int step = 0; step < max_steps; ++step)
     for (int g = 0; g < G; ++g) {
       InvertGroup& Gp = P.groups[g];
       if (step >= Gp.nsteps) continue;
-      hipStream_t gs = gstream(g);
+      hipStream_t gs = gstream(g), side = ctx->inv_side[g];
       {
         ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
         launch_gj_pivot(d_mats[g], 0, Gp.active[step], step, gamma, 0, gs);
@@ -923,23 +962,36 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         launch_gj_panel(d_mats[g], static_cast<const MatJobH*>(Gp.d_panel) + Gp.panel_off[step],
                         Gp.panel_off[step + 1] - Gp.panel_off[step], step, gs);
       }
-      {
-        ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, gs);
-        launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_upd) + Gp.upd_off[step],
-                         Gp.upd_off[step + 1] - Gp.upd_off[step], 0, gs);
+      const bool has_ahead = Gp.upd_off[UPD_AHEAD][step + 1] > Gp.upd_off[UPD_AHEAD][step];
+      const bool has_rest = Gp.upd_off[UPD_REST][step + 1] > Gp.upd_off[UPD_REST][step];
+      upd_launch(g, UPD_INNER, step, gs);
+      if (has_ahead) {
+        if (last_rest[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_rest[last_rest[g]], 0));
+        upd_launch(g, UPD_AHEAD, step, gs);
+      }
+      if (has_rest) {
+        // started behind the look-ahead update so that it fills the machine during the next
+        // sweeps' pivot and panel kernels instead of competing with the chain's own updates
+        if (!Gp.ev_panel[step]) HIP_TRY(ctx, hipEventCreateWithFlags(&Gp.ev_panel[step], hipEventDisableTiming));
+        if (!Gp.ev_rest[step]) HIP_TRY(ctx, hipEventCreateWithFlags(&Gp.ev_rest[step], hipEventDisableTiming));
+        HIP_TRY(ctx, hipEventRecord(Gp.ev_panel[step], gs));
+        HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_panel[step], 0));
+        upd_launch(g, UPD_REST, step, side);
+        HIP_TRY(ctx, hipEventRecord(Gp.ev_rest[step], side));
+        last_rest[g] = step;
       }
     }
   for (int g = 0; g < G; ++g) {
     InvertGroup& Gp = P.groups[g];
     if (!Gp.n_large) continue;
+    if (last_rest[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gstream(g), Gp.ev_rest[last_rest[g]], 0));
     ScopedTiming tm(ctx, KFAC_K_INV_FINISH, gstream(g));
     launch_gj_finish(d_mats[g], Gp.d_finish, Gp.n_finish, gstream(g));
   }
-  if (G > 1)
-    for (int g = 0; g < G; ++g) {
-      HIP_TRY(ctx, hipEventRecord(ctx->inv_join[g], ctx->inv_stream[g]));
-      HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->inv_join[g], 0));
-    }
+  for (int g = 1; g < G; ++g) {
+    HIP_TRY(ctx, hipEventRecord(ctx->inv_join[g], ctx->inv_stream[g]));
+    HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->inv_join[g], 0));
+  }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
 }
