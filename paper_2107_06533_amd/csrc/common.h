@@ -98,13 +98,25 @@ struct ReduceJob {
 constexpr int NB = 128;   // pivot block order of the blocked symmetric sweep
 
 struct InvMat {
-  const float* F;   // input [d, d]
-  float* X;         // output / in-place work matrix [d, d]
+  const float* F;   // input [d, d] (whole matrices only)
+  float* X;         // work matrix, or a diagonal sub-matrix of it: element (i, j) at X[i*ld + j]
   float* Wt;        // panel workspace [NB][ldp]: new column panel (scaled by the inverse pivot)
   float* Zt;        // panel workspace [NB][ldp]: old column panel
   float* Q;         // inverse pivot block [NB][NB]
+  float* QB;        // sub-matrix views: full symmetric inverse of the swept view, [d][ldp]
   int32_t* info;    // may be null
-  int32_t d, ldp, nblk, pad;
+  int32_t d, ld, ldp;
+  int32_t info_base;   // row of the whole matrix at which this view starts
+  uint32_t xelems;     // floats from X to the end of the allocation behind it (buffer range checks)
+  int32_t pad;
+};
+
+// One block column of a whole matrix being moved between the matrix and a k-major panel buffer:
+// buf[k][i] <-> column c0 + k, row i of the symmetric matrix (lower triangle storage), k < w.
+struct PanelMove {
+  float* X;
+  float* buf;
+  int32_t d, ldp, c0, w;
 };
 
 }  // namespace kfac

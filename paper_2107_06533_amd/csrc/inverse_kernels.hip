@@ -88,7 +88,7 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
   const InvMat Mx = mats[mat0 + blockIdx.x];
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int li = lane & 31, lh = lane >> 5;
-  const int d = Mx.d;
+  const int d = Mx.d, ld = small ? Mx.d : Mx.ld;
   const int k0 = small ? 0 : step * NB;
   const int n = small ? d : (d - k0 < NB ? d - k0 : NB);
   const int nsb = (n + SB - 1) / SB;
@@ -96,14 +96,14 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
 
   // lower triangle -> full symmetric block in LDS, identity past n.  Loads go out in batches of
   // 32 per thread (range-checked buffer loads; skipped elements cost no memory traffic).
-  const rsrc_t rs_src = make_rsrc(small ? Mx.F : Mx.X, (uint32_t)d * (uint32_t)d * 4u);
+  const rsrc_t rs_src = make_rsrc(small ? Mx.F : Mx.X, small ? (uint32_t)d * (uint32_t)d * 4u : Mx.xelems * 4u);
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     float v[32];
 #pragma unroll
     for (int u = 0; u < 32; ++u) {
       const int i = (t >> 7) + 2 * (b * 32 + u), j = t & (NB - 1);
-      v[u] = buf_load(rs_src, (i < n && j <= i) ? ((uint32_t)(k0 + i) * (uint32_t)d + (uint32_t)(k0 + j)) * 4u : OOB_OFFSET);
+      v[u] = buf_load(rs_src, (i < n && j <= i) ? ((uint32_t)(k0 + i) * (uint32_t)ld + (uint32_t)(k0 + j)) * 4u : OOB_OFFSET);
     }
 #pragma unroll
     for (int u = 0; u < 32; ++u) {
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
   }
   if (t == 0 && Mx.info) {
     if (small) *Mx.info = bad;                                // whole matrix: sole writer
-    else if (bad && *Mx.info == 0) *Mx.info = k0 + bad;       // first failing sweep wins (zeroed by the init kernel)
+    else if (bad && *Mx.info == 0) *Mx.info = Mx.info_base + k0 + bad;   // first failing sweep wins (zeroed by the init kernel)
   }
 
   gf_ptr X = as_global(Mx.X);
@@ -189,10 +189,10 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
     const bool in = i < n && j < n;
     const float v = i >= j ? S[i * SP + j] : S[j * SP + i];
     if (small) {
-      if (in) X[(size_t)i * d + j] = -v;
+      if (in) X[(size_t)i * ld + j] = -v;
     } else {
       Q[i * NB + j] = in ? -v : 0.f;
-      if (in) X[(size_t)(k0 + i) * d + k0 + j] = v;
+      if (in) X[(size_t)(k0 + i) * ld + k0 + j] = v;
     }
   }
 }
@@ -211,6 +211,7 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
   const int it = J.bi, slot = J.aux;   // slot: which 128 rows of the aggregated panel buffers this sweep fills
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int d = Mx.d, ldp = Mx.ldp;
+  const uint32_t ld = (uint32_t)Mx.ld;
   const int k0 = step * NB, i0 = it * BM;
   const int kb = d - k0 < NB ? d - k0 : NB;
   const bool above = it < step;
@@ -229,8 +230,9 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
   // Buffer resources: Q is a dense 128 x 128 block; X is cut at the pivot block's last row when the
   // panel tile is read along rows, so rows of a ragged last pivot block read 0.
   const rsrc_t rs_q = make_rsrc(Mx.Q, NB * NB * 4u);
-  const rsrc_t rs_x = make_rsrc(Mx.X, (uint32_t)(above ? k0 + kb : d) * (uint32_t)d * 4u);
-  const uint32_t d4 = (uint32_t)d * 4u;
+  const uint32_t cut = (uint32_t)(k0 + kb) * ld;
+  const rsrc_t rs_x = make_rsrc(Mx.X, (above && cut < Mx.xelems ? cut : Mx.xelems) * 4u);
+  const uint32_t d4 = ld * 4u;
   float rq[NU], rz[NU];
   auto issue = [&](int kk0) {
 #pragma unroll
@@ -241,9 +243,10 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
       for (int u = 0; u < NU; ++u) rz[u] = buf_load(rs_x, base + (uint32_t)(2 * u) * d4);
     } else {
       const int kk = kk0 + kl;
-      const uint32_t base = kk < kb ? (uint32_t)(k0 + kk) * 4u : OOB_OFFSET;   // rows i >= d fall off the end
+      const uint32_t base = kk < kb ? (uint32_t)(k0 + kk) * 4u : OOB_OFFSET;
 #pragma unroll
-      for (int u = 0; u < NU; ++u) rz[u] = buf_load(rs_x, base + (uint32_t)(i0 + mg + MG * u) * d4);
+      for (int u = 0; u < NU; ++u)     // rows past the (sub-)matrix read 0
+        rz[u] = buf_load(rs_x, i0 + mg + MG * u < d ? base + (uint32_t)(i0 + mg + MG * u) * d4 : OOB_OFFSET);
     }
   };
 
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
 
   // acc(m, i) = W[i][m]: new panel entry for matrix row/col i0+i and pivot column k0+m
   gf_ptr Wt = as_global(Mx.Wt);
-  const rsrc_t rs_o = make_rsrc(Mx.X, (uint32_t)d * d4);
+  const rsrc_t rs_o = make_rsrc(Mx.X, Mx.xelems * 4u);
 #pragma unroll
   for (int qd = 0; qd < 4; ++qd) {
     const int mb0 = wm * 64 + (qd >> 1) * 32, ib0 = wn * 64 + (qd & 1) * 32;
@@ -326,6 +329,121 @@ __global__ __launch_bounds__(NT) void gj_finish_kernel(const InvMat* __restrict_
   }
 }
 
+// ---- QB = +inverse of a swept sub-matrix view, full symmetric ------------------------------------
+// The view holds -inverse in its lower triangle (diagonal tiles full).  One job per 32 x 32 tile
+// (bi, bj) of the output; tiles above the diagonal are read transposed through LDS.
+__global__ __launch_bounds__(NT) void gj_qmirror_kernel(const InvMat* __restrict__ mats,
+                                                        const MatJob* __restrict__ jobs, int njobs) {
+  __shared__ float tile[32][33];
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const MatJob J = jobs[g];
+  const InvMat Mx = mats[J.mat];
+  const int d = Mx.d, ld = Mx.ld, ldq = Mx.ldp;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  const bool upper = J.bi < J.bj;
+  const int si = (upper ? J.bj : J.bi) * 32, sj = (upper ? J.bi : J.bj) * 32;   // source tile in the lower triangle
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int li = ty + 8 * r;
+    const int i = si + li, j = sj + tx;
+    float v = 0.f;
+    if (i < d && j < d) {
+      // inside a diagonal 32 x 32 tile only the lower triangle is taken, which makes QB exactly symmetric
+      const int hi = i > j ? i : j, lo = i > j ? j : i;
+      v = -Mx.X[(size_t)hi * ld + lo];
+    }
+    tile[li][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int li = ty + 8 * r;
+    const int i = J.bi * 32 + li, j = J.bj * 32 + tx;
+    if (i < d && j < d) Mx.QB[(size_t)i * ldq + j] = upper ? tile[tx][li] : tile[li][tx];
+  }
+}
+
+// ---- block column <-> k-major panel buffer ---------------------------------------------------------
+// Grid (jobs, 32-wide k chunks): one workgroup moves a 128 (i) x 32 (k) piece of the 128-row tile
+// `it` of the whole matrix outside the block column [c0, c0 + w).  Tiles above the block column
+// live in block rows c0.. of the lower triangle (plain 2-D copy); tiles below are transposed
+// through LDS.  to_matrix = 0: buf <- matrix (columns past d are zero-filled); 1: matrix <- buf.
+__global__ __launch_bounds__(NT) void gj_move_kernel(const PanelMove* __restrict__ moves,
+                                                     const MatJob* __restrict__ jobs, int njobs, int to_matrix) {
+  __shared__ float tile[4][32][33];
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const MatJob J = jobs[g];
+  const PanelMove Mv = moves[J.mat];
+  const int d = Mv.d, ldp = Mv.ldp, c0 = Mv.c0, w = Mv.w;
+  const int kt = blockIdx.y * 32;
+  if (kt >= w) return;
+  const int i0 = J.bi * BM;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  gf_ptr X = as_global(Mv.X);
+  gf_ptr B = as_global(Mv.buf);
+  float v[4][4];
+  if (i0 < c0) {
+    // above: buf[k][i] <-> X[(c0 + k) * d + i], both contiguous in i
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int k = kt + ty + 8 * r, i = i0 + tx + 32 * q;
+        v[r][q] = 0.f;
+        if (k < w && i < d) v[r][q] = to_matrix ? B[(size_t)k * ldp + i] : X[(size_t)(c0 + k) * d + i];
+      }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int k = kt + ty + 8 * r, i = i0 + tx + 32 * q;
+        if (k >= w) continue;
+        if (to_matrix) {
+          if (i < d) X[(size_t)(c0 + k) * d + i] = v[r][q];
+        } else {
+          B[(size_t)k * ldp + i] = v[r][q];
+        }
+      }
+    return;
+  }
+  // below: buf[k][i] <-> X[i * d + c0 + k]; q = 32-row group of i, a = slow index inside a 32 x 32 tile
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int a = ty + 8 * r;
+      v[q][r] = 0.f;
+      if (to_matrix) {            // source rows k, columns i
+        const int k = kt + a, i = i0 + 32 * q + tx;
+        if (k < w) v[q][r] = B[(size_t)k * ldp + i];
+      } else {                    // source rows i, columns k
+        const int i = i0 + 32 * q + a, k = kt + tx;
+        if (i < d && k < w) v[q][r] = X[(size_t)i * d + c0 + k];
+      }
+    }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) tile[q][ty + 8 * r][tx] = v[q][r];
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int a = ty + 8 * r;
+      const float x = tile[q][tx][a];
+      if (to_matrix) {            // destination rows i, columns k
+        const int i = i0 + 32 * q + a, k = kt + tx;
+        if (i < d && k < w) X[(size_t)i * d + c0 + k] = x;
+      } else {                    // destination rows k, columns i
+        const int k = kt + a, i = i0 + 32 * q + tx;
+        if (k < w) B[(size_t)k * ldp + i] = x;
+      }
+    }
+}
+
 void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma, hipStream_t s) {
   if (njobs <= 0) return;
   hipLaunchKernelGGL(gj_init_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, gamma);
@@ -337,6 +455,14 @@ void launch_gj_pivot(const InvMat* mats, int mat0, int nmats, int step, float ga
 void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s) {
   if (njobs <= 0) return;
   hipLaunchKernelGGL(gj_panel_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, step);
+}
+void launch_gj_qmirror(const InvMat* mats, const void* jobs, int njobs, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(gj_qmirror_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs);
+}
+void launch_gj_move(const PanelMove* moves, const void* jobs, int njobs, int kchunks, int to_matrix, hipStream_t s) {
+  if (njobs <= 0 || kchunks <= 0) return;
+  hipLaunchKernelGGL(gj_move_kernel, dim3(njobs, kchunks), dim3(NT), 0, s, moves, (const MatJob*)jobs, njobs, to_matrix);
 }
 void launch_gj_finish(const InvMat* mats, const void* jobs, int njobs, hipStream_t s) {
   if (njobs <= 0) return;

@@ -21,8 +21,8 @@ struct MatJobH {
   int32_t mat, bi, bj, aux;
 };
 
-// The three update lists of a sweep step (see schedule_invert).
-enum { UPD_INNER = 0, UPD_AHEAD = 1, UPD_REST = 2 };
+// The three update lists of an outer block (see schedule_invert).
+enum { UPD_DIAG = 0, UPD_COL = 1, UPD_REST = 2 };
 
 inline int ceil_div(int64_t a, int64_t b) { return int((a + b - 1) / b); }
 
@@ -54,17 +54,20 @@ struct FactorPlan {
 struct InvertGroup {
   std::vector<int> idx;              // caller indices of the group's matrices
   std::vector<int> order;            // sorted position -> position in idx (large first, descending d)
-  int n_large = 0, n_small = 0, nsteps = 0;
-  std::vector<int> active;           // [step] number of large matrices still being swept
-  std::vector<int> panel_off;
-  std::vector<int> upd_off[3];       // [UPD_INNER / UPD_AHEAD / UPD_REST][step]
+  int n_large = 0, n_small = 0, n_ob = 0, n_views = 0;
+  std::vector<int> view_off, n_in_ob;            // [outer block]
+  std::vector<int> sub_active;                   // [outer block * agg + sub-step]
+  std::vector<int> sub_panel_off, sub_upd_off;   // [outer block * agg + sub-step (+1)]
+  std::vector<int> qm_off, mv_off, bp_off;       // [outer block (+1)]
+  std::vector<int> upd_off[3];                   // [UPD_DIAG / UPD_COL / UPD_REST][outer block (+1)]
   std::vector<size_t> ws_off;        // per large matrix: float offset of its workspace inside the group's region
   void* d_init = nullptr; int n_init = 0;
   void* d_finish = nullptr; int n_finish = 0;
-  void* d_panel = nullptr;
+  void* d_sub_panel = nullptr; void* d_sub_upd = nullptr;
+  void* d_qm = nullptr; void* d_mv = nullptr; void* d_bp = nullptr;
   void* d_upd[3] = {nullptr, nullptr, nullptr};
-  std::vector<hipEvent_t> ev_panel, ev_rest;   // [step], created on first use
-  DynTable tab;                      // [InvMat x n][TileDesc x n_large]
+  std::vector<hipEvent_t> ev_chain, ev_col, ev_rest;   // [outer block], created on first use
+  DynTable tab;                      // [InvMat x n][InvMat x views][PanelMove x 2 views][TileDesc x (2 views + n_large)]
   size_t ws_floats = 0, ws_base = 0;
 };
 
@@ -363,9 +366,12 @@ void release(FactorPlan& p) {
 }
 void release(InvertPlan& p) {
   for (InvertGroup& g : p.groups) {
-    free_dev(g.d_init); free_dev(g.d_finish); free_dev(g.d_panel); free_table(g.tab);
+    free_dev(g.d_init); free_dev(g.d_finish); free_dev(g.d_sub_panel); free_dev(g.d_sub_upd);
+    free_dev(g.d_qm); free_dev(g.d_mv); free_dev(g.d_bp);
     for (int k = 0; k < 3; ++k) free_dev(g.d_upd[k]);
-    for (hipEvent_t e : g.ev_panel) if (e) (void)hipEventDestroy(e);
+    free_table(g.tab);
+    for (hipEvent_t e : g.ev_chain) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g.ev_col) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : g.ev_rest) if (e) (void)hipEventDestroy(e);
   }
   p = InvertPlan{};
@@ -451,26 +457,49 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
 }
 
 // ------------------------------------------------------------------------------- invert plan
-// Sweeps are aggregated in outer blocks of `agg` pivot blocks.  Sweep s updates at once only the
-// tiles in the block rows/columns of its own outer block (UPD_INNER, rank 128).  After the last
-// sweep of an outer block every other tile gets the whole block's panels in one rank-(agg*128)
-// update, split in two lists: the tiles in the rows/columns of the NEXT outer block (UPD_AHEAD),
-// which the next sweeps need at once, and all the others (UPD_REST), which nothing touches before
-// the next outer block ends and which therefore run beside the next sweeps on a second stream.
+// Two-level blocked symmetric sweep.  A matrix is cut in outer blocks of `agg` pivot blocks
+// (agg*128 rows).  For outer block b, with D its diagonal sub-matrix and Z the rest of its block
+// column:
+//   1. D is swept in place by the one-level algorithm (pivot, panel, rank-128 update, only on the
+//      <= agg x agg tiles of D): D <- -D^-1;
+//   2. QB = D^-1 as a full symmetric matrix;  Zt = Z^T gathered k-major;
+//   3. Wt = QB Zt (one GEMM with K = agg*128), scattered back into the block column;
+//   4. every tile outside the outer block gets  M_ij -= W_i Z_j^T  (K = agg*128), in three lists:
+//      the diagonal sub-matrix of the NEXT outer block (UPD_DIAG), which step 1 of the next block
+//      needs at once; the rest of the next block's rows/columns (UPD_COL), needed by its step 2;
+//      and all the others (UPD_REST), which nothing touches before the next block's step 4.
+//      UPD_COL and UPD_REST run on a second stream beside the next block's latency-bound step 1.
 // The panel buffers of consecutive outer blocks alternate between two halves of the workspace so
 // that the off-chain update can still read its panels while the next ones are written.
+// All matrices of a group advance in lockstep: one launch per step covers every matrix that
+// still has that step.  Large matrices are sorted by descending size, so the matrices taking part
+// in sub-step t of outer block b are always a prefix of the block's view list.
 struct InvertSchedule {
   std::vector<int> order;
-  int n_large = 0, n_small = 0, nsteps = 0;
-  std::vector<int> active, panel_off;
-  std::vector<int> upd_off[3];
+  int n_large = 0, n_small = 0, n_ob = 0, n_views = 0;
+  std::vector<int> nblk, ldp, nob;
   std::vector<size_t> ws_off;
-  std::vector<int> nblk, ldp;
-  std::vector<MatJobH> init, finish, panel;
-  std::vector<TileJob> upd[3];
+  std::vector<int> view_off, n_in_ob, sub_active, sub_panel_off, sub_upd_off, qm_off, mv_off, bp_off;
+  std::vector<int> upd_off[3];
+  std::vector<MatJobH> init, finish, sub_panel, qm, mv;
+  std::vector<TileJob> sub_upd, bp, upd[3];
   size_t ws_floats = 0;
   kfac_plan_stats stats{};
 };
+
+// workspace of one large matrix, offsets in floats
+struct InvWsLayout {
+  size_t wt, zt, swt, szt, q, qb, total;
+};
+InvWsLayout inv_ws_layout(int ldp, int agg) {
+  InvWsLayout L{};
+  const size_t big = size_t(2) * agg * NB * ldp;      // two halves of agg panels
+  const size_t sub = size_t(NB) * agg * NB;           // one panel of the diagonal sub-matrix
+  L.wt = 0; L.zt = big; L.swt = 2 * big; L.szt = 2 * big + sub; L.q = 2 * big + 2 * sub;
+  L.qb = L.q + size_t(NB) * NB;
+  L.total = L.qb + size_t(agg) * NB * agg * NB;
+  return L;
+}
 
 InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
   InvertSchedule S;
@@ -478,66 +507,105 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
   for (int i = 0; i < n; ++i) S.order[i] = i;
   std::stable_sort(S.order.begin(), S.order.end(), [&](int a, int b) { return dims[a] > dims[b]; });
   for (int i = 0; i < n; ++i) (dims[S.order[i]] > NB ? S.n_large : S.n_small)++;
-  S.nblk.resize(S.n_large); S.ldp.resize(S.n_large); S.ws_off.resize(S.n_large);
+  S.nblk.resize(S.n_large); S.ldp.resize(S.n_large); S.nob.resize(S.n_large); S.ws_off.resize(S.n_large);
   for (int m = 0; m < S.n_large; ++m) {
     const int d = dims[S.order[m]];
     S.nblk[m] = ceil_div(d, NB);
     S.ldp[m] = S.nblk[m] * NB;
+    S.nob[m] = ceil_div(S.nblk[m], agg);
     S.ws_off[m] = S.ws_floats;
-    S.ws_floats += size_t(4) * agg * NB * S.ldp[m] + size_t(NB) * NB;   // Wt, Zt: two halves of agg panels each; Q
-    S.nsteps = std::max(S.nsteps, S.nblk[m]);
+    S.ws_floats += inv_ws_layout(S.ldp[m], agg).total;
+    S.n_ob = std::max(S.n_ob, S.nob[m]);
     for (int bi = 0; bi < S.nblk[m]; ++bi)
       for (int bj = 0; bj <= bi; ++bj) S.init.push_back({m, bi, bj, 0});
     const int t32 = ceil_div(d, 32);
     for (int bi = 0; bi < t32; ++bi)
       for (int bj = 0; bj <= bi; ++bj) S.finish.push_back({m, bi, bj, 0});
   }
-  S.active.assign(S.nsteps, 0);
-  S.panel_off.assign(S.nsteps + 1, 0);
-  for (int k = 0; k < 3; ++k) S.upd_off[k].assign(S.nsteps + 1, 0);
-  int n_upd_launches = 0;
-  for (int s = 0; s < S.nsteps; ++s) {
-    for (int m = 0; m < S.n_large; ++m) {
-      if (S.nblk[m] <= s) continue;
-      S.active[s]++;
+  S.view_off.assign(S.n_ob + 1, 0); S.n_in_ob.assign(S.n_ob, 0);
+  for (int b = 0; b < S.n_ob; ++b) {
+    for (int m = 0; m < S.n_large; ++m) S.n_in_ob[b] += S.nob[m] > b;
+    S.view_off[b + 1] = S.view_off[b] + S.n_in_ob[b];
+  }
+  S.n_views = S.view_off[S.n_ob];
+  S.sub_active.assign(size_t(S.n_ob) * agg, 0);
+  S.sub_panel_off.assign(size_t(S.n_ob) * agg + 1, 0);
+  S.sub_upd_off.assign(size_t(S.n_ob) * agg + 1, 0);
+  S.qm_off.assign(S.n_ob + 1, 0); S.mv_off.assign(S.n_ob + 1, 0); S.bp_off.assign(S.n_ob + 1, 0);
+  for (int k = 0; k < 3; ++k) S.upd_off[k].assign(S.n_ob + 1, 0);
+  int64_t launches = 0;
+  for (int b = 0; b < S.n_ob; ++b) {
+    const int ob0 = b * agg;
+    // ---- step 1: sweeps of the diagonal sub-matrices (views)
+    for (int t = 0; t < agg; ++t) {
+      const int st = b * agg + t;
+      for (int m = 0; m < S.n_in_ob[b]; ++m) {
+        const int v = S.view_off[b] + m;
+        const int d = dims[S.order[m]];
+        const int nsub = std::min(agg, S.nblk[m] - ob0);
+        const int dimB = std::min(agg * NB, d - ob0 * NB);
+        if (t >= nsub) continue;
+        S.sub_active[st]++;
+        const int kb = std::min(NB, dimB - t * NB);
+        for (int it = 0; it < nsub; ++it)
+          if (it != t) S.sub_panel.push_back({v, it, 0, 0});
+        for (int bi = 0; bi < nsub; ++bi)
+          for (int bj = 0; bj <= bi; ++bj) {
+            if (bi == t || bj == t) continue;
+            TileJob j{};
+            j.desc = v; j.bi = bi; j.bj = bj; j.kbeg = 0; j.kend = kb; j.part = -1;
+            S.sub_upd.push_back(j);
+            S.stats.mfma_flops += int64_t(ceil_div(kb, KC) * KC) * active_blocks(dimB, dimB, bi, bj, true) * 32 * 32 * 2;
+          }
+        S.stats.mfma_flops += int64_t(nsub - 1) * NB * 16 * 32 * 32 * 2;   // panel products
+      }
+      S.sub_panel_off[st + 1] = int(S.sub_panel.size());
+      S.sub_upd_off[st + 1] = int(S.sub_upd.size());
+      launches += (S.sub_active[st] > 0) + (S.sub_panel_off[st + 1] > S.sub_panel_off[st]) + (S.sub_upd_off[st + 1] > S.sub_upd_off[st]);
+    }
+    // ---- steps 2-4 for the matrices that have more than one outer block
+    for (int m = 0; m < S.n_in_ob[b]; ++m) {
+      if (S.nob[m] < 2) continue;
+      const int v = S.view_off[b] + m;
       const int d = dims[S.order[m]];
-      const int kb = std::min(NB, d - s * NB);
-      const int half = (s / agg) & 1;                 // which half of the panel buffers this outer block fills
-      const int slot = half * agg + s % agg;
-      const int ob0 = (s / agg) * agg, ob1 = std::min(ob0 + agg, S.nblk[m]);   // outer block [ob0, ob1)
-      const int nb1 = std::min(ob1 + agg, S.nblk[m]);                            // next outer block [ob1, nb1)
-      for (int it = 0; it < S.nblk[m]; ++it)
-        if (it != s) S.panel.push_back({m, it, 0, slot});
-      auto in_ob = [&](int b) { return b >= ob0 && b < ob1; };
-      auto in_next = [&](int b) { return b >= ob1 && b < nb1; };
-      const bool last_of_block = s == ob1 - 1;
-      const int kend_outer = (ob1 - 1 - ob0) * NB + std::min(NB, d - (ob1 - 1) * NB);
+      const int ob1 = std::min(ob0 + agg, S.nblk[m]), nb1 = std::min(ob1 + agg, S.nblk[m]);
+      const int dimB = std::min(agg * NB, d - ob0 * NB);
+      const int half = b & 1;
+      auto in_ob = [&](int x) { return x >= ob0 && x < ob1; };
+      auto in_next = [&](int x) { return x >= ob1 && x < nb1; };
+      const int q32 = ceil_div(dimB, 32);
+      for (int bi = 0; bi < q32; ++bi)
+        for (int bj = 0; bj < q32; ++bj) S.qm.push_back({v, bi, bj, 0});
+      for (int it = 0; it < S.nblk[m]; ++it) {
+        if (in_ob(it)) continue;
+        S.mv.push_back({2 * v, it, 0, 0});
+        for (int bi = 0; bi < ceil_div(dimB, BM); ++bi) {
+          TileJob j{};
+          j.desc = S.n_views + v; j.bi = bi; j.bj = it; j.kbeg = 0; j.kend = dimB; j.part = -1;
+          S.bp.push_back(j);
+          S.stats.mfma_flops += int64_t(ceil_div(dimB, KC) * KC) * active_blocks(dimB, d, bi, it, false) * 32 * 32 * 2;
+        }
+      }
       for (int bi = 0; bi < S.nblk[m]; ++bi)
         for (int bj = 0; bj <= bi; ++bj) {
+          if (in_ob(bi) || in_ob(bj)) continue;
           TileJob j{};
-          j.desc = m; j.bi = bi; j.bj = bj; j.part = -1;
-          if (in_ob(bi) || in_ob(bj)) {
-            if (bi == s || bj == s) continue;
-            j.kbeg = slot * NB; j.kend = slot * NB + kb;
-            S.upd[UPD_INNER].push_back(j);
-          } else {
-            if (!last_of_block) continue;
-            j.kbeg = half * agg * NB; j.kend = j.kbeg + kend_outer;
-            S.upd[(in_next(bi) || in_next(bj)) ? UPD_AHEAD : UPD_REST].push_back(j);
-          }
-          S.stats.mfma_flops += int64_t(ceil_div(j.kend - j.kbeg, KC) * KC) * active_blocks(d, d, bi, bj, true) * 32 * 32 * 2;
+          j.desc = 2 * S.n_views + m; j.bi = bi; j.bj = bj; j.part = -1;
+          j.kbeg = half * agg * NB; j.kend = j.kbeg + dimB;
+          S.upd[(in_next(bi) && in_next(bj)) ? UPD_DIAG : (in_next(bi) || in_next(bj)) ? UPD_COL : UPD_REST].push_back(j);
+          S.stats.mfma_flops += int64_t(ceil_div(dimB, KC) * KC) * active_blocks(d, d, bi, bj, true) * 32 * 32 * 2;
         }
-      S.stats.mfma_flops += int64_t(S.nblk[m] - 1) * NB * 16 * 32 * 32 * 2;   // panel products
     }
-    S.panel_off[s + 1] = int(S.panel.size());
+    S.qm_off[b + 1] = int(S.qm.size()); S.mv_off[b + 1] = int(S.mv.size()); S.bp_off[b + 1] = int(S.bp.size());
+    launches += (S.qm_off[b + 1] > S.qm_off[b]) + 2 * (S.mv_off[b + 1] > S.mv_off[b]) + (S.bp_off[b + 1] > S.bp_off[b]);
     for (int k = 0; k < 3; ++k) {
-      S.upd_off[k][s + 1] = int(S.upd[k].size());
-      n_upd_launches += S.upd_off[k][s + 1] > S.upd_off[k][s];
+      S.upd_off[k][b + 1] = int(S.upd[k].size());
+      launches += S.upd_off[k][b + 1] > S.upd_off[k][b];
     }
   }
-  S.stats.n_jobs = int64_t(S.init.size() + S.finish.size() + S.panel.size()) + S.n_small;
-  for (int k = 0; k < 3; ++k) S.stats.n_jobs += int64_t(S.upd[k].size());
-  S.stats.n_launches = (S.n_small ? 1 : 0) + (S.n_large ? 2 + 2 * S.nsteps + n_upd_launches : 0);
+  S.stats.n_jobs = int64_t(S.init.size() + S.finish.size() + S.sub_panel.size() + S.sub_upd.size() + S.qm.size() +
+                           2 * S.mv.size() + S.bp.size() + S.upd[0].size() + S.upd[1].size() + S.upd[2].size()) + S.n_small;
+  S.stats.n_launches = (S.n_small ? 1 : 0) + (S.n_large ? 2 + launches : 0);
   S.stats.ws_bytes = int64_t(S.ws_floats * sizeof(float));
   return S;
 }
@@ -840,10 +908,13 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       std::vector<int32_t> gd;
       for (int i : Gp.idx) gd.push_back(dims[i]);
       InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), ctx->inv_agg);
-      Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.nsteps = S.nsteps;
-      Gp.active = S.active; Gp.panel_off = S.panel_off; Gp.ws_off = S.ws_off;
+      Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.n_ob = S.n_ob; Gp.n_views = S.n_views;
+      Gp.view_off = S.view_off; Gp.n_in_ob = S.n_in_ob; Gp.sub_active = S.sub_active;
+      Gp.sub_panel_off = S.sub_panel_off; Gp.sub_upd_off = S.sub_upd_off;
+      Gp.qm_off = S.qm_off; Gp.mv_off = S.mv_off; Gp.bp_off = S.bp_off;
       for (int k = 0; k < 3; ++k) Gp.upd_off[k] = S.upd_off[k];
-      Gp.ev_panel.assign(S.nsteps, nullptr); Gp.ev_rest.assign(S.nsteps, nullptr);
+      Gp.ws_off = S.ws_off;
+      Gp.ev_chain.assign(S.n_ob, nullptr); Gp.ev_col.assign(S.n_ob, nullptr); Gp.ev_rest.assign(S.n_ob, nullptr);
       Gp.n_init = int(S.init.size()); Gp.n_finish = int(S.finish.size());
       Gp.ws_floats = S.ws_floats;
       Gp.ws_base = P.ws_floats;
@@ -852,11 +923,16 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       P.stats.mfma_flops += S.stats.mfma_flops; P.stats.ws_bytes += S.stats.ws_bytes;
       if (!ctx->host_only) {
         kfac_status st;
-        if ((st = upload_static(ctx, &Gp.d_init, S.init.data(), S.init.size() * sizeof(MatJobH))) != KFAC_OK) return st;
-        if ((st = upload_static(ctx, &Gp.d_finish, S.finish.data(), S.finish.size() * sizeof(MatJobH))) != KFAC_OK) return st;
-        if ((st = upload_static(ctx, &Gp.d_panel, S.panel.data(), S.panel.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        auto up = [&](void** dev, const void* src, size_t bytes) { return upload_static(ctx, dev, src, bytes); };
+        if ((st = up(&Gp.d_init, S.init.data(), S.init.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = up(&Gp.d_finish, S.finish.data(), S.finish.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = up(&Gp.d_sub_panel, S.sub_panel.data(), S.sub_panel.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = up(&Gp.d_sub_upd, S.sub_upd.data(), S.sub_upd.size() * sizeof(TileJob))) != KFAC_OK) return st;
+        if ((st = up(&Gp.d_qm, S.qm.data(), S.qm.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = up(&Gp.d_mv, S.mv.data(), S.mv.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = up(&Gp.d_bp, S.bp.data(), S.bp.size() * sizeof(TileJob))) != KFAC_OK) return st;
         for (int k = 0; k < 3; ++k)
-          if ((st = upload_static(ctx, &Gp.d_upd[k], S.upd[k].data(), S.upd[k].size() * sizeof(TileJob))) != KFAC_OK) return st;
+          if ((st = up(&Gp.d_upd[k], S.upd[k].data(), S.upd[k].size() * sizeof(TileJob))) != KFAC_OK) return st;
       }
     }
     P.valid = true;
@@ -883,49 +959,80 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   }
   auto gstream = [&](int g) { return g > 0 ? ctx->inv_stream[g] : s; };
 
-  // per-call tables of every group: [InvMat x n_g] then [TileDesc x n_large_g]
-  std::vector<const InvMat*> d_mats(G);
+  // per-call tables of every group: [InvMat x n_g][InvMat x views][PanelMove x 2 views][TileDesc x (2 views + n_large)]
+  std::vector<const InvMat*> d_mats(G), d_views(G);
+  std::vector<const PanelMove*> d_moves(G);
   std::vector<const TileDesc*> d_descs(G);
   float* wsf = static_cast<float*>(ctx->ws);
+  const int agg = ctx->inv_agg;
   for (int g = 0; g < G; ++g) {
     InvertGroup& Gp = P.groups[g];
-    const int ng = int(Gp.idx.size());
+    const int ng = int(Gp.idx.size()), nv = Gp.n_views;
     const size_t mats_bytes = sizeof(InvMat) * size_t(ng);
-    const size_t tab_bytes = mats_bytes + sizeof(TileDesc) * size_t(Gp.n_large);
+    const size_t views_bytes = sizeof(InvMat) * size_t(nv);
+    const size_t moves_bytes = sizeof(PanelMove) * size_t(2 * nv);
+    const size_t descs_bytes = sizeof(TileDesc) * size_t(2 * nv + Gp.n_large);
+    const size_t tab_bytes = mats_bytes + views_bytes + moves_bytes + descs_bytes;
     std::vector<unsigned char> img(tab_bytes, 0);
     InvMat* hm = reinterpret_cast<InvMat*>(img.data());
-    TileDesc* hd = reinterpret_cast<TileDesc*>(img.data() + mats_bytes);
+    InvMat* hv = reinterpret_cast<InvMat*>(img.data() + mats_bytes);
+    PanelMove* hp = reinterpret_cast<PanelMove*>(img.data() + mats_bytes + views_bytes);
+    TileDesc* hd = reinterpret_cast<TileDesc*>(img.data() + mats_bytes + views_bytes + moves_bytes);
     for (int m = 0; m < ng; ++m) {
       const int o = Gp.idx[Gp.order[m]];
       InvMat& M = hm[m];
-      M.F = F[o]; M.X = X[o]; M.d = dims[o];
+      M.F = F[o]; M.X = X[o]; M.d = M.ld = dims[o];
       M.info = info_dev ? info_dev + o : nullptr;
-      if (m < Gp.n_large) {
-        M.nblk = ceil_div(M.d, NB);
-        M.ldp = M.nblk * NB;
-        M.Wt = wsf + Gp.ws_base + Gp.ws_off[m];
-        M.Zt = M.Wt + size_t(2 * ctx->inv_agg) * NB * M.ldp;
-        M.Q = M.Zt + size_t(2 * ctx->inv_agg) * NB * M.ldp;
-        TileDesc& D = hd[m];
-        D.a = rowmajor_operand(M.Wt, 2 * ctx->inv_agg * NB, M.ldp, M.ldp);
-        D.b = rowmajor_operand(M.Zt, 2 * ctx->inv_agg * NB, M.ldp, M.ldp);
-        D.out = M.X; D.ldo = M.d; D.M = D.N = M.d;
-        D.sym = 1; D.mirror = MIRROR_DIAG_TILE; D.alpha = -1.f; D.beta = 1.f;
-      } else {
-        M.nblk = 1; M.ldp = NB;
+      M.xelems = uint32_t(M.d) * uint32_t(M.d);
+      M.ldp = NB;
+      if (m >= Gp.n_large) continue;
+      const int d = M.d, nblk = ceil_div(d, NB), ldp = nblk * NB, nob = ceil_div(nblk, agg);
+      const InvWsLayout L = inv_ws_layout(ldp, agg);
+      float* base = wsf + Gp.ws_base + Gp.ws_off[m];
+      M.ldp = ldp;
+      TileDesc& DU = hd[2 * nv + m];    // step 4: X -= Wt^T Zt over one half of the panel buffers
+      DU.a = rowmajor_operand(base + L.wt, 2 * agg * NB, ldp, ldp);
+      DU.b = rowmajor_operand(base + L.zt, 2 * agg * NB, ldp, ldp);
+      DU.out = M.X; DU.ldo = d; DU.M = DU.N = d;
+      DU.sym = 1; DU.mirror = MIRROR_DIAG_TILE; DU.alpha = -1.f; DU.beta = 1.f;
+      for (int b = 0; b < nob; ++b) {
+        const int v = Gp.view_off[b] + m;
+        const int c0 = b * agg * NB, dimB = std::min(agg * NB, d - c0), half = b & 1;
+        InvMat& V = hv[v];              // step 1: the diagonal sub-matrix as a matrix of its own
+        V.F = nullptr; V.X = M.X + size_t(c0) * d + c0; V.d = dimB; V.ld = d; V.ldp = agg * NB;
+        V.Wt = base + L.swt; V.Zt = base + L.szt; V.Q = base + L.q; V.QB = base + L.qb;
+        V.info = M.info; V.info_base = c0;
+        V.xelems = uint32_t(size_t(d) * d - (size_t(c0) * d + c0));
+        TileDesc& DS = hd[v];
+        DS.a = rowmajor_operand(V.Wt, NB, agg * NB, agg * NB);
+        DS.b = rowmajor_operand(V.Zt, NB, agg * NB, agg * NB);
+        DS.out = V.X; DS.ldo = d; DS.M = DS.N = dimB;
+        DS.sym = 1; DS.mirror = MIRROR_DIAG_TILE; DS.alpha = -1.f; DS.beta = 1.f;
+        float* wt_half = base + L.wt + size_t(half) * agg * NB * ldp;
+        float* zt_half = base + L.zt + size_t(half) * agg * NB * ldp;
+        hp[2 * v] = PanelMove{M.X, zt_half, d, ldp, c0, dimB};       // step 2: gather Z
+        hp[2 * v + 1] = PanelMove{M.X, wt_half, d, ldp, c0, dimB};   // step 3: scatter W
+        TileDesc& DP = hd[nv + v];      // step 3: Wt = QB Zt
+        DP.a = rowmajor_operand(V.QB, dimB, dimB, agg * NB);
+        DP.b = rowmajor_operand(zt_half, dimB, ldp, ldp);
+        DP.out = wt_half; DP.ldo = ldp; DP.M = dimB; DP.N = ldp;
+        DP.sym = 0; DP.mirror = MIRROR_NONE; DP.alpha = 1.f; DP.beta = 0.f;
       }
     }
     st = sync_table(ctx, Gp.tab, img.data(), tab_bytes, gstream(g));
     if (st != KFAC_OK) return st;
-    d_mats[g] = static_cast<const InvMat*>(Gp.tab.dev);
-    d_descs[g] = reinterpret_cast<const TileDesc*>(static_cast<const unsigned char*>(Gp.tab.dev) + mats_bytes);
+    const unsigned char* dev = static_cast<const unsigned char*>(Gp.tab.dev);
+    d_mats[g] = reinterpret_cast<const InvMat*>(dev);
+    d_views[g] = reinterpret_cast<const InvMat*>(dev + mats_bytes);
+    d_moves[g] = reinterpret_cast<const PanelMove*>(dev + mats_bytes + views_bytes);
+    d_descs[g] = reinterpret_cast<const TileDesc*>(dev + mats_bytes + views_bytes + moves_bytes);
   }
 
-  int max_steps = 0;
+  int max_ob = 0;
   for (int g = 0; g < G; ++g) {
     InvertGroup& Gp = P.groups[g];
     hipStream_t gs = gstream(g);
-    max_steps = std::max(max_steps, Gp.nsteps);
+    max_ob = std::max(max_ob, Gp.n_ob);
     if (Gp.n_small) {
       ScopedTiming tm(ctx, KFAC_K_INV_SMALL, gs);
       launch_gj_pivot(d_mats[g], Gp.n_large, Gp.n_small, 0, gamma, 1, gs);
@@ -935,52 +1042,87 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       launch_gj_init(d_mats[g], Gp.d_init, Gp.n_init, gamma, gs);
     }
   }
-  // The groups' sweeps are issued step by step so that their kernels interleave in time.
-  // Order on a group's chain: pivot, panel, inner update [, look-ahead update].  The off-chain
-  // update of an outer block is queued on the side stream behind that look-ahead update.
-  // It shares tiles and panel buffers only with the chain's NEXT look-ahead update and what
-  // follows it, so the chain waits for the previous off-chain update right before that launch.
-  std::vector<int> last_rest(G, -1);    // step of the group's latest off-chain update
-  auto upd_launch = [&](int g, int kind, int step, hipStream_t st) {
+  // The groups are issued outer block by outer block so that their kernels interleave in time.
+  // Chain of a group (its main stream), per outer block: sweep of the diagonal sub-matrix, QB,
+  // gather, panel GEMM, scatter, update of the next diagonal sub-matrix.  The other two update
+  // lists follow on the side stream.  Cross-stream order, by what the kernels touch:
+  //   gather(b)    reads the tiles UPD_COL(b-1) wrote                 -> waits for ev_col[b-1]
+  //   UPD_DIAG(b)  writes tiles that UPD_REST(b-1) also updates, and gather(b+1)/panel GEMM(b+1)
+  //                reuse the buffer half UPD_REST(b-1) reads           -> waits for ev_rest[b-1]
+  //   side stream  reads the panels of block b                         -> waits for ev_chain[b]
+  std::vector<int> last_col(G, -1), last_rest(G, -1);    // outer block of the group's latest side-stream updates
+  auto ensure_event = [&](hipEvent_t& e) { return e ? hipSuccess : hipEventCreateWithFlags(&e, hipEventDisableTiming); };
+  auto upd_launch = [&](int g, int kind, int b, hipStream_t st) {
     InvertGroup& Gp = P.groups[g];
-    const int o0 = Gp.upd_off[kind][step], cnt = Gp.upd_off[kind][step + 1] - o0;
+    const int o0 = Gp.upd_off[kind][b], cnt = Gp.upd_off[kind][b + 1] - o0;
     if (cnt <= 0) return;
     ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, st);
     launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_upd[kind]) + o0, cnt, 0, st);
   };
-  for (int step = 0; step < max_steps; ++step)
+  for (int b = 0; b < max_ob; ++b)
     for (int g = 0; g < G; ++g) {
       InvertGroup& Gp = P.groups[g];
-      if (step >= Gp.nsteps) continue;
+      if (b >= Gp.n_ob) continue;
       hipStream_t gs = gstream(g), side = ctx->inv_side[g];
-      {
-        ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
-        launch_gj_pivot(d_mats[g], 0, Gp.active[step], step, gamma, 0, gs);
+      const InvMat* views = d_views[g];
+      for (int t = 0; t < agg; ++t) {
+        const int stp = b * agg + t;
+        if (Gp.sub_active[stp] == 0) break;
+        {
+          ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
+          launch_gj_pivot(views, Gp.view_off[b], Gp.sub_active[stp], t, gamma, 0, gs);
+        }
+        if (Gp.sub_panel_off[stp + 1] > Gp.sub_panel_off[stp]) {
+          ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
+          launch_gj_panel(views, static_cast<const MatJobH*>(Gp.d_sub_panel) + Gp.sub_panel_off[stp],
+                          Gp.sub_panel_off[stp + 1] - Gp.sub_panel_off[stp], t, gs);
+        }
+        if (Gp.sub_upd_off[stp + 1] > Gp.sub_upd_off[stp]) {
+          ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, gs);
+          launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_sub_upd) + Gp.sub_upd_off[stp],
+                           Gp.sub_upd_off[stp + 1] - Gp.sub_upd_off[stp], 0, gs);
+        }
       }
-      {
+      if (Gp.qm_off[b + 1] > Gp.qm_off[b]) {
+        const int nmv = Gp.mv_off[b + 1] - Gp.mv_off[b];
+        const MatJobH* mvj = static_cast<const MatJobH*>(Gp.d_mv) + Gp.mv_off[b];
+        {
+          ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
+          launch_gj_qmirror(views, static_cast<const MatJobH*>(Gp.d_qm) + Gp.qm_off[b], Gp.qm_off[b + 1] - Gp.qm_off[b], gs);
+        }
+        if (last_col[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_col[last_col[g]], 0));
         ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
-        launch_gj_panel(d_mats[g], static_cast<const MatJobH*>(Gp.d_panel) + Gp.panel_off[step],
-                        Gp.panel_off[step + 1] - Gp.panel_off[step], step, gs);
+        launch_gj_move(d_moves[g], mvj, nmv, agg * NB / 32, 0, gs);
+        launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_bp) + Gp.bp_off[b], Gp.bp_off[b + 1] - Gp.bp_off[b], 0, gs);
+        launch_gj_move(d_moves[g] + 1, mvj, nmv, agg * NB / 32, 1, gs);
       }
-      const bool has_ahead = Gp.upd_off[UPD_AHEAD][step + 1] > Gp.upd_off[UPD_AHEAD][step];
-      const bool has_rest = Gp.upd_off[UPD_REST][step + 1] > Gp.upd_off[UPD_REST][step];
-      upd_launch(g, UPD_INNER, step, gs);
-      if (has_ahead) {
+      const bool has_diag = Gp.upd_off[UPD_DIAG][b + 1] > Gp.upd_off[UPD_DIAG][b];
+      const bool has_col = Gp.upd_off[UPD_COL][b + 1] > Gp.upd_off[UPD_COL][b];
+      const bool has_rest = Gp.upd_off[UPD_REST][b + 1] > Gp.upd_off[UPD_REST][b];
+      if (has_diag) {
         if (last_rest[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_rest[last_rest[g]], 0));
-        upd_launch(g, UPD_AHEAD, step, gs);
+        upd_launch(g, UPD_DIAG, b, gs);
       }
-      if (has_rest) {
-        // started behind the look-ahead update so that it fills the machine during the next
-        // sweeps' pivot and panel kernels instead of competing with the chain's own updates
-        if (!Gp.ev_panel[step]) HIP_TRY(ctx, hipEventCreateWithFlags(&Gp.ev_panel[step], hipEventDisableTiming));
-        if (!Gp.ev_rest[step]) HIP_TRY(ctx, hipEventCreateWithFlags(&Gp.ev_rest[step], hipEventDisableTiming));
-        HIP_TRY(ctx, hipEventRecord(Gp.ev_panel[step], gs));
-        HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_panel[step], 0));
-        upd_launch(g, UPD_REST, step, side);
-        HIP_TRY(ctx, hipEventRecord(Gp.ev_rest[step], side));
-        last_rest[g] = step;
+      if (has_col || has_rest) {
+        HIP_TRY(ctx, ensure_event(Gp.ev_chain[b]));
+        HIP_TRY(ctx, hipEventRecord(Gp.ev_chain[b], gs));
+        HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_chain[b], 0));
+        if (has_col) {
+          upd_launch(g, UPD_COL, b, side);
+          HIP_TRY(ctx, ensure_event(Gp.ev_col[b]));
+          HIP_TRY(ctx, hipEventRecord(Gp.ev_col[b], side));
+          last_col[g] = b;
+        }
+        if (has_rest) {
+          upd_launch(g, UPD_REST, b, side);
+          HIP_TRY(ctx, ensure_event(Gp.ev_rest[b]));
+          HIP_TRY(ctx, hipEventRecord(Gp.ev_rest[b], side));
+          last_rest[g] = b;
+        }
       }
     }
+  for (int g = 0; g < G; ++g)   // everything on the side stream must be done before the finish
+    if (last_col[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gstream(g), P.groups[g].ev_col[last_col[g]], 0));
   for (int g = 0; g < G; ++g) {
     InvertGroup& Gp = P.groups[g];
     if (!Gp.n_large) continue;
