@@ -48,7 +48,9 @@ enum : int32_t {
   OP_CONV11 = 1,   // NCHW tensor through a 1x1 window (also: plain [M, K] row-major matrices)
   OP_CONV33 = 2,   // 3x3 window
   OP_CONV77 = 3,   // 7x7 window
-  OP_CONVGEN = 4   // any window (run-time kh, kw)
+  OP_CONVGEN = 4,  // any window (run-time kh, kw)
+  OP_CONV25 = 5,   // 2x5 window (lag products)
+  OP_CONV13 = 6    // 1x3 window (lag products)
 };
 
 struct Operand {
@@ -59,8 +61,11 @@ struct Operand {
   int32_t bias;     // 1: column M-1 is an implicit column of ones
   int32_t ld;       // OP_KMAJOR: row pitch in elements
   uint32_t bytes;   // size of the tensor behind ptr (buffer-load range check); < 2 GiB
-  // convolution view: k = (n*OH + oy)*OW + ox,  m = (c*KH + i)*KW + j
-  int32_t C, H, W, OH, OW, stride, pad, KH, KW;
+  // convolution view: k = (n*OH + oy)*OW + ox,  m = (c*KH + i)*KW + j; element = input pixel
+  // ((oy + oy0)*stride - pad_h + i, (ox + ox0)*stride - pad_w + j), 0 outside the image.
+  // OH x OW is the extent of the window of output pixels that is contracted, (oy0, ox0) its origin;
+  // pads may be negative (windows that look only forward).
+  int32_t C, H, W, OH, OW, stride, pad_h, pad_w, oy0, ox0, KH, KW;
   FastDiv dOW, dOHW;
 };
 
@@ -92,6 +97,29 @@ struct ReduceJob {
   int32_t bi, bj;
   int32_t part0, nsplit;
   int32_t pad0, pad1, pad2;
+};
+
+// ---- activation factor of a 3x3 / stride 1 / pad 1 convolution from lag products --------------
+// With a the [n, C, H, W] activations (zero outside the image) and t = (i, j), t' = (i', j') two taps,
+//   A[(c,t),(c',t')] = sum over pixels q with q - (t - 1) inside the image of a[c, q] * a[c', q + (t' - t)],
+// which depends on the taps only through the lag t' - t and through which border row / column of q
+// the first tap excludes.  So the 81 C x C blocks follow from lag products over the whole image,
+//   G1[c, (c', dy, dx)], dy in {1, 2}, dx in {-2..2};   G2[c, (c', 0, dx)], dx in {0, 1, 2}
+// (negative lags are transposes), minus the same products restricted to one border row and one
+// border column of q, plus the corner pixel (25 lags each; a ones column gives the bias sums).
+enum : int32_t { LAG_G1 = 0, LAG_G2, LAG_TOP, LAG_BOT, LAG_LEFT, LAG_RIGHT, LAG_TL, LAG_TR, LAG_BL, LAG_BR, LAG_NMAT };
+
+struct LagAsm {
+  const float* G[LAG_NMAT];   // G1 [C][10C], G2 [C][3C + bias], the rest [C][25C + bias]
+  float* A;                   // [dA][dA], dA = 9C + bias
+  int32_t C, bias, dA, pad0;
+  float alpha, beta;          // A <- beta * A + alpha * (assembled sums)
+  float rows;                 // number of rows R (the bias-bias entry sums R ones)
+  float pad1;
+};
+
+struct LagJob {
+  int32_t lag, bi, bj, pad;
 };
 
 // ---- batched inversion ---------------------------------------------------------------------

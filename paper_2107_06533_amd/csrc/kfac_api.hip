@@ -36,6 +36,13 @@ struct DynTable {
   std::vector<unsigned char> last;   // image currently on the device
 };
 
+// An activation factor that is assembled from lag products: descriptors desc0 .. desc0 + LAG_NMAT - 1
+// write the small matrices at float offsets off[] of the lag scratch region.
+struct LagLayer {
+  int layer = 0, desc0 = 0;
+  size_t off[LAG_NMAT] = {};
+};
+
 struct FactorPlan {
   bool valid = false;
   std::vector<kfac_layer> layers;
@@ -44,9 +51,12 @@ struct FactorPlan {
   std::vector<TileDesc> descs;       // shape part filled at build time, pointers/scalars per call
   void* d_jobs = nullptr;
   void* d_rjobs = nullptr;
-  int njobs = 0, nrjobs = 0;
+  void* d_ljobs = nullptr;
+  int njobs = 0, nrjobs = 0, nljobs = 0;
   size_t nslots = 0;
-  DynTable tab;
+  std::vector<LagLayer> lags;        // activation factors built from lag products
+  size_t lag_floats = 0;             // their scratch matrices, behind the split-reduction slots
+  DynTable tab;                      // [TileDesc x descs][LagAsm x lags]
   kfac_plan_stats stats{};
 };
 
@@ -274,7 +284,7 @@ Operand act_operand(const kfac_layer& L) {
   else if (L.kh == 7 && L.kw == 7) o.type = OP_CONV77;
   else o.type = OP_CONVGEN;
   o.C = L.c_in; o.H = L.h; o.W = L.w; o.OH = conv_oh(L); o.OW = conv_ow(L);
-  o.stride = L.stride; o.pad = L.pad; o.KH = L.kh; o.KW = L.kw;
+  o.stride = L.stride; o.pad_h = o.pad_w = L.pad; o.KH = L.kh; o.KW = L.kw;
   o.dOW = make_fastdiv(uint32_t(o.OW));
   o.dOHW = make_fastdiv(uint32_t(o.OH) * uint32_t(o.OW));
   return o;
@@ -294,7 +304,7 @@ Operand gout_operand(const kfac_layer& L) {
   o.bytes = uint32_t(o.K * int64_t(L.c_out) * 4);
   o.type = OP_CONV11;   // [n, c_out, oh, ow] read through a 1x1 window: k = (n, oy, ox), m = channel
   o.C = L.c_out; o.H = conv_oh(L); o.W = conv_ow(L); o.OH = o.H; o.OW = o.W;
-  o.stride = 1; o.pad = 0; o.KH = 1; o.KW = 1;
+  o.stride = 1; o.pad_h = o.pad_w = 0; o.KH = 1; o.KW = 1;
   o.dOW = make_fastdiv(uint32_t(o.OW));
   o.dOHW = make_fastdiv(uint32_t(o.OH) * uint32_t(o.OW));
   return o;
@@ -311,7 +321,7 @@ Operand transposed_operand(const float* p, int K, int M) {   // element (k, m) a
   Operand o{};
   o.ptr = p; o.type = OP_CONV11; o.K = K; o.M = M; o.bias = 0;
   o.bytes = uint32_t(int64_t(K) * M * 4);
-  o.C = M; o.H = 1; o.W = K; o.OH = 1; o.OW = K; o.stride = 1; o.pad = 0; o.KH = 1; o.KW = 1;
+  o.C = M; o.H = 1; o.W = K; o.OH = 1; o.OW = K; o.stride = 1; o.pad_h = o.pad_w = 0; o.KH = 1; o.KW = 1;
   o.dOW = make_fastdiv(uint32_t(K));
   o.dOHW = make_fastdiv(uint32_t(K));
   return o;
@@ -361,7 +371,7 @@ bool xcd_enabled() {
 
 // ------------------------------------------------------------------------------- factor plan
 void release(FactorPlan& p) {
-  free_dev(p.d_jobs); free_dev(p.d_rjobs); free_table(p.tab);
+  free_dev(p.d_jobs); free_dev(p.d_rjobs); free_dev(p.d_ljobs); free_table(p.tab);
   p = FactorPlan{};
 }
 void release(InvertPlan& p) {
@@ -386,9 +396,38 @@ struct FactorSchedule {
   std::vector<int> desc_of;
   std::vector<TileJob> jobs;
   std::vector<ReduceJob> rjobs;
-  size_t nslots = 0;
+  std::vector<LagLayer> lags;
+  std::vector<LagJob> ljobs;
+  size_t nslots = 0, lag_floats = 0;
   kfac_plan_stats stats{};
 };
+
+// Activation factors of 3x3 / stride 1 / pad 1 convolutions with enough channels are built from
+// lag products (about a third of the multiply-adds of the patch-matrix product, see LagAsm).
+constexpr int LAG_MIN_C = 64;
+bool lag_enabled() {
+  static const bool on = [] { const char* e = std::getenv("KFAC_LAG"); return !(e && e[0] == '0'); }();
+  return on;
+}
+bool lag_eligible(const kfac_layer& L) {
+  return lag_enabled() && L.kind == 1 && L.kh == 3 && L.kw == 3 && L.stride == 1 && L.pad == 1 && L.c_in >= LAG_MIN_C;
+}
+
+// View of the activations through a KH x KW window of lags over the pixel window [y0, y1] x [x0, x1]
+Operand lag_operand(const kfac_layer& L, int type, int KH, int KW, int pad_h, int pad_w, int bias,
+                    int y0, int y1, int x0, int x1) {
+  Operand o{};
+  o.type = type;
+  o.C = L.c_in; o.H = L.h; o.W = L.w; o.OH = y1 - y0 + 1; o.OW = x1 - x0 + 1; o.oy0 = y0; o.ox0 = x0;
+  o.stride = 1; o.pad_h = pad_h; o.pad_w = pad_w; o.KH = KH; o.KW = KW;
+  o.K = int32_t(int64_t(L.n) * o.OH * o.OW);
+  o.M = L.c_in * KH * KW + bias;
+  o.bias = bias;
+  o.bytes = uint32_t(int64_t(L.n) * L.c_in * L.h * L.w * 4);
+  o.dOW = make_fastdiv(uint32_t(o.OW));
+  o.dOHW = make_fastdiv(uint32_t(o.OH) * uint32_t(o.OW));
+  return o;
+}
 
 FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vector<uint8_t>& present, int kjob) {
   FactorSchedule S;
@@ -396,34 +435,62 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
   for (int l = 0; l < n; ++l)
     for (int which = 0; which < 2; ++which) {
       if (!present[2 * l + which]) continue;
+      S.desc_of[2 * l + which] = int(S.descs.size());
+      const kfac_layer& L = layers[l];
+      if (which == 0 && lag_eligible(L)) {
+        LagLayer lg;
+        lg.layer = l; lg.desc0 = int(S.descs.size());
+        const int H = L.h, W = L.w, b = L.has_bias;
+        const int win[LAG_NMAT][4] = {{0, H - 1, 0, W - 1}, {0, H - 1, 0, W - 1},
+                                      {0, 0, 0, W - 1}, {H - 1, H - 1, 0, W - 1}, {0, H - 1, 0, 0}, {0, H - 1, W - 1, W - 1},
+                                      {0, 0, 0, 0}, {0, 0, W - 1, W - 1}, {H - 1, H - 1, 0, 0}, {H - 1, H - 1, W - 1, W - 1}};
+        for (int k = 0; k < LAG_NMAT; ++k) {
+          TileDesc D{};
+          const int* w = win[k];
+          D.a = lag_operand(L, OP_CONV11, 1, 1, 0, 0, 0, w[0], w[1], w[2], w[3]);
+          if (k == LAG_G1) D.b = lag_operand(L, OP_CONV25, 2, 5, -1, 2, 0, w[0], w[1], w[2], w[3]);
+          else if (k == LAG_G2) D.b = lag_operand(L, OP_CONV13, 1, 3, 0, 0, b, w[0], w[1], w[2], w[3]);
+          else D.b = lag_operand(L, OP_CONVGEN, 5, 5, 2, 2, b, w[0], w[1], w[2], w[3]);
+          D.M = D.a.M; D.N = D.ldo = D.b.M;
+          D.sym = 0; D.mirror = MIRROR_NONE; D.alpha = 1.f; D.beta = 0.f;
+          lg.off[k] = S.lag_floats;
+          S.lag_floats += size_t(D.M) * D.N;
+          S.descs.push_back(D);
+        }
+        const int T = ceil_div(dA_of(L), 64);
+        for (int bi = 0; bi < T; ++bi)
+          for (int bj = 0; bj <= bi; ++bj) S.ljobs.push_back(LagJob{int(S.lags.size()), bi, bj, 0});
+        S.lags.push_back(lg);
+        continue;
+      }
       TileDesc D{};
-      D.a = which == 0 ? act_operand(layers[l]) : gout_operand(layers[l]);
+      D.a = which == 0 ? act_operand(L) : gout_operand(L);
       D.b = D.a;
       D.M = D.N = D.ldo = D.a.M;
       D.sym = 1;
       D.mirror = MIRROR_ALL;
-      S.desc_of[2 * l + which] = int(S.descs.size());
       S.descs.push_back(D);
     }
   struct Group { std::vector<TileJob> jobs; int64_t job_cost; };
   std::vector<Group> groups;
   for (size_t di = 0; di < S.descs.size(); ++di) {
     const TileDesc& D = S.descs[di];
-    const int d = D.M, R = D.a.K, T = ceil_div(d, BM);
+    const bool sym = D.sym != 0;
+    const int R = D.a.K, Tm = ceil_div(D.M, BM), Tn = ceil_div(D.N, BN);
     int nsplit = ceil_div(R, kjob);
     int chunk = ceil_div(ceil_div(R, nsplit), KC) * KC;
     nsplit = ceil_div(R, chunk);
-    const int ntile = T * (T + 1) / 2;
+    const int ntile = sym ? Tm * (Tm + 1) / 2 : Tm * Tn;
     const size_t slot0 = S.nslots;
     if (nsplit > 1) S.nslots += size_t(ntile) * nsplit;
     Group G;
-    G.job_cost = int64_t(std::min(R, chunk)) * 16;
+    G.job_cost = int64_t(std::min(R, chunk)) * (sym ? 16 : active_blocks(D.M, D.N, 0, 0, false));
     // row chunk outermost: the jobs that run side by side read the same rows of the activations
     for (int sidx = 0; sidx < nsplit; ++sidx) {
       int tile = 0;
-      for (int bi = 0; bi < T; ++bi)
-        for (int bj = 0; bj <= bi; ++bj, ++tile) {
-          const int ab = active_blocks(d, d, bi, bj, true);
+      for (int bi = 0; bi < Tm; ++bi)
+        for (int bj = 0; bj < (sym ? bi + 1 : Tn); ++bj, ++tile) {
+          const int ab = active_blocks(D.M, D.N, bi, bj, sym);
           if (nsplit > 1 && sidx == 0) {
             ReduceJob rj{};
             rj.desc = int(di); rj.bi = bi; rj.bj = bj; rj.part0 = int(slot0 + size_t(tile) * nsplit); rj.nsplit = nsplit;
@@ -450,9 +517,9 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
   } else {
     for (auto& l : lists) S.jobs.insert(S.jobs.end(), l.begin(), l.end());
   }
-  S.stats.n_jobs = int64_t(S.jobs.size() + S.rjobs.size());
-  S.stats.n_launches = 1 + (S.rjobs.empty() ? 0 : 1);
-  S.stats.ws_bytes = int64_t(S.nslots * size_t(BM) * BN * sizeof(float));
+  S.stats.n_jobs = int64_t(S.jobs.size() + S.rjobs.size() + S.ljobs.size());
+  S.stats.n_launches = 1 + (S.rjobs.empty() ? 0 : 1) + (S.ljobs.empty() ? 0 : 1);
+  S.stats.ws_bytes = int64_t((S.nslots * size_t(BM) * BN + S.lag_floats) * sizeof(float));
   return S;
 }
 
@@ -816,11 +883,16 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
     P.njobs = int(S.jobs.size());
     P.nrjobs = int(S.rjobs.size());
     P.nslots = S.nslots;
+    P.lags = S.lags;
+    P.lag_floats = S.lag_floats;
+    P.nljobs = int(S.ljobs.size());
     P.stats = S.stats;
     if (!ctx->host_only) {
       kfac_status st = upload_static(ctx, &P.d_jobs, S.jobs.data(), S.jobs.size() * sizeof(TileJob));
       if (st != KFAC_OK) return st;
       st = upload_static(ctx, &P.d_rjobs, S.rjobs.data(), S.rjobs.size() * sizeof(ReduceJob));
+      if (st != KFAC_OK) return st;
+      st = upload_static(ctx, &P.d_ljobs, S.ljobs.data(), S.ljobs.size() * sizeof(LagJob));
       if (st != KFAC_OK) return st;
     }
     P.valid = true;
@@ -828,12 +900,16 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
   if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  kfac_status st = ensure_ws(ctx, P.nslots * size_t(BM) * BN * sizeof(float));
+  const size_t slot_floats = P.nslots * size_t(BM) * BN;
+  kfac_status st = ensure_ws(ctx, (slot_floats + P.lag_floats) * sizeof(float));
   if (st != KFAC_OK) return st;
+  float* lag_ws = static_cast<float*>(ctx->ws) + slot_floats;
+  std::vector<uint8_t> is_lag(n, 0);
+  for (const LagLayer& lg : P.lags) is_lag[lg.layer] = 1;
   for (int l = 0; l < n; ++l)
     for (int which = 0; which < 2; ++which) {
       const int di = P.desc_of[2 * l + which];
-      if (di < 0) continue;
+      if (di < 0 || (which == 0 && is_lag[l])) continue;
       TileDesc& D = P.descs[di];
       D.a.ptr = which == 0 ? act[l] : gout[l];
       D.b.ptr = D.a.ptr;
@@ -844,16 +920,41 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
       D.alpha = (1.f - xi) * scale;
       D.beta = xi;
     }
-  st = sync_table(ctx, P.tab, P.descs.data(), P.descs.size() * sizeof(TileDesc), s);
+  std::vector<LagAsm> asms(P.lags.size());
+  for (size_t i = 0; i < P.lags.size(); ++i) {
+    const LagLayer& lg = P.lags[i];
+    const kfac_layer& L = P.layers[lg.layer];
+    LagAsm& Q = asms[i];
+    for (int k = 0; k < LAG_NMAT; ++k) {
+      TileDesc& D = P.descs[lg.desc0 + k];
+      D.a.ptr = D.b.ptr = act[lg.layer];
+      D.out = lag_ws + lg.off[k];
+      D.partial = static_cast<float*>(ctx->ws);
+      Q.G[k] = D.out;
+    }
+    const double rows = double(rows_of(L));
+    Q.A = A[lg.layer];
+    Q.C = L.c_in; Q.bias = L.has_bias; Q.dA = dA_of(L);
+    Q.alpha = (1.f - xi) * (scale_a > 0.f ? scale_a : float(1.0 / rows));
+    Q.beta = xi;
+    Q.rows = float(rows);
+  }
+  const size_t descs_bytes = P.descs.size() * sizeof(TileDesc), asms_bytes = asms.size() * sizeof(LagAsm);
+  std::vector<unsigned char> img(descs_bytes + asms_bytes);
+  std::memcpy(img.data(), P.descs.data(), descs_bytes);
+  if (asms_bytes) std::memcpy(img.data() + descs_bytes, asms.data(), asms_bytes);
+  st = sync_table(ctx, P.tab, img.data(), img.size(), s);
   if (st != KFAC_OK) return st;
   const TileDesc* d_descs = static_cast<const TileDesc*>(P.tab.dev);
+  const LagAsm* d_asms = reinterpret_cast<const LagAsm*>(static_cast<const unsigned char*>(P.tab.dev) + descs_bytes);
   {
     ScopedTiming tm(ctx, KFAC_K_FACTOR_TILES, s);
     launch_tile_any(d_descs, static_cast<const TileJob*>(P.d_jobs), P.njobs, xcd_enabled() ? 1 : 0, s);
   }
-  if (P.nrjobs) {
+  if (P.nrjobs || P.nljobs) {
     ScopedTiming tm(ctx, KFAC_K_FACTOR_REDUCE, s);
     launch_tile_reduce(d_descs, static_cast<const ReduceJob*>(P.d_rjobs), P.nrjobs, s);
+    launch_lag_assemble(d_asms, static_cast<const LagJob*>(P.d_ljobs), P.nljobs, s);
   }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;

@@ -7,6 +7,7 @@ namespace kfac {
 void launch_tile_any(const TileDesc* descs, const TileJob* jobs, int njobs, int xcd_order, hipStream_t s);
 void launch_tile_gemm(const TileDesc* descs, const TileJob* jobs, int njobs, int xcd_order, hipStream_t s);
 void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs, hipStream_t s);
+void launch_lag_assemble(const LagAsm* lags, const LagJob* jobs, int njobs, hipStream_t s);
 
 void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma, hipStream_t s);
 void launch_gj_pivot(const InvMat* mats, int mat0, int nmats, int step, float gamma, int small, hipStream_t s);

@@ -153,7 +153,7 @@ struct ConvLoader {
   uint32_t taps[(NU + 3) / 4];      // 8 bits per column
   uint32_t CHW4, pix4;
   typename std::conditional<TAP64, uint64_t, uint32_t>::type outside;
-  int kend, H, W, OHW, OW, stride, pad, KH, KW, kl, mg;
+  int kend, H, W, OHW, OW, stride, pad_h, pad_w, oy0, ox0, KH, KW, kl, mg;
   unsigned biasmask;
   bool okcur, tile_bias;
   FastDiv dOW, dOHW;
@@ -187,7 +187,8 @@ struct ConvLoader {
     rs = make_rsrc(op.ptr, op.bytes);
     CHW4 = (uint32_t)(op.C * op.H * op.W) * 4u;
     kend = kend_;
-    H = op.H; W = op.W; OW = op.OW; OHW = op.OH * op.OW; stride = op.stride; pad = op.pad;
+    H = op.H; W = op.W; OW = op.OW; OHW = op.OH * op.OW; stride = op.stride;
+    pad_h = op.pad_h; pad_w = op.pad_w; oy0 = op.oy0; ox0 = op.ox0;
     dOW = op.dOW; dOHW = op.dOHW;
     okcur = false;
   }
@@ -200,7 +201,7 @@ struct ConvLoader {
     const uint32_t rem = kk - n * (uint32_t)OHW;
     const uint32_t oy = fast_div(rem, dOW);
     const uint32_t ox = rem - oy * (uint32_t)OW;
-    const int y0 = (int)oy * stride - pad, x0 = (int)ox * stride - pad;   // window origin (may be < 0)
+    const int y0 = ((int)oy + oy0) * stride - pad_h, x0 = ((int)ox + ox0) * stride - pad_w;   // window origin (may be < 0)
     pix4 = n * CHW4 + (uint32_t)(y0 * W + x0) * 4u;
     if (!TAP64) {
       uint32_t colbits = 0, inside = 0;
@@ -221,7 +222,7 @@ struct ConvLoader {
   // decomposition (window origin, outside-tap mask) are computed once and shared.
   __device__ __forceinline__ void share_geometry(const ConvLoader& o) {
     rs = o.rs; CHW4 = o.CHW4; kend = o.kend; H = o.H; W = o.W; OHW = o.OHW; OW = o.OW;
-    stride = o.stride; pad = o.pad; KH = o.KH; KW = o.KW; dOW = o.dOW; dOHW = o.dOHW;
+    stride = o.stride; pad_h = o.pad_h; pad_w = o.pad_w; oy0 = o.oy0; ox0 = o.ox0; KH = o.KH; KW = o.KW; dOW = o.dOW; dOHW = o.dOHW;
   }
   __device__ __forceinline__ void load_shared(const ConvLoader& o, float (&r)[NU]) {
     okcur = o.okcur; pix4 = o.pix4; outside = o.outside;
@@ -482,6 +483,15 @@ __device__ __forceinline__ void run_tile_sym(const TileDesc& D, const TileJob& J
   else if (ta == OP_CONV33) run_tile<ConvLoader<3, 3>, ConvLoader<3, 3>, false, true>(D, J, smem);
   else if (ta == OP_CONV77) run_tile<ConvLoader<7, 7>, ConvLoader<7, 7>, false, true>(D, J, smem);
   else run_tile<ConvLoader<0, 0>, ConvLoader<0, 0>, false, true>(D, J, smem);
+}
+
+// Lag products (see lag_assemble_kernel): a = 1x1 view of a tensor, b = a small window of forward
+// lags of the same tensor, over the same window of pixels.
+__device__ __forceinline__ void run_tile_lag(const TileDesc& D, const TileJob& J, float* smem) {
+  const int tb = D.b.type;
+  if (tb == OP_CONV25) run_tile<ConvLoader<1, 1>, ConvLoader<2, 5>, false, false>(D, J, smem);
+  else if (tb == OP_CONV13) run_tile<ConvLoader<1, 1>, ConvLoader<1, 3>, false, false>(D, J, smem);
+  else run_tile<ConvLoader<1, 1>, ConvLoader<0, 0>, false, false>(D, J, smem);
 }
 
 }  // namespace kfac

@@ -91,7 +91,9 @@ def test_r50_schedule(hctx):
     assert hctx.kfac_update_factors(ls, [1] * n, [1] * n, [1] * n, [1] * n, 0.95, check=False) == pk.KFAC_ERR_DEVICE
     st = hctx.plan_stats(0)
     alg = shapes.flops(ls)
-    assert alg["factor_a"] + alg["factor_g"] <= st["mfma_flops"] <= 1.2 * (alg["factor_a"] + alg["factor_g"])
+    # the 3x3 layers are built from lag products, which execute fewer flops than the patch-matrix
+    # product the algorithmic count is defined on
+    assert 0.6 * (alg["factor_a"] + alg["factor_g"]) <= st["mfma_flops"] <= 1.2 * (alg["factor_a"] + alg["factor_g"])
     assert st["ws_bytes"] == hctx.workspace_bytes_factors(ls)
     dims = [l.dA for l in ls] + [l.dG for l in ls]
     assert hctx.kfac_invert_batch(dims, [1] * 2 * n, [2] * 2 * n, 0.03, check=False) == pk.KFAC_ERR_DEVICE

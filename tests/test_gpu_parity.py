@@ -75,6 +75,13 @@ CONV_CASES = [
     (2, 4, 9, 8, 3, 2, 3, 1, 0, 1),         # rectangular window
     (2, 4, 9, 8, 3, 1, 1, 1, 1, 1),         # padded 1x1 goes through the generic window path
     (16, 8, 40, 40, 8, 3, 3, 1, 1, 1),      # R = 25600 > one job: split reduction with patches
+    # 3x3 / stride 1 / pad 1 with >= 64 channels: built from lag products
+    (2, 64, 5, 6, 4, 3, 3, 1, 1, 1),
+    (2, 70, 2, 5, 4, 3, 3, 1, 1, 1),        # two rows: top and bottom strips touch
+    (3, 64, 1, 1, 4, 3, 3, 1, 1, 1),        # single pixel: only the centre tap is ever inside
+    (2, 130, 7, 7, 4, 3, 3, 1, 1, 0),       # channels span two tiles, no bias
+    (2, 64, 1, 9, 4, 3, 3, 1, 1, 1),        # single row
+    (9, 64, 31, 30, 4, 3, 3, 1, 1, 1),      # R = 8370 > one job: split reduction of the lag products
 ]
 
 
