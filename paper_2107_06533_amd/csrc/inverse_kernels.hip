@@ -37,9 +37,9 @@ __global__ __launch_bounds__(NT) void gj_init_kernel(const InvMat* __restrict__ 
 // ---- pivot block: symmetric sweep of an n x n (n <= 128) SPD block in one workgroup ---------------
 // The block lives in LDS as 4 x 4 sub-blocks of 32 x 32 and is swept sub-block by sub-block:
 //   (A) every wave inverts the 32 x 32 diagonal sub-block D in registers (redundantly, so no
-//       exchange is needed): lane (i, h) = i + 32 h holds D[i][2t + h], t = 0..15, which is exactly
-//       the operand layout of v_mfma_f32_32x32x2_f32; step k of the scalar sweep fetches row k with
-//       16 cross-lane reads and does 16 fused multiply-adds per lane;
+//       exchange between waves is needed) by the scalar sweep, 16 fused multiply-adds per lane and
+//       step (see sweep32_step), and turns the result into the operand layout of
+//       v_mfma_f32_32x32x2_f32 (lane (i, h) = i + 32 h holds D^-1[i][2t + h], t = 0..15);
 //   (B) wave w != kb owns sub-block row w:  W_w = Z_w D^-1  (Z_w = old sub-block (w, kb)), then
 //       S_wj -= W_w Z_j^T for j != kb, all on the matrix cores; after a barrier it stores W_w into
 //       sub-block (w, kb) and its transpose into (kb, w); wave kb stores -D^-1.
@@ -52,31 +52,47 @@ constexpr int SB = 32;          // sub-block order
 constexpr int SP = NB + 1;      // LDS row pitch of the block (odd: conflict-free rows and columns)
 constexpr int WP = SB + 1;      // pitch of a wave's staging sub-block
 
-// In-register sweep of a 32 x 32 SPD sub-block held as r[t] = D[i][2t + h]; returns +D^-1 in the
-// same layout.  `bad` receives the 1-based index of the first non-positive pivot (0 if none).
-__device__ __forceinline__ void sweep32(float (&r)[16], int lane, int& bad) {
-  const int i = lane & 31, h = lane >> 5;
-  const int row_src = (h << 5) << 2;   // byte address of lane (0, h) for ds_bpermute
+// In-register sweep of a 32 x 32 SPD sub-block.  Lane 16 g + m holds rows m and m + 16 of the
+// column group 8g .. 8g+7:  r[8a + b] = D[m + 16a][8g + b].  Step k needs row k (for the lane's
+// eight columns: a broadcast inside the lane's 16-lane row, folded into the multiply-add as a DPP
+// operand) and column k (for the lane's two rows: two cross-lane reads from column group k / 8).
+// Returns +D^-1 in the same layout; `bad` receives the 1-based index of the first non-positive
+// pivot (0 if none).
+template <int KM>
+__device__ __forceinline__ float row_bcast(float x) {   // lane KM of every 16-lane row, to the whole row
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + KM, 0xF, 0xF, false));
+}
+
+template <int K>
+__device__ __forceinline__ void sweep32_step(float (&r)[16], int m, int g, int& bad) {
+  constexpr int ka = K >> 4, km = K & 15, kg = K >> 3, kb = K & 7;
+  const int src = (16 * kg + m) << 2;
+  const float ci0 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, r[kb])));
+  const float ci1 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, r[8 + kb])));
+  const float p = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[8 * ka + kb]), 16 * kg + km));
+  if (!(p > 0.f) && bad == 0) bad = K + 1;
+  float ip = __builtin_amdgcn_rcpf(p);
+  ip = fmaf(fmaf(-p, ip, 1.f), ip, ip);   // one Newton step on the hardware reciprocal
+  const float w0 = ci0 * ip, w1 = ci1 * ip;
+  // the lane that holds row k: r - (1 - 1/p) r = r / p, the swept pivot row
+  const bool prow = m == km;
+  const float wu0 = (prow && ka == 0) ? 1.f - ip : w0;
+  const float wu1 = (prow && ka == 1) ? 1.f - ip : w1;
 #pragma unroll
-  for (int k = 0; k < SB; ++k) {
-    const int tk = k >> 1, hk = k & 1;
-    float c[16];
-#pragma unroll
-    for (int t = 0; t < 16; ++t)       // row k, columns 2t + h: held by lane (k, h)
-      c[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(row_src + (k << 2), __float_as_int(r[t])));
-    // column k, row i: held by lane (i, hk)
-    const float ci = __int_as_float(__builtin_amdgcn_ds_bpermute((i + (hk << 5)) << 2, __float_as_int(r[tk])));
-    const float p = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r[tk]), k + (hk << 5)));
-    if (!(p > 0.f) && bad == 0) bad = k + 1;
-    float ip = __builtin_amdgcn_rcpf(p);
-    ip = fmaf(fmaf(-p, ip, 1.f), ip, ip);   // one Newton step on the hardware reciprocal
-    const float wi = ci * ip;
-    // lane row k: r - (1 - 1/p) r = r / p, the swept pivot row
-    const float wu = (i == k) ? 1.f - ip : wi;
-#pragma unroll
-    for (int t = 0; t < 16; ++t) r[t] = fmaf(-wu, c[t], r[t]);
-    if (h == hk) r[tk] = (i == k) ? -ip : wi;   // pivot column
+  for (int b = 0; b < 8; ++b) {
+    const float c = row_bcast<km>(r[8 * ka + b]);   // row k, this lane's column b (read before it is updated)
+    r[b] = fmaf(-wu0, c, r[b]);
+    r[8 + b] = fmaf(-wu1, c, r[8 + b]);
   }
+  if (g == kg) {   // pivot column
+    r[kb] = (prow && ka == 0) ? -ip : w0;
+    r[8 + kb] = (prow && ka == 1) ? -ip : w1;
+  }
+  if constexpr (K + 1 < 32) sweep32_step<K + 1>(r, m, g, bad);
+}
+
+__device__ __forceinline__ void sweep32(float (&r)[16], int lane, int& bad) {
+  sweep32_step<0>(r, lane & 15, lane >> 4, bad);
 #pragma unroll
   for (int t = 0; t < 16; ++t) r[t] = -r[t];
 }
@@ -119,13 +135,33 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
 
   int bad = 0;
   for (int kb = 0; kb < nsb; ++kb) {
-    // (A) inverse of the diagonal sub-block, in every wave
+    // (A) inverse of the diagonal sub-block, in every wave; the result goes through the wave's
+    // staging block to reach the operand layout dinv[q] = D^-1[li][2q + lh]
     float dinv[16];
+    {
+      const int m = lane & 15, g = lane >> 4;
+      float r[16];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) dinv[q] = S[(kb * SB + li) * SP + kb * SB + 2 * q + lh];
-    int bad_k = 0;
-    sweep32(dinv, lane, bad_k);
-    if (bad_k && bad == 0) bad = kb * SB + bad_k;
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) r[8 * a + b] = S[(kb * SB + m + 16 * a) * SP + kb * SB + 8 * g + b];
+      int bad_k = 0;
+      sweep32(r, lane, bad_k);
+      if (bad_k && bad == 0) bad = kb * SB + bad_k;
+      float* st = stage[w];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) st[(m + 16 * a) * WP + 8 * g + b] = r[8 * a + b];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int q = 0; q < 16; ++q) dinv[q] = st[li * WP + 2 * q + lh];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
 
     // (B) panel and update of sub-block row w
     f32x16 wacc;

@@ -450,7 +450,14 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
           D.a = lag_operand(L, OP_CONV11, 1, 1, 0, 0, 0, w[0], w[1], w[2], w[3]);
           if (k == LAG_G1) D.b = lag_operand(L, OP_CONV25, 2, 5, -1, 2, 0, w[0], w[1], w[2], w[3]);
           else if (k == LAG_G2) D.b = lag_operand(L, OP_CONV13, 1, 3, 0, 0, b, w[0], w[1], w[2], w[3]);
-          else D.b = lag_operand(L, OP_CONVGEN, 5, 5, 2, 2, b, w[0], w[1], w[2], w[3]);
+          else {
+            // lags a strip's tap can ask for: the tap in row i = 0 (which drops the bottom row) pairs
+            // with rows i' >= 0 only, i.e. lags 0..2, and so on
+            static const int geo[LAG_NMAT][4] = {{0, 0, 0, 0}, {0, 0, 0, 0},                 // KH, KW, pad_h, pad_w
+                                                 {3, 5, 2, 2}, {3, 5, 0, 2}, {5, 3, 2, 2}, {5, 3, 2, 0},
+                                                 {3, 3, 2, 2}, {3, 3, 2, 0}, {3, 3, 0, 2}, {3, 3, 0, 0}};
+            D.b = lag_operand(L, OP_CONVGEN, geo[k][0], geo[k][1], geo[k][2], geo[k][3], b, w[0], w[1], w[2], w[3]);
+          }
           D.M = D.a.M; D.N = D.ldo = D.b.M;
           D.sym = 0; D.mirror = MIRROR_NONE; D.alpha = 1.f; D.beta = 0.f;
           lg.off[k] = S.lag_floats;

@@ -104,53 +104,86 @@ __global__ __launch_bounds__(NT) void tile_reduce_kernel(const TileDesc* __restr
 // of A per workgroup; every element is a sum of at most four entries of the small lag matrices,
 // blended with the old value and written to both (q, q') and (q', q).
 constexpr int LAG_TILE = 64;
-__device__ __forceinline__ float lag_value(const LagAsm& L, int q, int q2) {
-  // value of the raw sum for row q (a real tap column) and column q2 (tap column or the bias column)
-  const int C = L.C, ld1 = 10 * C, ld2 = 3 * C + L.bias, lds = 25 * C + L.bias;
-  const int c = q / 9, t = q - 9 * c, i = t / 3, j = t - 3 * i;
-  float v;
-  int col;
-  if (q2 == 9 * C) {            // bias column: sums of a over the pixels the tap keeps
-    v = L.G[LAG_G2][(size_t)c * ld2 + 3 * C];
-    col = 25 * C;
-  } else {
-    const int c2 = q2 / 9, t2 = q2 - 9 * c2, i2 = t2 / 3, j2 = t2 - 3 * i2;
-    const int dy = i2 - i, dx = j2 - j;
-    if (dy > 0) v = L.G[LAG_G1][(size_t)c * ld1 + c2 * 10 + (dy - 1) * 5 + dx + 2];
-    else if (dy == 0 && dx >= 0) v = L.G[LAG_G2][(size_t)c * ld2 + c2 * 3 + dx];
-    else if (dy < 0) v = L.G[LAG_G1][(size_t)c2 * ld1 + c * 10 + (-dy - 1) * 5 - dx + 2];
-    else v = L.G[LAG_G2][(size_t)c2 * ld2 + c * 3 - dx];
-    col = c2 * 25 + (dy + 2) * 5 + dx + 2;
+// Raw sum for the tap column (c, i, j) against the tap column (c2, i2, j2), or against the bias
+// column when isbias (then c2 = C, i2 = j2 = 0 are ignored).  All offsets fit 32 bits.
+__device__ __forceinline__ float lag_value(const LagAsm& L, int c, int i, int j, int c2, int i2, int j2, bool isbias) {
+  const uint32_t C = (uint32_t)L.C, ld1 = 10u * C, ld2 = 3u * C + L.bias, ld15 = 15u * C + L.bias, ld9 = 9u * C + L.bias;
+  const int dy = isbias ? 0 : i2 - i, dx = isbias ? 0 : j2 - j;
+  gcf_ptr G1 = as_global(L.G[LAG_G1]);
+  gcf_ptr G2 = as_global(L.G[LAG_G2]);
+  float v;   // forward lags are stored; a backward lag is the transposed entry of its opposite
+  if (isbias) v = G2[c * ld2 + 3u * C];   // sums of a over the whole image
+  else if (dy > 0) v = G1[c * ld1 + c2 * 10 + (dy - 1) * 5 + dx + 2];
+  else if (dy == 0 && dx >= 0) v = G2[c * ld2 + c2 * 3 + dx];
+  else if (dy < 0) v = G1[c2 * ld1 + c * 10 + (-dy - 1) * 5 - dx + 2];
+  else v = G2[c2 * ld2 + c * 3 - dx];
+  // Pixels q whose output pixel q - (t - 1) lies outside the grid are taken out again: bottom row for
+  // i = 0, top row for i = 2, right column for j = 0, left column for j = 2.  Each strip matrix holds
+  // only the lags its tap row / column can ask for (lag = window index - pad); in the bias column
+  // (c2 = C) the index below lands on the ones column of every strip.
+  const int ph = i == 0 ? 0 : 2, pw = j == 0 ? 0 : 2;        // pads of the 3-wide lag windows
+  const int uy = isbias ? 0 : dy + ph, ux = isbias ? 0 : dx + pw;
+  if (i != 1) {
+    gcf_ptr S = as_global(i == 0 ? L.G[LAG_BOT] : L.G[LAG_TOP]);                           // [C][15C + bias], 3 x 5 lags
+    v -= S[c * ld15 + c2 * 15 + uy * 5 + (isbias ? 0 : dx + 2)];
   }
-  // pixels q whose output pixel q - (t - 1) lies outside the grid: bottom row for i = 0, top row
-  // for i = 2, right column for j = 0, left column for j = 2
-  const int rs = i == 0 ? LAG_BOT : (i == 2 ? LAG_TOP : -1);
-  const int cs = j == 0 ? LAG_RIGHT : (j == 2 ? LAG_LEFT : -1);
-  const size_t e = (size_t)c * lds + col;
-  if (rs >= 0) v -= L.G[rs][e];
-  if (cs >= 0) v -= L.G[cs][e];
-  if (rs >= 0 && cs >= 0) v += L.G[LAG_TL + (rs == LAG_BOT ? 2 : 0) + (cs == LAG_RIGHT ? 1 : 0)][e];
+  if (j != 1) {
+    gcf_ptr S = as_global(j == 0 ? L.G[LAG_RIGHT] : L.G[LAG_LEFT]);                        // [C][15C + bias], 5 x 3 lags
+    v -= S[c * ld15 + c2 * 15 + (isbias ? 0 : (dy + 2) * 3) + ux];
+  }
+  if (i != 1 && j != 1) {
+    gcf_ptr S = as_global(i == 0 ? (j == 0 ? L.G[LAG_BR] : L.G[LAG_BL]) : (j == 0 ? L.G[LAG_TR] : L.G[LAG_TL]));   // [C][9C + bias]
+    v += S[c * ld9 + c2 * 9 + uy * 3 + ux];
+  }
   return v;
 }
 
+// One 64 x 64 tile of the lower triangle of A per workgroup (thread = one column, 16 rows).  Only
+// elements on or below the diagonal are computed; the mirror image goes through LDS so that both
+// copies are stored row by row, and both hold the same bits.
 __global__ __launch_bounds__(NT) void lag_assemble_kernel(const LagAsm* __restrict__ lags,
                                                           const LagJob* __restrict__ jobs, int njobs) {
+  __shared__ float tile[LAG_TILE][LAG_TILE + 1];
   const int g = blockIdx.x;
   if (g >= njobs) return;
   const LagJob J = jobs[g];
   const LagAsm L = lags[J.lag];
   const int dA = L.dA, nb = 9 * L.C;
-  for (int e = threadIdx.x; e < LAG_TILE * LAG_TILE; e += NT) {
-    const int q = J.bi * LAG_TILE + (e >> 6), q2 = J.bj * LAG_TILE + (e & (LAG_TILE - 1));
-    if (q >= dA || q2 > q) continue;
-    float v;
-    if (q < nb) v = lag_value(L, q, q2);               // q2 <= q < nb: both are tap columns
-    else if (q2 < nb) v = lag_value(L, q2, q);         // bias row: the mirrored bias-column entry
-    else v = L.rows;                                   // bias-bias
-    const float old = L.beta != 0.f ? L.A[(size_t)q * dA + q2] : 0.f;
-    const float val = L.alpha * v + L.beta * old;
-    L.A[(size_t)q * dA + q2] = val;
-    if (q2 != q) L.A[(size_t)q2 * dA + q] = val;
+  constexpr int PER = LAG_TILE * LAG_TILE / NT;
+  gf_ptr A = as_global(L.A);
+  const int lc = threadIdx.x & (LAG_TILE - 1), lr0 = threadIdx.x >> 6;
+  const int cc = J.bj * LAG_TILE + lc;                  // this thread's column
+  const bool cbias = cc >= nb;
+  const int c2 = cbias ? L.C : cc / 9, t2 = cbias ? 0 : cc - 9 * c2, i2 = t2 / 3, j2 = t2 - 3 * i2;
+  float v[PER], old[PER];
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int r = J.bi * LAG_TILE + lr0 + 4 * u;
+    v[u] = 0.f; old[u] = 0.f;
+    if (r >= dA || cc > r) continue;
+    if (r < nb) {
+      const int c = r / 9, t = r - 9 * c, i = t / 3, j = t - 3 * i;
+      v[u] = lag_value(L, c, i, j, c2, i2, j2, false);
+    } else if (!cbias) {
+      v[u] = lag_value(L, c2, i2, j2, L.C, 0, 0, true);   // bias row: the mirrored bias-column entry
+    } else {
+      v[u] = L.rows;                                      // bias-bias
+    }
+    if (L.beta != 0.f) old[u] = A[(uint32_t)r * (uint32_t)dA + (uint32_t)cc];
+  }
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int lr = lr0 + 4 * u, r = J.bi * LAG_TILE + lr;
+    const float val = L.alpha * v[u] + L.beta * old[u];
+    tile[lr][lc] = val;
+    if (r < dA && cc <= r) A[(uint32_t)r * (uint32_t)dA + (uint32_t)cc] = val;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int lr = lr0 + 4 * u;
+    const int r = J.bj * LAG_TILE + lr, c = J.bi * LAG_TILE + lc;   // element (r, c) of the mirrored tile = tile[lc][lr]
+    if (c < dA && r < c) A[(uint32_t)r * (uint32_t)dA + (uint32_t)c] = tile[lc][lr];
   }
 }
 
