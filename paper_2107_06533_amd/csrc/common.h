@@ -50,7 +50,8 @@ enum : int32_t {
   OP_CONV77 = 3,   // 7x7 window
   OP_CONVGEN = 4,  // any window (run-time kh, kw)
   OP_CONV25 = 5,   // 2x5 window (lag products)
-  OP_CONV13 = 6    // 1x3 window (lag products)
+  OP_CONV13 = 6,   // 1x3 window (lag products)
+  OP_CONV11V = 7   // 1x1 window, stride 1, whole images of 4p pixels: read four pixels at a time
 };
 
 struct Operand {

@@ -267,6 +267,11 @@ int conv_ow(const kfac_layer& L) { return (L.w + 2 * L.pad - L.kw) / L.stride + 
 int64_t rows_of(const kfac_layer& L) { return L.kind == 0 ? L.rows : int64_t(L.n) * conv_oh(L) * conv_ow(L); }
 int dA_of(const kfac_layer& L) { return (L.kind == 0 ? L.c_in : L.c_in * L.kh * L.kw) + L.has_bias; }
 
+bool vec_enabled() {
+  static const bool on = [] { const char* e = std::getenv("KFAC_VEC11"); return !(e && e[0] == '0'); }();
+  return on;
+}
+
 Operand act_operand(const kfac_layer& L) {
   Operand o{};
   o.K = int32_t(rows_of(L));
@@ -279,7 +284,7 @@ Operand act_operand(const kfac_layer& L) {
     return o;
   }
   o.bytes = uint32_t(int64_t(L.n) * L.c_in * L.h * L.w * 4);
-  if (L.kh == 1 && L.kw == 1 && L.pad == 0) o.type = OP_CONV11;
+  if (L.kh == 1 && L.kw == 1 && L.pad == 0) o.type = (L.stride == 1 && vec_enabled() && (L.h * L.w) % 4 == 0) ? OP_CONV11V : OP_CONV11;
   else if (L.kh == 3 && L.kw == 3) o.type = OP_CONV33;
   else if (L.kh == 7 && L.kw == 7) o.type = OP_CONV77;
   else o.type = OP_CONVGEN;
@@ -302,8 +307,9 @@ Operand gout_operand(const kfac_layer& L) {
     return o;
   }
   o.bytes = uint32_t(o.K * int64_t(L.c_out) * 4);
-  o.type = OP_CONV11;   // [n, c_out, oh, ow] read through a 1x1 window: k = (n, oy, ox), m = channel
+  // [n, c_out, oh, ow] read through a 1x1 window: k = (n, oy, ox), m = channel
   o.C = L.c_out; o.H = conv_oh(L); o.W = conv_ow(L); o.OH = o.H; o.OW = o.W;
+  o.type = (vec_enabled() && (o.H * o.W) % 4 == 0) ? OP_CONV11V : OP_CONV11;
   o.stride = 1; o.pad_h = o.pad_w = 0; o.KH = 1; o.KW = 1;
   o.dOW = make_fastdiv(uint32_t(o.OW));
   o.dOHW = make_fastdiv(uint32_t(o.OH) * uint32_t(o.OW));
@@ -447,7 +453,8 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
         for (int k = 0; k < LAG_NMAT; ++k) {
           TileDesc D{};
           const int* w = win[k];
-          D.a = lag_operand(L, OP_CONV11, 1, 1, 0, 0, 0, w[0], w[1], w[2], w[3]);
+          const bool whole = k <= LAG_G2 && vec_enabled() && (H * W) % 4 == 0;   // whole images: four pixels per load
+          D.a = lag_operand(L, whole ? OP_CONV11V : OP_CONV11, 1, 1, 0, 0, 0, w[0], w[1], w[2], w[3]);
           if (k == LAG_G1) D.b = lag_operand(L, OP_CONV25, 2, 5, -1, 2, 0, w[0], w[1], w[2], w[3]);
           else if (k == LAG_G2) D.b = lag_operand(L, OP_CONV13, 1, 3, 0, 0, b, w[0], w[1], w[2], w[3]);
           else {

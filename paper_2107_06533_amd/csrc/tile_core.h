@@ -251,6 +251,79 @@ struct ConvLoader {
   }
 };
 
+// NCHW tensor through a 1x1 window of stride 1 over whole images whose pixel count HW is a multiple
+// of four: k = n*HW + pixel, m = channel, element at (k + n*(C-1)*HW + m*HW).  Four consecutive k
+// (k % 4 == 0) never straddle an image and are 16 contiguous bytes: a thread moves four such
+// groups per k step with 128-bit loads and writes each as two 64-bit LDS stores (k, k+2 and
+// k+1, k+3 are neighbours in the LDS row order).  A wave reads 8 channel rows of 128 bytes.
+struct Conv11VecLoader {
+  static_assert(KC == 32 && NT == 256, "eight groups of four k per row of 32 threads");
+  static constexpr uint32_t ROW_OOB = 0x40000000u;   // >= any operand size, and ROW_OOB + OOB_OFFSET does not wrap
+  rsrc_t rs;
+  uint32_t qoff4[4];   // byte offsets m*HW*4 of the thread's four columns (OOB_OFFSET beyond the matrix)
+  uint32_t base, skip; // byte offset of the thread's k group in channel 0; (C-1)*HW
+  int kend, kq, mrow, kcur;
+  unsigned biasmask;
+  bool tile_bias;
+  FastDiv dHW;
+
+  __device__ __forceinline__ void init(const Operand& op, int m0, int kend_, int t) {
+    kq = (t & 7) * 4;
+    mrow = t >> 3;
+    const int mreal = op.M - op.bias;
+    const uint32_t HW = (uint32_t)(op.OH * op.OW);
+    tile_bias = op.bias && m0 + BM > mreal && m0 <= mreal;
+    biasmask = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int m = m0 + mrow + 32 * u;
+      qoff4[u] = m < mreal ? (uint32_t)m * HW * 4u : OOB_OFFSET;
+      if (op.bias && m == mreal) biasmask |= 1u << u;
+    }
+    rs = make_rsrc(op.ptr, op.bytes);
+    skip = (uint32_t)(op.C - 1) * HW;
+    dHW = op.dOHW;
+    kend = kend_;
+    kcur = 0;
+  }
+  __device__ __forceinline__ void begin(int k0) {
+    kcur = k0;
+    const uint32_t k = (uint32_t)(k0 + kq);
+    const uint32_t n = fast_div(k, dHW);
+    base = (int)k < kend ? (k + n * skip) * 4u : ROW_OOB;
+  }
+  __device__ __forceinline__ void issue(float (&r)[NU]) const {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(base + qoff4[u]), 0, 0));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[4 * u + e] = v[e];
+    }
+  }
+  __device__ __forceinline__ void load(int k0, float (&r)[NU]) {
+    begin(k0);
+    issue(r);
+  }
+  __device__ __forceinline__ void share_geometry(const Conv11VecLoader& o) { rs = o.rs; skip = o.skip; dHW = o.dHW; kend = o.kend; }
+  __device__ __forceinline__ void load_shared(const Conv11VecLoader& o, float (&r)[NU]) {
+    kcur = o.kcur; base = o.base;
+    issue(r);
+  }
+  __device__ __forceinline__ void store(float* lds, const float (&r)[NU]) const {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    // k = kq + e: positions (kq & ~7) + 2*((kq >> 2) & 1) + {0, 4, 1, 5} for e = 0..3
+    const int p0 = (kq & ~7) + ((kq >> 1) & 2);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float* row = lds + (mrow + 32 * u) * PK + p0;
+      const bool ones = tile_bias && ((biasmask >> u) & 1u);
+      const float one = kcur + kq < kend ? 1.f : 0.f;
+      *reinterpret_cast<f32x2*>(row) = ones ? f32x2{one, one} : f32x2{r[4 * u], r[4 * u + 2]};
+      *reinterpret_cast<f32x2*>(row + 4) = ones ? f32x2{one, one} : f32x2{r[4 * u + 1], r[4 * u + 3]};
+    }
+  }
+};
+
 // ------------------------------------------------------------------------------ MFMA step
 // One staged k step (KC deep).  Lane l supplies a(k = l/32, i = l%32) and b(k = l/32, j = l%32).
 // PAT is the compile-time set of the wave's 32x32 blocks that are computed (bit a*2+b): the
@@ -479,6 +552,7 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
 __device__ __forceinline__ void run_tile_sym(const TileDesc& D, const TileJob& J, float* smem) {
   const int ta = D.a.type;
   if (ta == OP_KMAJOR) run_tile<KMajorLoader, KMajorLoader, false, true>(D, J, smem);
+  else if (ta == OP_CONV11V) run_tile<Conv11VecLoader, Conv11VecLoader, false, true>(D, J, smem);
   else if (ta == OP_CONV11) run_tile<ConvLoader<1, 1>, ConvLoader<1, 1>, false, true>(D, J, smem);
   else if (ta == OP_CONV33) run_tile<ConvLoader<3, 3>, ConvLoader<3, 3>, false, true>(D, J, smem);
   else if (ta == OP_CONV77) run_tile<ConvLoader<7, 7>, ConvLoader<7, 7>, false, true>(D, J, smem);
@@ -489,7 +563,10 @@ __device__ __forceinline__ void run_tile_sym(const TileDesc& D, const TileJob& J
 // lags of the same tensor, over the same window of pixels.
 __device__ __forceinline__ void run_tile_lag(const TileDesc& D, const TileJob& J, float* smem) {
   const int tb = D.b.type;
-  if (tb == OP_CONV25) run_tile<ConvLoader<1, 1>, ConvLoader<2, 5>, false, false>(D, J, smem);
+  if (D.a.type == OP_CONV11V) {
+    if (tb == OP_CONV25) run_tile<Conv11VecLoader, ConvLoader<2, 5>, false, false>(D, J, smem);
+    else run_tile<Conv11VecLoader, ConvLoader<1, 3>, false, false>(D, J, smem);
+  } else if (tb == OP_CONV25) run_tile<ConvLoader<1, 1>, ConvLoader<2, 5>, false, false>(D, J, smem);
   else if (tb == OP_CONV13) run_tile<ConvLoader<1, 1>, ConvLoader<1, 3>, false, false>(D, J, smem);
   else run_tile<ConvLoader<1, 1>, ConvLoader<0, 0>, false, false>(D, J, smem);
 }

@@ -82,6 +82,12 @@ CONV_CASES = [
     (2, 130, 7, 7, 4, 3, 3, 1, 1, 0),       # channels span two tiles, no bias
     (2, 64, 1, 9, 4, 3, 3, 1, 1, 1),        # single row
     (9, 64, 31, 30, 4, 3, 3, 1, 1, 1),      # R = 8370 > one job: split reduction of the lag products
+    (2, 64, 6, 6, 4, 3, 3, 1, 1, 1),        # 36 pixels per image: lag products read four pixels at a time
+    # 1x1 / stride 1 with a pixel count divisible by four: four pixels per load
+    (2, 70, 8, 6, 130, 1, 1, 1, 0, 1),
+    (3, 5, 2, 2, 3, 1, 1, 1, 0, 0),
+    (40, 16, 16, 16, 8, 1, 1, 1, 0, 1),     # R = 10240 > one job
+    (5, 129, 4, 3, 257, 1, 1, 1, 0, 1),     # ragged channel tiles on both factors
 ]
 
 
