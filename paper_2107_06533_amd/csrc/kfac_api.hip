@@ -69,6 +69,7 @@ struct InvertGroup {
   std::vector<int> sub_active;                   // [outer block * agg + sub-step]
   std::vector<int> sub_panel_off, sub_upd_off;   // [outer block * agg + sub-step (+1)]
   std::vector<int> qm_off, mv_off, bp_off;       // [outer block (+1)]
+  std::vector<int> mv_mid, bp_mid;               // [outer block]: first job that does not belong to the next outer block's rows
   std::vector<int> upd_off[3];                   // [UPD_DIAG / UPD_COL / UPD_REST][outer block (+1)]
   std::vector<size_t> ws_off;        // per large matrix: float offset of its workspace inside the group's region
   void* d_init = nullptr; int n_init = 0;
@@ -76,7 +77,7 @@ struct InvertGroup {
   void* d_sub_panel = nullptr; void* d_sub_upd = nullptr;
   void* d_qm = nullptr; void* d_mv = nullptr; void* d_bp = nullptr;
   void* d_upd[3] = {nullptr, nullptr, nullptr};
-  std::vector<hipEvent_t> ev_chain, ev_col, ev_rest;   // [outer block], created on first use
+  std::vector<hipEvent_t> ev_gather, ev_chain, ev_col, ev_rest;   // [outer block], created on first use
   DynTable tab;                      // [InvMat x n][InvMat x views][PanelMove x 2 views][TileDesc x (2 views + n_large)]
   size_t ws_floats = 0, ws_base = 0;
 };
@@ -118,7 +119,7 @@ struct kfac_ctx {
   void* ws = nullptr;
   size_t ws_cap = 0;
   int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
-  int inv_groups = 1;                     // matrix groups swept concurrently
+  int inv_groups = 2;                     // matrix groups swept concurrently
   int inv_agg = 4;                        // pivot blocks per aggregated (rank agg*128) update
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
   hipStream_t inv_side[MAX_INV_GROUPS] = {};     // every group's side stream for the off-chain updates
@@ -387,6 +388,7 @@ void release(InvertPlan& p) {
     for (int k = 0; k < 3; ++k) free_dev(g.d_upd[k]);
     free_table(g.tab);
     for (hipEvent_t e : g.ev_chain) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g.ev_gather) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : g.ev_col) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : g.ev_rest) if (e) (void)hipEventDestroy(e);
   }
@@ -560,7 +562,7 @@ struct InvertSchedule {
   int n_large = 0, n_small = 0, n_ob = 0, n_views = 0;
   std::vector<int> nblk, ldp, nob;
   std::vector<size_t> ws_off;
-  std::vector<int> view_off, n_in_ob, sub_active, sub_panel_off, sub_upd_off, qm_off, mv_off, bp_off;
+  std::vector<int> view_off, n_in_ob, sub_active, sub_panel_off, sub_upd_off, qm_off, mv_off, bp_off, mv_mid, bp_mid;
   std::vector<int> upd_off[3];
   std::vector<MatJobH> init, finish, sub_panel, qm, mv;
   std::vector<TileJob> sub_upd, bp, upd[3];
@@ -613,6 +615,7 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
   S.sub_panel_off.assign(size_t(S.n_ob) * agg + 1, 0);
   S.sub_upd_off.assign(size_t(S.n_ob) * agg + 1, 0);
   S.qm_off.assign(S.n_ob + 1, 0); S.mv_off.assign(S.n_ob + 1, 0); S.bp_off.assign(S.n_ob + 1, 0);
+  S.mv_mid.assign(S.n_ob, 0); S.bp_mid.assign(S.n_ob, 0);
   for (int k = 0; k < 3; ++k) S.upd_off[k].assign(S.n_ob + 1, 0);
   int64_t launches = 0;
   for (int b = 0; b < S.n_ob; ++b) {
@@ -644,7 +647,11 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
       S.sub_upd_off[st + 1] = int(S.sub_upd.size());
       launches += (S.sub_active[st] > 0) + (S.sub_panel_off[st + 1] > S.sub_panel_off[st]) + (S.sub_upd_off[st + 1] > S.sub_upd_off[st]);
     }
-    // ---- steps 2-4 for the matrices that have more than one outer block
+    // ---- steps 2-4 for the matrices that have more than one outer block.  The gather/scatter and
+    // panel-product jobs of the rows of the NEXT outer block come first in their lists: the chain
+    // needs only those, the others go to the side stream.
+    std::vector<MatJobH> mv_rest;
+    std::vector<TileJob> bp_rest;
     for (int m = 0; m < S.n_in_ob[b]; ++m) {
       if (S.nob[m] < 2) continue;
       const int v = S.view_off[b] + m;
@@ -659,11 +666,11 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
         for (int bj = 0; bj < q32; ++bj) S.qm.push_back({v, bi, bj, 0});
       for (int it = 0; it < S.nblk[m]; ++it) {
         if (in_ob(it)) continue;
-        S.mv.push_back({2 * v, it, 0, 0});
+        (in_next(it) ? S.mv : mv_rest).push_back({2 * v, it, 0, 0});
         for (int bi = 0; bi < ceil_div(dimB, BM); ++bi) {
           TileJob j{};
           j.desc = S.n_views + v; j.bi = bi; j.bj = it; j.kbeg = 0; j.kend = dimB; j.part = -1;
-          S.bp.push_back(j);
+          (in_next(it) ? S.bp : bp_rest).push_back(j);
           S.stats.mfma_flops += int64_t(ceil_div(dimB, KC) * KC) * active_blocks(dimB, d, bi, it, false) * 32 * 32 * 2;
         }
       }
@@ -677,8 +684,12 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
           S.stats.mfma_flops += int64_t(ceil_div(dimB, KC) * KC) * active_blocks(d, d, bi, bj, true) * 32 * 32 * 2;
         }
     }
+    S.mv_mid[b] = int(S.mv.size()); S.bp_mid[b] = int(S.bp.size());
+    S.mv.insert(S.mv.end(), mv_rest.begin(), mv_rest.end());
+    S.bp.insert(S.bp.end(), bp_rest.begin(), bp_rest.end());
     S.qm_off[b + 1] = int(S.qm.size()); S.mv_off[b + 1] = int(S.mv.size()); S.bp_off[b + 1] = int(S.bp.size());
-    launches += (S.qm_off[b + 1] > S.qm_off[b]) + 2 * (S.mv_off[b + 1] > S.mv_off[b]) + (S.bp_off[b + 1] > S.bp_off[b]);
+    launches += (S.qm_off[b + 1] > S.qm_off[b]) + (S.mv_off[b + 1] > S.mv_off[b]) +
+                (S.mv_mid[b] > S.mv_off[b]) * 2 + (S.mv_off[b + 1] > S.mv_mid[b]) * 2;
     for (int k = 0; k < 3; ++k) {
       S.upd_off[k][b + 1] = int(S.upd[k].size());
       launches += S.upd_off[k][b + 1] > S.upd_off[k][b];
@@ -1026,10 +1037,11 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.n_ob = S.n_ob; Gp.n_views = S.n_views;
       Gp.view_off = S.view_off; Gp.n_in_ob = S.n_in_ob; Gp.sub_active = S.sub_active;
       Gp.sub_panel_off = S.sub_panel_off; Gp.sub_upd_off = S.sub_upd_off;
-      Gp.qm_off = S.qm_off; Gp.mv_off = S.mv_off; Gp.bp_off = S.bp_off;
+      Gp.qm_off = S.qm_off; Gp.mv_off = S.mv_off; Gp.bp_off = S.bp_off; Gp.mv_mid = S.mv_mid; Gp.bp_mid = S.bp_mid;
       for (int k = 0; k < 3; ++k) Gp.upd_off[k] = S.upd_off[k];
       Gp.ws_off = S.ws_off;
       Gp.ev_chain.assign(S.n_ob, nullptr); Gp.ev_col.assign(S.n_ob, nullptr); Gp.ev_rest.assign(S.n_ob, nullptr);
+      Gp.ev_gather.assign(S.n_ob, nullptr);
       Gp.n_init = int(S.init.size()); Gp.n_finish = int(S.finish.size());
       Gp.ws_floats = S.ws_floats;
       Gp.ws_base = P.ws_floats;
@@ -1158,14 +1170,18 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     }
   }
   // The groups are issued outer block by outer block so that their kernels interleave in time.
-  // Chain of a group (its main stream), per outer block: sweep of the diagonal sub-matrix, QB,
-  // gather, panel GEMM, scatter, update of the next diagonal sub-matrix.  The other two update
-  // lists follow on the side stream.  Cross-stream order, by what the kernels touch:
-  //   gather(b)    reads the tiles UPD_COL(b-1) wrote                 -> waits for ev_col[b-1]
-  //   UPD_DIAG(b)  writes tiles that UPD_REST(b-1) also updates, and gather(b+1)/panel GEMM(b+1)
-  //                reuse the buffer half UPD_REST(b-1) reads           -> waits for ev_rest[b-1]
-  //   side stream  reads the panels of block b                         -> waits for ev_chain[b]
-  std::vector<int> last_col(G, -1), last_rest(G, -1);    // outer block of the group's latest side-stream updates
+  // Chain of a group (its main stream), per outer block b: sweep of the diagonal sub-matrix, QB,
+  // gather of the block column, then only what the next diagonal sub-matrix needs: panel product
+  // and scatter for the rows of the next outer block, update of the next diagonal sub-matrix.
+  // Side stream: panel product and scatter for all other rows, then the other two update lists.
+  // Cross-stream order, by what the kernels touch:
+  //   QB(b), gather(b)   rewrite QB, which the side's panel product (b-1) reads, and read tiles
+  //                      that UPD_COL(b-1) wrote                        -> chain waits for ev_col[b-1]
+  //   UPD_DIAG(b)        writes tiles that UPD_REST(b-1) also updates; gather(b+1) and the panel
+  //                      products (b+1) reuse the buffer half it reads   -> chain waits for ev_rest[b-1]
+  //   side panel product reads QB(b) and the gathered column            -> side waits for ev_gather[b]
+  //   UPD_COL/REST(b)    read the chain's part of the W panel           -> side waits for ev_chain[b]
+  std::vector<int> last_col(G, -1), last_rest(G, -1);    // outer block of the group's latest side-stream work
   auto ensure_event = [&](hipEvent_t& e) { return e ? hipSuccess : hipEventCreateWithFlags(&e, hipEventDisableTiming); };
   auto upd_launch = [&](int g, int kind, int b, hipStream_t st) {
     InvertGroup& Gp = P.groups[g];
@@ -1198,18 +1214,26 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
                            Gp.sub_upd_off[stp + 1] - Gp.sub_upd_off[stp], 0, gs);
         }
       }
-      if (Gp.qm_off[b + 1] > Gp.qm_off[b]) {
-        const int nmv = Gp.mv_off[b + 1] - Gp.mv_off[b];
-        const MatJobH* mvj = static_cast<const MatJobH*>(Gp.d_mv) + Gp.mv_off[b];
+      const MatJobH* mvj = static_cast<const MatJobH*>(Gp.d_mv);
+      const TileJob* bpj = static_cast<const TileJob*>(Gp.d_bp);
+      const int mv0 = Gp.mv_off[b], mv1 = Gp.mv_mid[b], mv2 = Gp.mv_off[b + 1];
+      const int bp0 = Gp.bp_off[b], bp1 = Gp.bp_mid[b], bp2 = Gp.bp_off[b + 1];
+      const int kch = agg * NB / 32;
+      const bool has_panel = Gp.qm_off[b + 1] > Gp.qm_off[b];
+      if (has_panel) {
+        if (last_col[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_col[last_col[g]], 0));
         {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
           launch_gj_qmirror(views, static_cast<const MatJobH*>(Gp.d_qm) + Gp.qm_off[b], Gp.qm_off[b + 1] - Gp.qm_off[b], gs);
+          launch_gj_move(d_moves[g], mvj + mv0, mv2 - mv0, kch, 0, gs);
         }
-        if (last_col[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_col[last_col[g]], 0));
-        ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
-        launch_gj_move(d_moves[g], mvj, nmv, agg * NB / 32, 0, gs);
-        launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_bp) + Gp.bp_off[b], Gp.bp_off[b + 1] - Gp.bp_off[b], 0, gs);
-        launch_gj_move(d_moves[g] + 1, mvj, nmv, agg * NB / 32, 1, gs);
+        HIP_TRY(ctx, ensure_event(Gp.ev_gather[b]));
+        HIP_TRY(ctx, hipEventRecord(Gp.ev_gather[b], gs));
+        if (bp1 > bp0) {
+          ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
+          launch_tile_gemm(d_descs[g], bpj + bp0, bp1 - bp0, 0, gs);
+          launch_gj_move(d_moves[g] + 1, mvj + mv0, mv1 - mv0, kch, 1, gs);
+        }
       }
       const bool has_diag = Gp.upd_off[UPD_DIAG][b + 1] > Gp.upd_off[UPD_DIAG][b];
       const bool has_col = Gp.upd_off[UPD_COL][b + 1] > Gp.upd_off[UPD_COL][b];
@@ -1218,23 +1242,29 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         if (last_rest[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_rest[last_rest[g]], 0));
         upd_launch(g, UPD_DIAG, b, gs);
       }
-      if (has_col || has_rest) {
+      if (!has_panel) continue;
+      HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_gather[b], 0));
+      if (bp2 > bp1) {
+        ScopedTiming tm(ctx, KFAC_K_INV_PANEL, side);
+        launch_tile_gemm(d_descs[g], bpj + bp1, bp2 - bp1, 0, side);
+        launch_gj_move(d_moves[g] + 1, mvj + mv1, mv2 - mv1, kch, 1, side);
+      }
+      if (bp1 > bp0) {   // the chain wrote part of the W panel
         HIP_TRY(ctx, ensure_event(Gp.ev_chain[b]));
         HIP_TRY(ctx, hipEventRecord(Gp.ev_chain[b], gs));
         HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_chain[b], 0));
-        if (has_col) {
-          upd_launch(g, UPD_COL, b, side);
-          HIP_TRY(ctx, ensure_event(Gp.ev_col[b]));
-          HIP_TRY(ctx, hipEventRecord(Gp.ev_col[b], side));
-          last_col[g] = b;
-        }
-        if (has_rest) {
-          upd_launch(g, UPD_REST, b, side);
-          HIP_TRY(ctx, ensure_event(Gp.ev_rest[b]));
-          HIP_TRY(ctx, hipEventRecord(Gp.ev_rest[b], side));
-          last_rest[g] = b;
-        }
       }
+      upd_launch(g, UPD_COL, b, side);
+      HIP_TRY(ctx, ensure_event(Gp.ev_col[b]));
+      HIP_TRY(ctx, hipEventRecord(Gp.ev_col[b], side));
+      last_col[g] = b;
+      if (has_rest) {
+        upd_launch(g, UPD_REST, b, side);
+        HIP_TRY(ctx, ensure_event(Gp.ev_rest[b]));
+        HIP_TRY(ctx, hipEventRecord(Gp.ev_rest[b], side));
+        last_rest[g] = b;
+      }
+      (void)has_col;
     }
   for (int g = 0; g < G; ++g)   // everything on the side stream must be done before the finish
     if (last_col[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gstream(g), P.groups[g].ev_col[last_col[g]], 0));
