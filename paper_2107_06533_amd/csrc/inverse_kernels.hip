@@ -97,11 +97,11 @@ __device__ __forceinline__ void sweep32(float (&r)[16], int lane, int& bad) {
   for (int t = 0; t < 16; ++t) r[t] = -r[t];
 }
 
-__global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__ mats, int mat0, int step,
-                                                      float gamma, int small) {
+__global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__ mats, const MatJob* __restrict__ jobs,
+                                                      int mat0, int step, float gamma, int small) {
   __shared__ float S[NB * SP];
   __shared__ float stage[4][SB * WP];
-  const InvMat Mx = mats[mat0 + blockIdx.x];
+  const InvMat Mx = mats[jobs ? jobs[blockIdx.x].mat : mat0 + (int)blockIdx.x];   // a job list, or consecutive matrices
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int li = lane & 31, lh = lane >> 5;
   const int d = Mx.d, ld = small ? Mx.d : Mx.ld;
@@ -484,9 +484,9 @@ void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma
   if (njobs <= 0) return;
   hipLaunchKernelGGL(gj_init_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, gamma);
 }
-void launch_gj_pivot(const InvMat* mats, int mat0, int nmats, int step, float gamma, int small, hipStream_t s) {
+void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s) {
   if (nmats <= 0) return;
-  hipLaunchKernelGGL(gj_pivot_kernel, dim3(nmats), dim3(NT), 0, s, mats, mat0, step, gamma, small);
+  hipLaunchKernelGGL(gj_pivot_kernel, dim3(nmats), dim3(NT), 0, s, mats, (const MatJob*)jobs, mat0, step, gamma, small);
 }
 void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s) {
   if (njobs <= 0) return;

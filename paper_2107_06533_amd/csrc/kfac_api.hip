@@ -66,15 +66,14 @@ struct InvertGroup {
   std::vector<int> order;            // sorted position -> position in idx (large first, descending d)
   int n_large = 0, n_small = 0, n_ob = 0, n_views = 0;
   std::vector<int> view_off, n_in_ob;            // [outer block]
-  std::vector<int> sub_active;                   // [outer block * agg + sub-step]
-  std::vector<int> sub_panel_off, sub_upd_off;   // [outer block * agg + sub-step (+1)]
+  std::vector<int> sub_pivot_off, sub_panel_off, sub_upd_off;   // [outer block * (agg + 1) + sub-step (+1)]
   std::vector<int> qm_off, mv_off, bp_off;       // [outer block (+1)]
   std::vector<int> mv_mid, bp_mid;               // [outer block]: first job that does not belong to the next outer block's rows
   std::vector<int> upd_off[3];                   // [UPD_DIAG / UPD_COL / UPD_REST][outer block (+1)]
   std::vector<size_t> ws_off;        // per large matrix: float offset of its workspace inside the group's region
   void* d_init = nullptr; int n_init = 0;
   void* d_finish = nullptr; int n_finish = 0;
-  void* d_sub_panel = nullptr; void* d_sub_upd = nullptr;
+  void* d_sub_pivot = nullptr; void* d_sub_panel = nullptr; void* d_sub_upd = nullptr;
   void* d_qm = nullptr; void* d_mv = nullptr; void* d_bp = nullptr;
   void* d_upd[3] = {nullptr, nullptr, nullptr};
   std::vector<hipEvent_t> ev_gather, ev_chain, ev_col, ev_rest;   // [outer block], created on first use
@@ -383,7 +382,7 @@ void release(FactorPlan& p) {
 }
 void release(InvertPlan& p) {
   for (InvertGroup& g : p.groups) {
-    free_dev(g.d_init); free_dev(g.d_finish); free_dev(g.d_sub_panel); free_dev(g.d_sub_upd);
+    free_dev(g.d_init); free_dev(g.d_finish); free_dev(g.d_sub_pivot); free_dev(g.d_sub_panel); free_dev(g.d_sub_upd);
     free_dev(g.d_qm); free_dev(g.d_mv); free_dev(g.d_bp);
     for (int k = 0; k < 3; ++k) free_dev(g.d_upd[k]);
     free_table(g.tab);
@@ -555,16 +554,15 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
 // The panel buffers of consecutive outer blocks alternate between two halves of the workspace so
 // that the off-chain update can still read its panels while the next ones are written.
 // All matrices of a group advance in lockstep: one launch per step covers every matrix that
-// still has that step.  Large matrices are sorted by descending size, so the matrices taking part
-// in sub-step t of outer block b are always a prefix of the block's view list.
+// still has that step.
 struct InvertSchedule {
   std::vector<int> order;
   int n_large = 0, n_small = 0, n_ob = 0, n_views = 0;
   std::vector<int> nblk, ldp, nob;
   std::vector<size_t> ws_off;
-  std::vector<int> view_off, n_in_ob, sub_active, sub_panel_off, sub_upd_off, qm_off, mv_off, bp_off, mv_mid, bp_mid;
+  std::vector<int> view_off, n_in_ob, sub_pivot_off, sub_panel_off, sub_upd_off, qm_off, mv_off, bp_off, mv_mid, bp_mid;
   std::vector<int> upd_off[3];
-  std::vector<MatJobH> init, finish, sub_panel, qm, mv;
+  std::vector<MatJobH> init, finish, sub_pivot, sub_panel, qm, mv;
   std::vector<TileJob> sub_upd, bp, upd[3];
   size_t ws_floats = 0;
   kfac_plan_stats stats{};
@@ -574,13 +572,27 @@ struct InvertSchedule {
 struct InvWsLayout {
   size_t wt, zt, swt, szt, q, qb, total;
 };
+// Outer blocks hold `agg` pivot blocks.  A last pivot block of at most TAIL_ROWS rows (the bias row of
+// a factor whose other rows fill whole blocks) joins the outer block before it instead of forming
+// one of its own, so an outer block spans at most agg + 1 pivot blocks.
+constexpr int TAIL_ROWS = 32;
+int inv_nob(int d, int agg) {
+  const int nblk = ceil_div(d, NB);
+  int nob = ceil_div(nblk, agg);
+  if (nob > 1 && (nblk - 1) % agg == 0 && d - (nblk - 1) * NB <= TAIL_ROWS) --nob;
+  return nob;
+}
+int inv_ob_end(int d, int agg, int b) {   // first pivot block behind outer block b
+  return b >= inv_nob(d, agg) - 1 ? ceil_div(d, NB) : (b + 1) * agg;
+}
 InvWsLayout inv_ws_layout(int ldp, int agg) {
   InvWsLayout L{};
-  const size_t big = size_t(2) * agg * NB * ldp;      // two halves of agg panels
-  const size_t sub = size_t(NB) * agg * NB;           // one panel of the diagonal sub-matrix
+  const size_t aw = size_t(agg + 1) * NB;             // widest outer block
+  const size_t big = 2 * aw * ldp;                    // two halves of panels
+  const size_t sub = size_t(NB) * aw;                 // one panel of the diagonal sub-matrix
   L.wt = 0; L.zt = big; L.swt = 2 * big; L.szt = 2 * big + sub; L.q = 2 * big + 2 * sub;
   L.qb = L.q + size_t(NB) * NB;
-  L.total = L.qb + size_t(agg) * NB * agg * NB;
+  L.total = L.qb + aw * aw;
   return L;
 }
 
@@ -595,7 +607,7 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
     const int d = dims[S.order[m]];
     S.nblk[m] = ceil_div(d, NB);
     S.ldp[m] = S.nblk[m] * NB;
-    S.nob[m] = ceil_div(S.nblk[m], agg);
+    S.nob[m] = inv_nob(d, agg);
     S.ws_off[m] = S.ws_floats;
     S.ws_floats += inv_ws_layout(S.ldp[m], agg).total;
     S.n_ob = std::max(S.n_ob, S.nob[m]);
@@ -611,9 +623,10 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
     S.view_off[b + 1] = S.view_off[b] + S.n_in_ob[b];
   }
   S.n_views = S.view_off[S.n_ob];
-  S.sub_active.assign(size_t(S.n_ob) * agg, 0);
-  S.sub_panel_off.assign(size_t(S.n_ob) * agg + 1, 0);
-  S.sub_upd_off.assign(size_t(S.n_ob) * agg + 1, 0);
+  const int aw = agg + 1;   // sub-steps per outer block
+  S.sub_pivot_off.assign(size_t(S.n_ob) * aw + 1, 0);
+  S.sub_panel_off.assign(size_t(S.n_ob) * aw + 1, 0);
+  S.sub_upd_off.assign(size_t(S.n_ob) * aw + 1, 0);
   S.qm_off.assign(S.n_ob + 1, 0); S.mv_off.assign(S.n_ob + 1, 0); S.bp_off.assign(S.n_ob + 1, 0);
   S.mv_mid.assign(S.n_ob, 0); S.bp_mid.assign(S.n_ob, 0);
   for (int k = 0; k < 3; ++k) S.upd_off[k].assign(S.n_ob + 1, 0);
@@ -621,15 +634,16 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
   for (int b = 0; b < S.n_ob; ++b) {
     const int ob0 = b * agg;
     // ---- step 1: sweeps of the diagonal sub-matrices (views)
-    for (int t = 0; t < agg; ++t) {
-      const int st = b * agg + t;
+    for (int t = 0; t < aw; ++t) {
+      const int st = b * aw + t;
       for (int m = 0; m < S.n_in_ob[b]; ++m) {
         const int v = S.view_off[b] + m;
         const int d = dims[S.order[m]];
-        const int nsub = std::min(agg, S.nblk[m] - ob0);
-        const int dimB = std::min(agg * NB, d - ob0 * NB);
+        const int ob1 = inv_ob_end(d, agg, b);
+        const int nsub = ob1 - ob0;
+        const int dimB = std::min(d, ob1 * NB) - ob0 * NB;
         if (t >= nsub) continue;
-        S.sub_active[st]++;
+        S.sub_pivot.push_back({v, 0, 0, 0});
         const int kb = std::min(NB, dimB - t * NB);
         for (int it = 0; it < nsub; ++it)
           if (it != t) S.sub_panel.push_back({v, it, 0, 0});
@@ -643,9 +657,10 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
           }
         S.stats.mfma_flops += int64_t(nsub - 1) * NB * 16 * 32 * 32 * 2;   // panel products
       }
+      S.sub_pivot_off[st + 1] = int(S.sub_pivot.size());
       S.sub_panel_off[st + 1] = int(S.sub_panel.size());
       S.sub_upd_off[st + 1] = int(S.sub_upd.size());
-      launches += (S.sub_active[st] > 0) + (S.sub_panel_off[st + 1] > S.sub_panel_off[st]) + (S.sub_upd_off[st + 1] > S.sub_upd_off[st]);
+      launches += (S.sub_pivot_off[st + 1] > S.sub_pivot_off[st]) + (S.sub_panel_off[st + 1] > S.sub_panel_off[st]) + (S.sub_upd_off[st + 1] > S.sub_upd_off[st]);
     }
     // ---- steps 2-4 for the matrices that have more than one outer block.  The gather/scatter and
     // panel-product jobs of the rows of the NEXT outer block come first in their lists: the chain
@@ -656,8 +671,8 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
       if (S.nob[m] < 2) continue;
       const int v = S.view_off[b] + m;
       const int d = dims[S.order[m]];
-      const int ob1 = std::min(ob0 + agg, S.nblk[m]), nb1 = std::min(ob1 + agg, S.nblk[m]);
-      const int dimB = std::min(agg * NB, d - ob0 * NB);
+      const int ob1 = inv_ob_end(d, agg, b), nb1 = b + 1 < S.nob[m] ? inv_ob_end(d, agg, b + 1) : ob1;
+      const int dimB = std::min(d, ob1 * NB) - ob0 * NB;
       const int half = b & 1;
       auto in_ob = [&](int x) { return x >= ob0 && x < ob1; };
       auto in_next = [&](int x) { return x >= ob1 && x < nb1; };
@@ -679,7 +694,7 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
           if (in_ob(bi) || in_ob(bj)) continue;
           TileJob j{};
           j.desc = 2 * S.n_views + m; j.bi = bi; j.bj = bj; j.part = -1;
-          j.kbeg = half * agg * NB; j.kend = j.kbeg + dimB;
+          j.kbeg = half * aw * NB; j.kend = j.kbeg + dimB;
           S.upd[(in_next(bi) && in_next(bj)) ? UPD_DIAG : (in_next(bi) || in_next(bj)) ? UPD_COL : UPD_REST].push_back(j);
           S.stats.mfma_flops += int64_t(ceil_div(dimB, KC) * KC) * active_blocks(d, d, bi, bj, true) * 32 * 32 * 2;
         }
@@ -695,7 +710,7 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
       launches += S.upd_off[k][b + 1] > S.upd_off[k][b];
     }
   }
-  S.stats.n_jobs = int64_t(S.init.size() + S.finish.size() + S.sub_panel.size() + S.sub_upd.size() + S.qm.size() +
+  S.stats.n_jobs = int64_t(S.init.size() + S.finish.size() + S.sub_pivot.size() + S.sub_panel.size() + S.sub_upd.size() + S.qm.size() +
                            2 * S.mv.size() + S.bp.size() + S.upd[0].size() + S.upd[1].size() + S.upd[2].size()) + S.n_small;
   S.stats.n_launches = (S.n_small ? 1 : 0) + (S.n_large ? 2 + launches : 0);
   S.stats.ws_bytes = int64_t(S.ws_floats * sizeof(float));
@@ -1035,7 +1050,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       for (int i : Gp.idx) gd.push_back(dims[i]);
       InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), ctx->inv_agg);
       Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.n_ob = S.n_ob; Gp.n_views = S.n_views;
-      Gp.view_off = S.view_off; Gp.n_in_ob = S.n_in_ob; Gp.sub_active = S.sub_active;
+      Gp.view_off = S.view_off; Gp.n_in_ob = S.n_in_ob; Gp.sub_pivot_off = S.sub_pivot_off;
       Gp.sub_panel_off = S.sub_panel_off; Gp.sub_upd_off = S.sub_upd_off;
       Gp.qm_off = S.qm_off; Gp.mv_off = S.mv_off; Gp.bp_off = S.bp_off; Gp.mv_mid = S.mv_mid; Gp.bp_mid = S.bp_mid;
       for (int k = 0; k < 3; ++k) Gp.upd_off[k] = S.upd_off[k];
@@ -1053,6 +1068,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         auto up = [&](void** dev, const void* src, size_t bytes) { return upload_static(ctx, dev, src, bytes); };
         if ((st = up(&Gp.d_init, S.init.data(), S.init.size() * sizeof(MatJobH))) != KFAC_OK) return st;
         if ((st = up(&Gp.d_finish, S.finish.data(), S.finish.size() * sizeof(MatJobH))) != KFAC_OK) return st;
+        if ((st = up(&Gp.d_sub_pivot, S.sub_pivot.data(), S.sub_pivot.size() * sizeof(MatJobH))) != KFAC_OK) return st;
         if ((st = up(&Gp.d_sub_panel, S.sub_panel.data(), S.sub_panel.size() * sizeof(MatJobH))) != KFAC_OK) return st;
         if ((st = up(&Gp.d_sub_upd, S.sub_upd.data(), S.sub_upd.size() * sizeof(TileJob))) != KFAC_OK) return st;
         if ((st = up(&Gp.d_qm, S.qm.data(), S.qm.size() * sizeof(MatJobH))) != KFAC_OK) return st;
@@ -1091,7 +1107,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   std::vector<const PanelMove*> d_moves(G);
   std::vector<const TileDesc*> d_descs(G);
   float* wsf = static_cast<float*>(ctx->ws);
-  const int agg = ctx->inv_agg;
+  const int agg = ctx->inv_agg, aw = agg + 1;
   for (int g = 0; g < G; ++g) {
     InvertGroup& Gp = P.groups[g];
     const int ng = int(Gp.idx.size()), nv = Gp.n_views;
@@ -1113,34 +1129,34 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       M.xelems = uint32_t(M.d) * uint32_t(M.d);
       M.ldp = NB;
       if (m >= Gp.n_large) continue;
-      const int d = M.d, nblk = ceil_div(d, NB), ldp = nblk * NB, nob = ceil_div(nblk, agg);
+      const int d = M.d, nblk = ceil_div(d, NB), ldp = nblk * NB, nob = inv_nob(d, agg);
       const InvWsLayout L = inv_ws_layout(ldp, agg);
       float* base = wsf + Gp.ws_base + Gp.ws_off[m];
       M.ldp = ldp;
       TileDesc& DU = hd[2 * nv + m];    // step 4: X -= Wt^T Zt over one half of the panel buffers
-      DU.a = rowmajor_operand(base + L.wt, 2 * agg * NB, ldp, ldp);
-      DU.b = rowmajor_operand(base + L.zt, 2 * agg * NB, ldp, ldp);
+      DU.a = rowmajor_operand(base + L.wt, 2 * aw * NB, ldp, ldp);
+      DU.b = rowmajor_operand(base + L.zt, 2 * aw * NB, ldp, ldp);
       DU.out = M.X; DU.ldo = d; DU.M = DU.N = d;
       DU.sym = 1; DU.mirror = MIRROR_DIAG_TILE; DU.alpha = -1.f; DU.beta = 1.f;
       for (int b = 0; b < nob; ++b) {
         const int v = Gp.view_off[b] + m;
-        const int c0 = b * agg * NB, dimB = std::min(agg * NB, d - c0), half = b & 1;
+        const int c0 = b * agg * NB, dimB = std::min(d, inv_ob_end(d, agg, b) * NB) - c0, half = b & 1;
         InvMat& V = hv[v];              // step 1: the diagonal sub-matrix as a matrix of its own
-        V.F = nullptr; V.X = M.X + size_t(c0) * d + c0; V.d = dimB; V.ld = d; V.ldp = agg * NB;
+        V.F = nullptr; V.X = M.X + size_t(c0) * d + c0; V.d = dimB; V.ld = d; V.ldp = aw * NB;
         V.Wt = base + L.swt; V.Zt = base + L.szt; V.Q = base + L.q; V.QB = base + L.qb;
         V.info = M.info; V.info_base = c0;
         V.xelems = uint32_t(size_t(d) * d - (size_t(c0) * d + c0));
         TileDesc& DS = hd[v];
-        DS.a = rowmajor_operand(V.Wt, NB, agg * NB, agg * NB);
-        DS.b = rowmajor_operand(V.Zt, NB, agg * NB, agg * NB);
+        DS.a = rowmajor_operand(V.Wt, NB, aw * NB, aw * NB);
+        DS.b = rowmajor_operand(V.Zt, NB, aw * NB, aw * NB);
         DS.out = V.X; DS.ldo = d; DS.M = DS.N = dimB;
         DS.sym = 1; DS.mirror = MIRROR_DIAG_TILE; DS.alpha = -1.f; DS.beta = 1.f;
-        float* wt_half = base + L.wt + size_t(half) * agg * NB * ldp;
-        float* zt_half = base + L.zt + size_t(half) * agg * NB * ldp;
+        float* wt_half = base + L.wt + size_t(half) * aw * NB * ldp;
+        float* zt_half = base + L.zt + size_t(half) * aw * NB * ldp;
         hp[2 * v] = PanelMove{M.X, zt_half, d, ldp, c0, dimB};       // step 2: gather Z
         hp[2 * v + 1] = PanelMove{M.X, wt_half, d, ldp, c0, dimB};   // step 3: scatter W
         TileDesc& DP = hd[nv + v];      // step 3: Wt = QB Zt
-        DP.a = rowmajor_operand(V.QB, dimB, dimB, agg * NB);
+        DP.a = rowmajor_operand(V.QB, dimB, dimB, aw * NB);
         DP.b = rowmajor_operand(zt_half, dimB, ldp, ldp);
         DP.out = wt_half; DP.ldo = ldp; DP.M = dimB; DP.N = ldp;
         DP.sym = 0; DP.mirror = MIRROR_NONE; DP.alpha = 1.f; DP.beta = 0.f;
@@ -1162,7 +1178,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     max_ob = std::max(max_ob, Gp.n_ob);
     if (Gp.n_small) {
       ScopedTiming tm(ctx, KFAC_K_INV_SMALL, gs);
-      launch_gj_pivot(d_mats[g], Gp.n_large, Gp.n_small, 0, gamma, 1, gs);
+      launch_gj_pivot(d_mats[g], nullptr, Gp.n_large, Gp.n_small, 0, gamma, 1, gs);
     }
     if (Gp.n_large) {
       ScopedTiming tm(ctx, KFAC_K_INV_INIT, gs);
@@ -1196,12 +1212,13 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       if (b >= Gp.n_ob) continue;
       hipStream_t gs = gstream(g), side = ctx->inv_side[g];
       const InvMat* views = d_views[g];
-      for (int t = 0; t < agg; ++t) {
-        const int stp = b * agg + t;
-        if (Gp.sub_active[stp] == 0) break;
+      for (int t = 0; t < aw; ++t) {
+        const int stp = b * aw + t;
+        const int npiv = Gp.sub_pivot_off[stp + 1] - Gp.sub_pivot_off[stp];
+        if (npiv == 0) break;
         {
           ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
-          launch_gj_pivot(views, Gp.view_off[b], Gp.sub_active[stp], t, gamma, 0, gs);
+          launch_gj_pivot(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp], 0, npiv, t, gamma, 0, gs);
         }
         if (Gp.sub_panel_off[stp + 1] > Gp.sub_panel_off[stp]) {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
@@ -1218,7 +1235,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       const TileJob* bpj = static_cast<const TileJob*>(Gp.d_bp);
       const int mv0 = Gp.mv_off[b], mv1 = Gp.mv_mid[b], mv2 = Gp.mv_off[b + 1];
       const int bp0 = Gp.bp_off[b], bp1 = Gp.bp_mid[b], bp2 = Gp.bp_off[b + 1];
-      const int kch = agg * NB / 32;
+      const int kch = aw * NB / 32;
       const bool has_panel = Gp.qm_off[b + 1] > Gp.qm_off[b];
       if (has_panel) {
         if (last_col[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_col[last_col[g]], 0));

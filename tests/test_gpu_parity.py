@@ -148,7 +148,8 @@ def run_invert(ctx, Fs, gamma):
 
 
 def test_invert_batch_mixed_sizes(ctx):
-    dims = [1, 2, 3, 17, 64, 65, 127, 128, 129, 148, 256, 257, 300, 513, 640, 1025]
+    # incl. short last pivot blocks that join the previous outer block (513, 1025, 1040) and ones that do not (641, 1060)
+    dims = [1, 2, 3, 17, 64, 65, 127, 128, 129, 148, 256, 257, 300, 513, 640, 641, 1025, 1040, 1060]
     gamma = 0.03
     Fs = [spd(d, d, 5.0) + 0.5 * np.eye(d) for d in dims]
     F_d, X_d, info = run_invert(ctx, Fs, gamma)
