@@ -371,7 +371,9 @@ std::vector<TileJob> xcd_arrange(const std::vector<std::vector<TileJob>>& groups
 }
 
 bool xcd_enabled() {
-  static const bool on = !(std::getenv("KFAC_XCD") && std::atoi(std::getenv("KFAC_XCD")) == 0);
+  // off by default: with jobs sorted longest first, dealing contiguous segments to the XCDs measured
+  // 2 % slower on the ResNet-50 set than plain index order
+  static const bool on = std::getenv("KFAC_XCD") && std::atoi(std::getenv("KFAC_XCD")) != 0;
   return on;
 }
 
