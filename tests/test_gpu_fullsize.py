@@ -138,3 +138,57 @@ def test_large_sets_sampled_against_oracle(ctx, name):
         if i not in sample:
             check_layer_properties(i, l, hp, out)
     print(f"{name}: properties of the other {len(layers) - len(sample)} layers {time.perf_counter() - t0:.1f} s", flush=True)
+
+
+def test_invert_largest_dimension(ctx):
+    """d = 16384, the largest matrix kfac_invert_batch accepts: checked by the properties that hold at
+    any size (exact symmetry, damped-inverse residual in fp64 on the device); the oracle would need
+    minutes for this one matrix."""
+    import torch
+    d, gamma = 16384, 0.03
+    g = torch.Generator(device="cuda").manual_seed(210706533)
+    B = torch.randn((d, 256), device="cuda", generator=g)
+    F = 0.05 * (B @ B.T) / 256.0                # one running-average step from the identity, as every factor here
+    F.diagonal().add_(0.95)
+    F = torch.tril(F) + torch.tril(F, -1).T
+    X = torch.empty_like(F)
+    info = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    del B
+    ctx.kfac_invert_batch([d], [F], [X], gamma, info)
+    torch.cuda.synchronize()
+    assert int(info[0]) == 0
+    assert torch.equal(X, X.T)
+    res = 0.0
+    for c0 in range(0, d, 4096):                # residual column block by column block (bounded fp64 temporaries)
+        Rb = F.double() @ X[:, c0:c0 + 4096].double() + gamma * X[:, c0:c0 + 4096].double()
+        Rb[c0:c0 + 4096, :].diagonal().sub_(1.0)
+        res += float((Rb * Rb).sum())
+    res = (res / d) ** 0.5
+    print(f"\nd={d}: residual {res:.3e}", flush=True)
+    assert res <= TOL_INVERSE
+
+
+def test_factor_largest_operand(ctx):
+    """A linear layer whose activation tensor has 2^28 elements (1 GiB, the largest operand the library
+    accepts): sampled entries of A against the oracle's definition evaluated one entry at a time."""
+    import torch
+    rows, cin = 65536, 4096
+    layer = shapes.linear(rows, cin, 8, has_bias=1)
+    rng = np.random.default_rng(7)
+    a = rng.standard_normal((rows, cin), dtype=np.float32)
+    np.maximum(a, 0.0, out=a)
+    a_d = torch.from_numpy(a).cuda()
+    A_d = torch.eye(layer.dA, device="cuda")
+    ctx.kfac_update_factors([layer], [a_d], None, [A_d], None, 0.95)
+    torch.cuda.synchronize()
+    assert torch.equal(A_d, A_d.T)
+    idx = rng.integers(0, layer.dA, size=(300, 2))
+    idx[:20, 1] = layer.dA - 1                   # bias column
+    idx[20:30, 0] = idx[20:30, 1]                # diagonal
+    idx[30] = (layer.dA - 1, layer.dA - 1)
+    got = A_d[torch.from_numpy(idx[:, 0]).cuda(), torch.from_numpy(idx[:, 1]).cuda()].cpu().numpy().astype(np.float64)
+    col = lambda q: np.ones(rows) if q == cin else a[:, q].astype(np.float64)
+    want = np.array([0.95 * (i == j) + 0.05 * float(col(i) @ col(j)) / rows for i, j in idx])
+    err = np.linalg.norm(got - want) / np.linalg.norm(want)
+    print(f"\nlargest operand: sampled rel error {err:.3e}", flush=True)
+    assert err <= TOL_FACTOR
