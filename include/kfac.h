@@ -27,6 +27,17 @@
  *   - Errors are returned, never thrown.  Arguments are validated on the host
  *     before anything is launched; kfac_last_error() describes the last failure.
  *   - Arithmetic is fp32 throughout (fp32 MFMA, fp32 accumulation).
+ *   - Limits (checked, KFAC_ERR_INVALID_ARG): every activation / gradient tensor holds at
+ *     most 2^28 elements (1 GiB; operands are addressed with 32-bit byte offsets), convolution
+ *     windows have at most 63 taps, matrices to invert have d <= 16384.
+ *   - kfac_invert_batch also launches on internal streams of the context (default priority),
+ *     forked from and joined back into `hip_stream` with events before the call returns; the
+ *     work is complete when `hip_stream` is.  The first call for a new set of shapes builds and
+ *     uploads a schedule (it synchronises the device once); later calls with the same shapes only
+ *     refresh a small pointer table.
+ *   - Activation factors of 3x3 / stride 1 / pad 1 convolutions with >= 64 input channels are
+ *     summed in a different order than the patch-matrix product (products over pixel lags,
+ *     then assembled); the result is the same sum up to fp32 rounding.
  */
 #ifndef KFAC_H_
 #define KFAC_H_
