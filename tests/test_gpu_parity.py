@@ -274,6 +274,15 @@ def test_cnn_config(ctx):
     print(run_config_steps(ctx, "cnn", 2))
 
 
+def test_cnn_config_on_user_stream(ctx):
+    """The same step issued on a caller-created (non-default) stream: the inverse forks its internal
+    streams from that stream and joins them back into it."""
+    import torch
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        print(run_config_steps(ctx, "cnn", 1))
+
+
 def test_empty_calls_are_noops(ctx):
     assert ctx.kfac_update_factors([], None, None, None, None, 0.95) == 0
     assert ctx.kfac_invert_batch([], None, None, 0.03) == 0
