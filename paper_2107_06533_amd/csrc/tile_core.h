@@ -420,28 +420,9 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
   __syncthreads();
   int cur = 0;
   for (int kt = 1; kt < nkt; ++kt) {
-#if defined(KFAC_EXP)
-    // timing experiments only (results are wrong): 1 = no global loads / LDS stores, 2 = also no
-    // barrier, 3 = loads, stores and barrier but no MFMA work
-#if KFAC_EXP == 1 || KFAC_EXP == 2
-    mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
-#if KFAC_EXP == 1
-    __syncthreads();
-#endif
-#else
-    la.load(kbeg + kt * KC, ra);
-    if (!SHARE) load_b<LA, LB, SAME>(la, lb, kbeg + kt * KC, rb);
-    la.store(As + (cur ^ 1) * PANEL, ra);
-    if (!SHARE) lb.store(Bs + (cur ^ 1) * PANEL, rb);
-    __syncthreads();
-#endif
-    cur ^= 1;
-    continue;
-#else
     la.load(kbeg + kt * KC, ra);
     if (!SHARE) load_b<LA, LB, SAME>(la, lb, kbeg + kt * KC, rb);
     mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
-#endif
     la.store(As + (cur ^ 1) * PANEL, ra);
     if (!SHARE) lb.store(Bs + (cur ^ 1) * PANEL, rb);
     __syncthreads();

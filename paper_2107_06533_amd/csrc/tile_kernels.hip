@@ -151,7 +151,8 @@ __global__ __launch_bounds__(NT) void lag_assemble_kernel(const LagAsm* __restri
   const int dA = L.dA, nb = 9 * L.C;
   constexpr int PER = LAG_TILE * LAG_TILE / NT;
   gf_ptr A = as_global(L.A);
-  const int lc = threadIdx.x & (LAG_TILE - 1), lr0 = threadIdx.x >> 6;
+  // a wave shares its row: row-derived index arithmetic runs on the scalar unit
+  const int lc = threadIdx.x & (LAG_TILE - 1), lr0 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int cc = J.bj * LAG_TILE + lc;                  // this thread's column
   const bool cbias = cc >= nb;
   const int c2 = cbias ? L.C : cc / 9, t2 = cbias ? 0 : cc - 9 * c2, i2 = t2 / 3, j2 = t2 - 3 * i2;
