@@ -21,6 +21,10 @@ What is computed, and where the paper defines it:
   gradient (Eq. kfacfinal with P = 1), evaluated as G^-1 . V . A^-1 on the
   [dG, dA] weight-gradient matrix.
 
+* Packed upper triangles of symmetric factors and inverses, the form in which the
+  paper communicates them (Sec. IV-A: d(d+1)/2 elements per factor; Sec. V-B: upper
+  triangle including the diagonal).
+
 Parity pins live in tests/test_oracle_*.py: brute-force sums, closed forms
 (Sherman-Morrison, diagonal, 2x2), statistical limits, and the brute-force
 Kronecker solve.  Every function below has at least one such pin.
@@ -155,6 +159,43 @@ def precondition(XG: np.ndarray, XA: np.ndarray, V) -> np.ndarray:
     the Kronecker-product inverse applied to the layer's gradient)."""
     V = np.asarray(V, dtype=np.float64)
     return np.asarray(XG, dtype=np.float64) @ V @ np.asarray(XA, dtype=np.float64)
+
+
+# ------------------------------------------------------------- packed triangles
+
+def packed_size(d: int) -> int:
+    """Number of communicated elements of a symmetric d x d factor: d (d + 1) / 2 (Sec. IV-A)."""
+    return d * (d + 1) // 2
+
+
+def pack_upper(M: np.ndarray) -> np.ndarray:
+    """Upper triangle of a symmetric matrix including the diagonal, row after row (Sec. V-B: only
+    these elements of a factor or of an inverse are sent): [m00 m01 .. m0,d-1 | m11 .. | .. | m_d-1,d-1].
+    Written as the explicit double loop; no symmetry is assumed (the lower triangle is ignored)."""
+    M = np.asarray(M)
+    d = M.shape[0]
+    assert M.shape == (d, d)
+    out = np.empty(packed_size(d), dtype=M.dtype)
+    p = 0
+    for i in range(d):
+        for j in range(i, d):
+            out[p] = M[i, j]
+            p += 1
+    return out
+
+
+def unpack_upper(packed: np.ndarray, d: int) -> np.ndarray:
+    """Inverse of pack_upper: the full symmetric matrix whose upper triangle is `packed`."""
+    packed = np.asarray(packed)
+    assert packed.shape == (packed_size(d),)
+    M = np.empty((d, d), dtype=packed.dtype)
+    p = 0
+    for i in range(d):
+        for j in range(i, d):
+            M[i, j] = packed[p]
+            M[j, i] = packed[p]
+            p += 1
+    return M
 
 
 # --------------------------------------------------------------------- whole step
