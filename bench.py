@@ -188,6 +188,37 @@ def main():
             breakdown[k] = {"ms_per_step": round(ms / reps, 4), "launches_per_step": cnt // reps}
         ctx.timing_enable([])
 
+    # ---- packed upper triangles of all factors (what a multi-GPU job would put on the wire): an
+    # HBM-bound move, reported next to the step, not part of it
+    packed_io = None
+    if not args.no_breakdown:
+        tot, _ = ctx.packed_elems(dims)
+        pbuf = torch.empty((tot,), device="cuda")
+        reps = 20
+        ev_p = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for _ in range(3):
+            ctx.kfac_pack_triangles(dims, A_d + G_d, pbuf, stream=stream)
+            ctx.kfac_unpack_triangles(dims, pbuf, XA_d + XG_d, stream=stream)
+        ev_p[0].record(stream)
+        for _ in range(reps):
+            ctx.kfac_pack_triangles(dims, A_d + G_d, pbuf, stream=stream)
+        ev_p[1].record(stream)
+        for _ in range(reps):
+            ctx.kfac_unpack_triangles(dims, pbuf, XA_d + XG_d, stream=stream)
+        ev_p[2].record(stream)
+        torch.cuda.synchronize()
+        pack_ms, unpack_ms = ev_p[0].elapsed_time(ev_p[1]) / reps, ev_p[1].elapsed_time(ev_p[2]) / reps
+        full_bytes = 4 * sum(d * d for d in dims)
+        pack_bytes, unpack_bytes = 2 * 4 * tot, 4 * tot + full_bytes      # read + write, algorithmic
+        packed_io = {"packed_elems": tot, "pack_ms": round(pack_ms, 4), "unpack_ms": round(unpack_ms, 4),
+                     "pack_gbps": round(pack_bytes / pack_ms / 1e6, 1), "unpack_gbps": round(unpack_bytes / unpack_ms / 1e6, 1),
+                     "bound": "hbm", "peak_gbps": 8000.0,
+                     "pack_frac": round(pack_bytes / pack_ms / 1e6 / 8000.0, 4),
+                     "unpack_frac": round(unpack_bytes / unpack_ms / 1e6 / 8000.0, 4)}
+        del pbuf
+        step()          # the unpack above overwrote the inverses: restore a consistent state
+        torch.cuda.synchronize()
+
     factor_flops = fl["factor_a"] + fl["factor_g"]
     dom_avg_ms = dom_ms / dom_n
     achieved = factor_flops / (dom_avg_ms * 1e-3) / 1e12
@@ -240,6 +271,8 @@ def main():
     }
     if breakdown is not None:
         out["kernel_breakdown"] = breakdown
+    if packed_io is not None:
+        out["packed_io"] = packed_io
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(layers, hp, args.cpu_budget, fl["total"])
     ctx.close()

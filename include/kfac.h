@@ -144,6 +144,27 @@ kfac_status kfac_precondition(kfac_ctx* ctx, int n_layers, const int32_t* dG, co
                               const float* const* Ginv, const float* const* Ainv,
                               const float* const* gradW, float* const* out, void* hip_stream);
 
+/*
+ * Packed upper triangles: the form in which the paper communicates symmetric factors and
+ * inverses between workers (Sec. IV-A: d(d+1)/2 communicated elements per factor; Sec. V-B: the
+ * upper triangle including the diagonal).  The triangles of the n matrices are concatenated in one
+ * device buffer, matrix after matrix, each row after row:
+ *     packed[off_m + i*d - i*(i-1)/2 + (j - i)] = M_m[i][j],   0 <= i <= j < d_m.
+ * kfac_packed_elems returns the total number of floats (0 on invalid input) and, if `offsets` is
+ * not NULL, writes the n+1 float offsets off_0 .. off_n (host memory; pure host).
+ * kfac_pack_triangles   reads only the upper triangle of every M_m (device, [d,d] row-major).
+ * kfac_unpack_triangles writes every M_m full and exactly symmetric.
+ * dims: host array, 1 <= d <= 46340.  M: host array of device pointers.  packed: device buffer of
+ * kfac_packed_elems floats, owned by the caller.  Asynchronous on hip_stream.
+ * Returns INVALID_ARG for NULL ctx/dims/M/packed, n_mats < 0, dims out of range, NULL entries.
+ * n_mats == 0 is a no-op.
+ */
+size_t kfac_packed_elems(int n_mats, const int32_t* dims, int64_t* offsets);
+kfac_status kfac_pack_triangles(kfac_ctx* ctx, int n_mats, const int32_t* dims, const float* const* M,
+                                float* packed, void* hip_stream);
+kfac_status kfac_unpack_triangles(kfac_ctx* ctx, int n_mats, const int32_t* dims, const float* packed,
+                                  float* const* M, void* hip_stream);
+
 /* Schedule statistics of the most recent call of each kind on this context (pure host;
  * for tests and benchmarks).  Fields that do not apply are 0. */
 typedef struct {
@@ -173,7 +194,8 @@ enum {
   KFAC_K_INV_FINISH = 7,
   KFAC_K_PRECOND_LEFT = 8,  /* Ginv . V                                                        */
   KFAC_K_PRECOND_RIGHT = 9, /* (Ginv . V) . Ainv                                               */
-  KFAC_K_COUNT = 10
+  KFAC_K_TRI_PACK = 10,     /* packed upper triangles <-> full matrices                        */
+  KFAC_K_COUNT = 11
 };
 void kfac_timing_enable(kfac_ctx* ctx, uint32_t class_mask);
 kfac_status kfac_timing_read(kfac_ctx* ctx, int kclass, double* total_ms, int64_t* n_launches, int reset);

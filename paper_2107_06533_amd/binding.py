@@ -15,11 +15,12 @@ EXPORTS = [
     "kfac_layer_dA", "kfac_layer_dG", "kfac_layer_rows",
     "kfac_workspace_bytes_factors", "kfac_workspace_bytes_invert", "kfac_workspace_bytes_precondition",
     "kfac_update_factors", "kfac_invert_batch", "kfac_check_info", "kfac_precondition",
+    "kfac_packed_elems", "kfac_pack_triangles", "kfac_unpack_triangles",
     "kfac_get_plan_stats", "kfac_timing_enable", "kfac_timing_read",
 ]
 
 KERNEL_CLASSES = ["factor_tiles", "factor_reduce", "inv_small", "inv_init", "inv_pivot", "inv_panel",
-                  "inv_update", "inv_finish", "precond_left", "precond_right"]
+                  "inv_update", "inv_finish", "precond_left", "precond_right", "tri_pack"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -86,6 +87,12 @@ def load():
     lib.kfac_check_info.restype = C.c_int
     lib.kfac_precondition.argtypes = [vp, C.c_int, i32p, i32p, fpp, fpp, fpp, fpp, vp]
     lib.kfac_precondition.restype = C.c_int
+    lib.kfac_packed_elems.argtypes = [C.c_int, i32p, C.POINTER(C.c_int64)]
+    lib.kfac_packed_elems.restype = C.c_size_t
+    lib.kfac_pack_triangles.argtypes = [vp, C.c_int, i32p, fpp, vp, vp]
+    lib.kfac_pack_triangles.restype = C.c_int
+    lib.kfac_unpack_triangles.argtypes = [vp, C.c_int, i32p, vp, fpp, vp]
+    lib.kfac_unpack_triangles.restype = C.c_int
     lib.kfac_get_plan_stats.argtypes = [vp, C.c_int, C.POINTER(plan_stats)]
     lib.kfac_get_plan_stats.restype = None
     lib.kfac_timing_enable.argtypes = [vp, C.c_uint32]
@@ -197,6 +204,29 @@ class Context:
         if check:
             self._check(st)
         return st
+
+    def kfac_pack_triangles(self, dims, M, packed, stream=None, check: bool = True) -> int:
+        n = len(dims)
+        st = self.lib.kfac_pack_triangles(self.h, n, _i32_array(dims) if n else None, _ptr_array(M, n), _ptr(packed),
+                                          _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def kfac_unpack_triangles(self, dims, packed, M, stream=None, check: bool = True) -> int:
+        n = len(dims)
+        st = self.lib.kfac_unpack_triangles(self.h, n, _i32_array(dims) if n else None, _ptr(packed), _ptr_array(M, n),
+                                            _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def packed_elems(self, dims):
+        """(total floats, offsets[n+1]) of the concatenated packed upper triangles."""
+        n = len(dims)
+        off = (C.c_int64 * (n + 1))()
+        tot = int(self.lib.kfac_packed_elems(n, _i32_array(dims) if n else None, off))
+        return tot, [int(v) for v in off]
 
     # -- host-side queries -------------------------------------------------------------------
     def workspace_bytes_factors(self, layers) -> int:

@@ -149,4 +149,12 @@ struct PanelMove {
   int32_t d, ldp, c0, w;
 };
 
+// ---- packed upper triangles ---------------------------------------------------------------------
+// Element (i, j), i <= j, of matrix m lives at packed[off + i*d - i*(i-1)/2 + (j - i)].
+struct PackMat {
+  float* M;        // full matrix [d][d]
+  uint64_t off;    // float offset of the matrix's triangle in the concatenated buffer
+  int32_t d, pad;
+};
+
 }  // namespace kfac

@@ -480,6 +480,50 @@ __global__ __launch_bounds__(NT) void gj_move_kernel(const PanelMove* __restrict
     }
 }
 
+// ---- packed upper triangles <-> full symmetric matrices -------------------------------------------
+// One job per 64 x 64 tile (bi <= bj) of the upper triangle.  to_full = 0: packed <- upper triangle
+// of M (rows are contiguous on both sides).  to_full = 1: M <- packed, both triangles; the mirror
+// image goes through LDS so that it is stored row by row as well.
+constexpr int PT = 64;
+__global__ __launch_bounds__(NT) void tri_pack_kernel(const PackMat* __restrict__ mats, const MatJob* __restrict__ jobs,
+                                                      int njobs, float* __restrict__ packed, int to_full) {
+  __shared__ float tile[PT][PT + 1];
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const MatJob J = jobs[g];
+  const PackMat P = mats[J.mat];
+  const int d = P.d;
+  const int tx = threadIdx.x & (PT - 1), ty = threadIdx.x >> 6;   // 64 x 4
+  gf_ptr M = as_global(P.M);
+  gf_ptr T = as_global(packed) + P.off;
+  constexpr int PER = PT * PT / NT;
+  float v[PER];
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const int i = J.bi * PT + ty + 4 * r, j = J.bj * PT + tx;
+    const size_t p = (size_t)i * d - (size_t)i * (i - 1) / 2 + (size_t)(j - i);
+    v[r] = 0.f;
+    if (i < d && j < d && i <= j) v[r] = to_full ? T[p] : M[(size_t)i * d + j];
+  }
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const int i = J.bi * PT + ty + 4 * r, j = J.bj * PT + tx;
+    const size_t p = (size_t)i * d - (size_t)i * (i - 1) / 2 + (size_t)(j - i);
+    if (i < d && j < d && i <= j) {
+      if (to_full) M[(size_t)i * d + j] = v[r];
+      else T[p] = v[r];
+    }
+    tile[ty + 4 * r][tx] = v[r];
+  }
+  if (!to_full) return;
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {   // element (jj, ii) of the mirrored tile = tile[ii - i0][jj - j0]
+    const int jj = J.bj * PT + ty + 4 * r, ii = J.bi * PT + tx;
+    if (jj < d && ii < jj) M[(size_t)jj * d + ii] = tile[tx][ty + 4 * r];
+  }
+}
+
 void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma, hipStream_t s) {
   if (njobs <= 0) return;
   hipLaunchKernelGGL(gj_init_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, gamma);
@@ -499,6 +543,10 @@ void launch_gj_qmirror(const InvMat* mats, const void* jobs, int njobs, hipStrea
 void launch_gj_move(const PanelMove* moves, const void* jobs, int njobs, int kchunks, int to_matrix, hipStream_t s) {
   if (njobs <= 0 || kchunks <= 0) return;
   hipLaunchKernelGGL(gj_move_kernel, dim3(njobs, kchunks), dim3(NT), 0, s, moves, (const MatJob*)jobs, njobs, to_matrix);
+}
+void launch_tri_pack(const PackMat* mats, const void* jobs, int njobs, float* packed, int to_full, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(tri_pack_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, packed, to_full);
 }
 void launch_gj_finish(const InvMat* mats, const void* jobs, int njobs, hipStream_t s) {
   if (njobs <= 0) return;

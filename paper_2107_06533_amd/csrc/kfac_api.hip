@@ -100,6 +100,15 @@ struct PrecondPlan {
   kfac_plan_stats stats{};
 };
 
+struct PackPlan {
+  bool valid = false;
+  std::vector<int32_t> dims;
+  std::vector<uint64_t> off;         // float offset of every matrix's triangle
+  void* d_jobs = nullptr;
+  int njobs = 0;
+  DynTable tab;                      // [PackMat x n]
+};
+
 }  // namespace
 
 constexpr int MAX_INV_GROUPS = 4;
@@ -126,6 +135,7 @@ struct kfac_ctx {
   FactorPlan fp;
   InvertPlan ip;
   PrecondPlan pp;
+  PackPlan kp;
 };
 
 namespace {
@@ -394,6 +404,10 @@ void release(InvertPlan& p) {
     for (hipEvent_t e : g.ev_rest) if (e) (void)hipEventDestroy(e);
   }
   p = InvertPlan{};
+}
+void release(PackPlan& p) {
+  free_dev(p.d_jobs); free_table(p.tab);
+  p = PackPlan{};
 }
 void release(PrecondPlan& p) {
   free_dev(p.d_jobs1); free_dev(p.d_jobs2); free_table(p.tab);
@@ -802,7 +816,7 @@ void kfac_destroy(kfac_ctx* ctx) {
   if (!ctx->host_only) {
     DeviceGuard g(ctx);
     (void)hipDeviceSynchronize();
-    release(ctx->fp); release(ctx->ip); release(ctx->pp);
+    release(ctx->fp); release(ctx->ip); release(ctx->pp); release(ctx->kp);
     free_dev(ctx->ws);
     for (const TimingRec& r : ctx->timing) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (int g = 0; g < MAX_INV_GROUPS; ++g) {
@@ -1300,6 +1314,85 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
+}
+
+// ----------------------------------------------------------------------------- packed triangles
+size_t kfac_packed_elems(int n, const int32_t* dims, int64_t* offsets) {
+  if (n <= 0 || !dims) return 0;
+  size_t tot = 0;
+  for (int i = 0; i < n; ++i) {
+    if (dims[i] < 1) return 0;
+    if (offsets) offsets[i] = int64_t(tot);
+    tot += size_t(dims[i]) * (size_t(dims[i]) + 1) / 2;
+  }
+  if (offsets) offsets[n] = int64_t(tot);
+  return tot;
+}
+
+namespace {
+kfac_status pack_call(kfac_ctx* ctx, const char* who, int n, const int32_t* dims, const float* const* M,
+                      const float* packed, int to_full, void* hip_stream) {
+  const std::string name(who);
+  if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, name + ": ctx is NULL");
+  if (n < 0) return fail(ctx, KFAC_ERR_INVALID_ARG, name + ": n_mats < 0");
+  if (n == 0) return KFAC_OK;
+  if (!dims || !M || !packed) return fail(ctx, KFAC_ERR_INVALID_ARG, name + ": dims, M or packed is NULL");
+  for (int i = 0; i < n; ++i) {
+    if (dims[i] < 1 || dims[i] > 46340)   // element offsets inside one matrix stay below 2^31
+      return fail(ctx, KFAC_ERR_INVALID_ARG, name + ": dims[" + std::to_string(i) + "] out of range");
+    if (!M[i]) return fail(ctx, KFAC_ERR_INVALID_ARG, name + ": NULL matrix pointer at " + std::to_string(i));
+  }
+  PackPlan& P = ctx->kp;
+  const bool same = P.valid && int(P.dims.size()) == n && std::memcmp(P.dims.data(), dims, sizeof(int32_t) * n) == 0;
+  DeviceGuard guard(ctx);
+  if (!same) {
+    if (!ctx->host_only) {
+      HIP_TRY(ctx, hipDeviceSynchronize());
+      release(P);
+    } else {
+      P = PackPlan{};
+    }
+    P.dims.assign(dims, dims + n);
+    P.off.resize(n);
+    std::vector<MatJobH> jobs;
+    uint64_t tot = 0;
+    for (int i = 0; i < n; ++i) {
+      P.off[i] = tot;
+      tot += uint64_t(dims[i]) * (uint64_t(dims[i]) + 1) / 2;
+      const int T = ceil_div(dims[i], 64);   // 64 x 64 tiles of the upper triangle
+      for (int bi = 0; bi < T; ++bi)
+        for (int bj = bi; bj < T; ++bj) jobs.push_back({i, bi, bj, 0});
+    }
+    P.njobs = int(jobs.size());
+    if (!ctx->host_only) {
+      kfac_status st = upload_static(ctx, &P.d_jobs, jobs.data(), jobs.size() * sizeof(MatJobH));
+      if (st != KFAC_OK) return st;
+    }
+    P.valid = true;
+  }
+  if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  std::vector<PackMat> mats(n);
+  for (int i = 0; i < n; ++i) mats[i] = PackMat{const_cast<float*>(M[i]), P.off[i], dims[i], 0};
+  kfac_status st = sync_table(ctx, P.tab, mats.data(), mats.size() * sizeof(PackMat), s);
+  if (st != KFAC_OK) return st;
+  {
+    ScopedTiming tm(ctx, KFAC_K_TRI_PACK, s);
+    launch_tri_pack(static_cast<const PackMat*>(P.tab.dev), P.d_jobs, P.njobs, const_cast<float*>(packed), to_full, s);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  return KFAC_OK;
+}
+}  // namespace
+
+kfac_status kfac_pack_triangles(kfac_ctx* ctx, int n, const int32_t* dims, const float* const* M, float* packed,
+                                void* hip_stream) {
+  return pack_call(ctx, "kfac_pack_triangles", n, dims, M, packed, 0, hip_stream);
+}
+
+kfac_status kfac_unpack_triangles(kfac_ctx* ctx, int n, const int32_t* dims, const float* packed, float* const* M,
+                                  void* hip_stream) {
+  return pack_call(ctx, "kfac_unpack_triangles", n, dims, M, packed, 1, hip_stream);
 }
 
 kfac_status kfac_check_info(kfac_ctx* ctx, int n, const int32_t* info_dev, int32_t* info_host, void* hip_stream) {

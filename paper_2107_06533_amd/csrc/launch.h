@@ -14,6 +14,7 @@ void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, 
 void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s);
 void launch_gj_qmirror(const InvMat* mats, const void* jobs, int njobs, hipStream_t s);
 void launch_gj_move(const PanelMove* moves, const void* jobs, int njobs, int kchunks, int to_matrix, hipStream_t s);
+void launch_tri_pack(const PackMat* mats, const void* jobs, int njobs, float* packed, int to_full, hipStream_t s);
 void launch_gj_finish(const InvMat* mats, const void* jobs, int njobs, hipStream_t s);
 
 }  // namespace kfac

@@ -104,3 +104,19 @@ def test_r50_schedule(hctx):
     assert hctx.kfac_precondition([l.dG for l in ls], [l.dA for l in ls], [1] * n, [2] * n, [3] * n, [4] * n, check=False) == pk.KFAC_ERR_DEVICE
     st = hctx.plan_stats(2)
     assert alg["precondition"] <= st["mfma_flops"] <= 1.1 * alg["precondition"]
+
+
+def test_packed_triangles_host_side(hctx):
+    tot, off = hctx.packed_elems([64, 4608, 3])
+    assert off == [0, 2080, 2080 + 10619136, 2080 + 10619136 + 6] and tot == off[-1]     # Sec. IV-A sizes
+    assert hctx.packed_elems([])[0] == 0 and hctx.packed_elems([4, 0])[0] == 0
+    ok = pk.KFAC_ERR_DEVICE            # validated and planned, then refused by the host-only context
+    assert hctx.kfac_pack_triangles([5, 130], [1, 2], 3, check=False) == ok
+    assert hctx.kfac_unpack_triangles([5, 130], 3, [1, 2], check=False) == ok
+    bad = pk.KFAC_ERR_INVALID_ARG
+    assert hctx.kfac_pack_triangles([5, 0], [1, 2], 3, check=False) == bad
+    assert hctx.kfac_pack_triangles([5, 46341], [1, 2], 3, check=False) == bad
+    assert hctx.kfac_pack_triangles([5, 6], [1, None], 3, check=False) == bad
+    assert hctx.kfac_pack_triangles([5, 6], [1, 2], None, check=False) == bad
+    assert hctx.kfac_unpack_triangles([5, 6], None, [1, 2], check=False) == bad
+    assert hctx.kfac_pack_triangles([], None, None) == 0

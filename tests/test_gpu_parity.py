@@ -287,3 +287,49 @@ def test_empty_calls_are_noops(ctx):
     assert ctx.kfac_update_factors([], None, None, None, None, 0.95) == 0
     assert ctx.kfac_invert_batch([], None, None, 0.03) == 0
     assert ctx.kfac_precondition([], [], None, None, None, None) == 0
+
+
+# ------------------------------------------------------------------------------ packed triangles
+def test_pack_and_unpack_triangles_bit_exact(ctx):
+    """Data movement: every packed element and every unpacked element must equal the oracle's bit for bit."""
+    import torch
+    dims = [1, 2, 31, 32, 33, 64, 100, 257, 1000]
+    rng = np.random.default_rng(11)
+    Ms = [rng.standard_normal((d, d)).astype(np.float32) for d in dims]       # not symmetric: only the upper triangle may be read
+    tot, off = ctx.packed_elems(dims)
+    assert tot == sum(oracle.packed_size(d) for d in dims)
+    M_d = [dev(M) for M in Ms]
+    packed = torch.full((tot,), float("nan"), device="cuda")
+    ctx.kfac_pack_triangles(dims, M_d, packed)
+    torch.cuda.synchronize()
+    got = packed.cpu().numpy()
+    for d, M, o in zip(dims, Ms, off):
+        assert np.array_equal(got[o:o + oracle.packed_size(d)], oracle.pack_upper(M)), f"pack d={d}"
+    for M, Md in zip(Ms, M_d):
+        assert np.array_equal(Md.cpu().numpy(), M)                             # inputs untouched
+    out_d = [torch.full((d, d), float("nan"), device="cuda") for d in dims]
+    ctx.kfac_unpack_triangles(dims, packed, out_d)
+    torch.cuda.synchronize()
+    for d, M, X in zip(dims, Ms, out_d):
+        assert np.array_equal(X.cpu().numpy(), oracle.unpack_upper(oracle.pack_upper(M), d)), f"unpack d={d}"
+
+
+def test_packed_round_trip_of_a_whole_factor_set(ctx):
+    """The ResNet-50 set's 108 factors: pack, unpack, compare with the mirrored upper triangles."""
+    import torch
+    layers = shapes.config_layers("r50")
+    dims = [l.dA for l in layers] + [l.dG for l in layers]
+    tot, off = ctx.packed_elems(dims)
+    assert tot == sum(d * (d + 1) // 2 for d in dims)
+    g = torch.Generator(device="cuda").manual_seed(1)
+    M_d = [torch.randn((d, d), device="cuda", generator=g) for d in dims]
+    packed = torch.empty((tot,), device="cuda")
+    out_d = [torch.empty_like(M) for M in M_d]
+    ctx.kfac_pack_triangles(dims, M_d, packed)
+    ctx.kfac_unpack_triangles(dims, packed, out_d)
+    torch.cuda.synchronize()
+    for d, M, X, o in zip(dims, M_d, out_d, off):
+        U = torch.triu(M)
+        assert torch.equal(X, U + torch.triu(M, 1).T), f"d={d}"
+        iu = torch.triu_indices(d, d, device="cuda")
+        assert torch.equal(packed[o:o + d * (d + 1) // 2], M[iu[0], iu[1]]), f"d={d}"
