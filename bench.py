@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--config", default="r50", choices=list(WORKLOAD_NAMES))
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--no-breakdown", action="store_true", help="skip the extra per-kernel timing pass")
+    ap.add_argument("--stale-inverses", action="store_true",
+                    help="also time the variant that preconditions with the previous step's inverses on a second "
+                         "stream while the new ones are computed (reported as an extra field, never as `value`)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy (reference dispatch for scaling rocprofv3 byte counters)")
     return ap.parse_args()
@@ -219,6 +222,31 @@ def main():
         step()          # the unpack above overwrote the inverses: restore a consistent state
         torch.cuda.synchronize()
 
+    # ---- stale-inverse variant: precondition with the last inverses while the new ones are computed
+    stale = None
+    if args.stale_inverses:
+        XA2 = [torch.empty_like(t) for t in XA_d]
+        XG2 = [torch.empty_like(t) for t in XG_d]
+        s_inv, s_pre = torch.cuda.Stream(), torch.cuda.Stream()
+        cur, nxt = (XA_d, XG_d), (XA2, XG2)
+        def stale_step():
+            nonlocal cur, nxt
+            ctx.kfac_update_factors(layers, a_d, g_d, A_d, G_d, hp["xi"], stream=stream)
+            s_inv.wait_stream(stream); s_pre.wait_stream(stream)
+            ctx.kfac_invert_batch(dims, A_d + G_d, nxt[0] + nxt[1], hp["gamma"], info, stream=s_inv)
+            ctx.kfac_precondition(dG, dA, cur[1], cur[0], v_d, P_d, stream=s_pre)
+            stream.wait_stream(s_inv); stream.wait_stream(s_pre)
+            cur, nxt = nxt, cur
+        for _ in range(3):
+            stale_step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            stale_step()
+        torch.cuda.synchronize()
+        stale = {"ms_per_step": round((time.perf_counter() - t1) * 1e3 / args.steps, 4),
+                 "note": "update_factors, then invert_batch (new inverses) and precondition (previous inverses) on two streams"}
+
     factor_flops = fl["factor_a"] + fl["factor_g"]
     dom_avg_ms = dom_ms / dom_n
     achieved = factor_flops / (dom_avg_ms * 1e-3) / 1e12
@@ -273,6 +301,8 @@ def main():
         out["kernel_breakdown"] = breakdown
     if packed_io is not None:
         out["packed_io"] = packed_io
+    if stale is not None:
+        out["stale_inverses"] = stale
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(layers, hp, args.cpu_budget, fl["total"])
     ctx.close()

@@ -124,8 +124,10 @@ struct kfac_ctx {
   int device = -1;
   bool host_only = true;
   std::string err;
-  void* ws = nullptr;
-  size_t ws_cap = 0;
+  // one workspace per call kind (factors, inverse, preconditioning), so calls of different kinds
+  // may run at the same time on different streams
+  void* ws[3] = {nullptr, nullptr, nullptr};
+  size_t ws_cap[3] = {0, 0, 0};
   int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
   int inv_groups = 2;                     // matrix groups swept concurrently
   int inv_agg = 4;                        // pivot blocks per aggregated (rank agg*128) update
@@ -230,17 +232,18 @@ kfac_status sync_table(kfac_ctx* ctx, DynTable& t, const void* img, size_t bytes
   return KFAC_OK;
 }
 
-kfac_status ensure_ws(kfac_ctx* ctx, size_t bytes) {
-  if (bytes <= ctx->ws_cap) return KFAC_OK;
+enum { WS_FACTORS = 0, WS_INVERT = 1, WS_PRECOND = 2 };
+kfac_status ensure_ws(kfac_ctx* ctx, int which, size_t bytes) {
+  if (bytes <= ctx->ws_cap[which]) return KFAC_OK;
   if (hipDeviceSynchronize() != hipSuccess) return fail(ctx, KFAC_ERR_DEVICE, "hipDeviceSynchronize failed");
-  free_dev(ctx->ws);
-  ctx->ws_cap = 0;
-  if (hipMalloc(&ctx->ws, bytes) != hipSuccess) {
-    ctx->ws = nullptr;
+  free_dev(ctx->ws[which]);
+  ctx->ws_cap[which] = 0;
+  if (hipMalloc(&ctx->ws[which], bytes) != hipSuccess) {
+    ctx->ws[which] = nullptr;
     (void)hipGetLastError();
     return fail(ctx, KFAC_ERR_WORKSPACE, "cannot allocate " + std::to_string(bytes) + " bytes of device workspace");
   }
-  ctx->ws_cap = bytes;
+  ctx->ws_cap[which] = bytes;
   return KFAC_OK;
 }
 
@@ -817,7 +820,7 @@ void kfac_destroy(kfac_ctx* ctx) {
     DeviceGuard g(ctx);
     (void)hipDeviceSynchronize();
     release(ctx->fp); release(ctx->ip); release(ctx->pp); release(ctx->kp);
-    free_dev(ctx->ws);
+    for (int k = 0; k < 3; ++k) free_dev(ctx->ws[k]);
     for (const TimingRec& r : ctx->timing) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (int g = 0; g < MAX_INV_GROUPS; ++g) {
       if (ctx->inv_stream[g]) (void)hipStreamDestroy(ctx->inv_stream[g]);
@@ -957,9 +960,9 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const size_t slot_floats = P.nslots * size_t(BM) * BN;
-  kfac_status st = ensure_ws(ctx, (slot_floats + P.lag_floats) * sizeof(float));
+  kfac_status st = ensure_ws(ctx, WS_FACTORS, (slot_floats + P.lag_floats) * sizeof(float));
   if (st != KFAC_OK) return st;
-  float* lag_ws = static_cast<float*>(ctx->ws) + slot_floats;
+  float* lag_ws = static_cast<float*>(ctx->ws[WS_FACTORS]) + slot_floats;
   std::vector<uint8_t> is_lag(n, 0);
   for (const LagLayer& lg : P.lags) is_lag[lg.layer] = 1;
   for (int l = 0; l < n; ++l)
@@ -970,7 +973,7 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
       D.a.ptr = which == 0 ? act[l] : gout[l];
       D.b.ptr = D.a.ptr;
       D.out = which == 0 ? A[l] : G[l];
-      D.partial = static_cast<float*>(ctx->ws);
+      D.partial = static_cast<float*>(ctx->ws[WS_FACTORS]);
       const float sc = which == 0 ? scale_a : scale_g;
       const float scale = sc > 0.f ? sc : float(1.0 / double(D.a.K));
       D.alpha = (1.f - xi) * scale;
@@ -985,7 +988,7 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
       TileDesc& D = P.descs[lg.desc0 + k];
       D.a.ptr = D.b.ptr = act[lg.layer];
       D.out = lag_ws + lg.off[k];
-      D.partial = static_cast<float*>(ctx->ws);
+      D.partial = static_cast<float*>(ctx->ws[WS_FACTORS]);
       Q.G[k] = D.out;
     }
     const double rows = double(rows_of(L));
@@ -1099,7 +1102,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  kfac_status st = ensure_ws(ctx, P.ws_floats * sizeof(float));
+  kfac_status st = ensure_ws(ctx, WS_INVERT, P.ws_floats * sizeof(float));
   if (st != KFAC_OK) return st;
   const int G = int(P.groups.size());
 
@@ -1122,7 +1125,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   std::vector<const InvMat*> d_mats(G), d_views(G);
   std::vector<const PanelMove*> d_moves(G);
   std::vector<const TileDesc*> d_descs(G);
-  float* wsf = static_cast<float*>(ctx->ws);
+  float* wsf = static_cast<float*>(ctx->ws[WS_INVERT]);
   const int agg = ctx->inv_agg, aw = agg + 1;
   for (int g = 0; g < G; ++g) {
     InvertGroup& Gp = P.groups[g];
@@ -1455,10 +1458,10 @@ kfac_status kfac_precondition(kfac_ctx* ctx, int n, const int32_t* dG, const int
   if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  kfac_status st = ensure_ws(ctx, P.ws_floats * sizeof(float));
+  kfac_status st = ensure_ws(ctx, WS_PRECOND, P.ws_floats * sizeof(float));
   if (st != KFAC_OK) return st;
   std::vector<TileDesc> descs(2 * size_t(n));
-  float* wsf = static_cast<float*>(ctx->ws);
+  float* wsf = static_cast<float*>(ctx->ws[WS_PRECOND]);
   for (int l = 0; l < n; ++l) {
     float* T = wsf + P.t_off[l];
     TileDesc& D1 = descs[2 * l];       // T = Ginv . V : a(k, i) = Ginv[i][k]

@@ -333,3 +333,47 @@ def test_packed_round_trip_of_a_whole_factor_set(ctx):
         assert torch.equal(X, U + torch.triu(M, 1).T), f"d={d}"
         iu = torch.triu_indices(d, d, device="cuda")
         assert torch.equal(packed[o:o + d * (d + 1) // 2], M[iu[0], iu[1]]), f"d={d}"
+
+
+# ------------------------------------------------------------------------------ stale inverses
+def test_precondition_with_last_inverses_while_inverting(ctx):
+    """Inverse update interval > 1 on one GPU: the new inverses are computed on one stream while the
+    gradients are preconditioned with the previous ones on another (calls of different kinds own
+    separate workspaces).  Both results must match the oracle."""
+    import torch
+    hp = shapes.config_hparams("cnn")
+    layers = shapes.config_layers("cnn")
+    n = len(layers)
+    dims = [l.dA for l in layers] + [l.dG for l in layers]
+    dG, dA = [l.dG for l in layers], [l.dA for l in layers]
+    A_ref, G_ref = [np.eye(l.dA) for l in layers], [np.eye(l.dG) for l in layers]
+    A_d = [dev(np.eye(l.dA, dtype=np.float32)) for l in layers]
+    G_d = [dev(np.eye(l.dG, dtype=np.float32)) for l in layers]
+    X_old = [torch.empty((d, d), device="cuda") for d in dims]
+    X_new = [torch.empty((d, d), device="cuda") for d in dims]
+    # step 0: ordinary step, gives the inverses that step 1 reuses
+    ins = [inputs.layer_inputs(l, hp["cid"], 0, i, hp["relu"]) for i, l in enumerate(layers)]
+    acts, gouts, grads = zip(*ins)
+    ctx.kfac_update_factors(layers, [dev(x) for x in acts], [dev(x) for x in gouts], A_d, G_d, hp["xi"])
+    ctx.kfac_invert_batch(dims, A_d + G_d, X_old, hp["gamma"])
+    torch.cuda.synchronize()
+    A_ref, G_ref, XA0, XG0, _ = oracle.kfac_step(layers, acts, gouts, grads, A_ref, G_ref, hp["xi"], hp["gamma"])
+    # step 1: new factors; invert on s1 while preconditioning with the old inverses on s2
+    ins = [inputs.layer_inputs(l, hp["cid"], 1, i, hp["relu"]) for i, l in enumerate(layers)]
+    acts, gouts, grads = zip(*ins)
+    v_d = [dev(x) for x in grads]
+    P_d = [torch.empty_like(v) for v in v_d]
+    ctx.kfac_update_factors(layers, [dev(x) for x in acts], [dev(x) for x in gouts], A_d, G_d, hp["xi"])
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx.kfac_invert_batch(dims, A_d + G_d, X_new, hp["gamma"], stream=s1)
+    ctx.kfac_precondition(dG, dA, X_old[n:], X_old[:n], v_d, P_d, stream=s2)
+    torch.cuda.synchronize()
+    A_ref, G_ref, XA1, XG1, _ = oracle.kfac_step(layers, acts, gouts, grads, A_ref, G_ref, hp["xi"], hp["gamma"])
+    for i in range(n):
+        want = oracle.precondition(XG0[i], XA0[i], grads[i])
+        e = rel_fro(host64(P_d[i]), want)
+        assert e <= TOL_PRECOND, f"layer {i}: preconditioning with the previous inverses, rel err {e:.3e}"
+        for X_t, F_ref in ((X_new[i], A_ref[i]), (X_new[n + i], G_ref[i])):
+            res = inv_residual(F_ref, hp["gamma"], host64(X_t))
+            assert res <= TOL_INVERSE, f"layer {i}: new inverse residual {res:.3e}"
