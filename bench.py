@@ -27,6 +27,7 @@ WORKLOAD_NAMES = {
     "r50": "r50: ResNet-50-shaped layer set, batch 32, 224x224 input (54 layers, 108 factor matrices)",
     "r152": "r152: ResNet-152-shaped layer set, batch 32, 224x224 input (156 layers, 312 factor matrices)",
     "bertl": "bertl: BERT-large linear layers, 24 blocks, 4096 tokens (144 layers, 288 factor matrices)",
+    "d201": "d201: DenseNet-201-shaped layer set, batch 16, 224x224 input (201 layers, 402 factor matrices)",
 }
 
 

@@ -106,6 +106,29 @@ def resnet_layers(blocks, batch=32, image=224, classes=1000, conv_bias=1) -> Lis
     return ls
 
 
+def densenet_layers(blocks=(6, 12, 48, 32), growth=32, bn_size=4, batch=16, image=224, classes=1000,
+                    conv_bias=1) -> List[Layer]:
+    """DenseNet (DenseNet-201 by default): 7x7/2 stem to 2*growth channels, 3x3/2 max-pool, dense
+    blocks whose layers are a 1x1 bottleneck to bn_size*growth channels followed by a 3x3 to `growth`
+    channels (input = concatenation of everything before), halving 1x1 transitions with 2x2 average
+    pooling between blocks, linear classifier."""
+    ls = [conv(batch, 3, image, image, 2 * growth, 7, 2, 3, conv_bias, name="stem")]
+    res = (image + 2 * 3 - 7) // 2 + 1
+    res = (res + 2 * 1 - 3) // 2 + 1
+    c = 2 * growth
+    for b, nl in enumerate(blocks):
+        for i in range(nl):
+            ls.append(conv(batch, c, res, res, bn_size * growth, 1, 1, 0, conv_bias, name=f"d{b + 1}l{i}.conv1"))
+            ls.append(conv(batch, bn_size * growth, res, res, growth, 3, 1, 1, conv_bias, name=f"d{b + 1}l{i}.conv2"))
+            c += growth
+        if b + 1 < len(blocks):
+            ls.append(conv(batch, c, res, res, c // 2, 1, 1, 0, conv_bias, name=f"t{b + 1}"))
+            c //= 2
+            res //= 2
+    ls.append(linear(batch, c, classes, 1, name="fc"))
+    return ls
+
+
 def bert_large_layers(blocks=24, hidden=1024, ffn=4096, tokens=32 * 128) -> List[Layer]:
     ls = []
     for b in range(blocks):
@@ -123,6 +146,7 @@ CONFIGS = {
     "r50":   dict(cid=3, xi=0.95, gamma=0.03, relu=True),
     "r152":  dict(cid=4, xi=0.95, gamma=0.03, relu=True),
     "bertl": dict(cid=5, xi=0.95, gamma=0.01, relu=False),
+    "d201":  dict(cid=6, xi=0.95, gamma=0.03, relu=True),
 }
 
 
@@ -137,6 +161,8 @@ def config_layers(name: str, batch: int | None = None) -> List[Layer]:
         return resnet_layers((3, 8, 36, 3), batch or 32)
     if name == "bertl":
         return bert_large_layers()
+    if name == "d201":
+        return densenet_layers(batch=batch or 16)
     raise KeyError(name)
 
 

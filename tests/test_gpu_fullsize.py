@@ -115,14 +115,19 @@ def test_r50_every_layer_against_oracle(ctx):
     print(f"r50: oracle over {len(layers)} layers {time.perf_counter() - t0:.1f} s, worst {worst}", flush=True)
 
 
-def sampled_layers(layers):
+def sampled_layers(layers, cap=28):
+    """First layer of every distinct shape class plus the last layer; when there are more classes
+    than `cap` (DenseNet: every dense layer has its own input width), an even subsample of them."""
     first = {}
     for i, l in enumerate(layers):
         first.setdefault((l.kind, l.dA, l.dG, l.R, l.kh, l.stride), i)
-    return sorted(set(first.values()) | {len(layers) - 1})
+    idx = sorted(first.values())
+    if len(idx) > cap:
+        idx = [idx[round(k * (len(idx) - 1) / (cap - 1))] for k in range(cap)]
+    return sorted(set(idx) | {len(layers) - 1})
 
 
-@pytest.mark.parametrize("name", ["r152", "bertl"])
+@pytest.mark.parametrize("name", ["r152", "bertl", "d201"])
 def test_large_sets_sampled_against_oracle(ctx, name):
     t0 = time.perf_counter()
     hp, layers, ins, out = gpu_step(ctx, name)

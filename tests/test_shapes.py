@@ -34,6 +34,19 @@ def test_resnet_matches_paper_table(model, blocks):
         assert min(sizes) == lo and max(sizes) == hi
 
 
+def test_densenet201_matches_paper_table():
+    L, As, Gs, _, _ = _gold()["densenet201"]
+    ls = shapes.densenet_layers(conv_bias=0)
+    assert len(ls) == L
+    tri = lambda d: d * (d + 1) // 2
+    assert abs(sum(tri(l.c_in * l.kh * l.kw) for l in ls) / 1e6 - As) < 0.06
+    assert abs(sum(tri(l.dG) for l in ls) / 1e6 - Gs) < 0.06
+    cfg = shapes.config_layers("d201")
+    assert len(cfg) == 201 and cfg[0].n == 16                       # the paper's per-GPU batch for this model
+    assert cfg[-1].dA == 1921 and max(l.dA for l in cfg) == 1921
+    assert sum(l.kind == 1 and l.kh == 3 and l.dA == 1153 for l in cfg) == 98
+
+
 def test_r50_config_dims():
     ls = shapes.config_layers("r50")
     assert len(ls) == 54
