@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--stale-inverses", action="store_true",
                     help="also time the variant that preconditions with the previous step's inverses on a second "
                          "stream while the new ones are computed (reported as an extra field, never as `value`)")
+    ap.add_argument("--fit-inverse-model", action="store_true",
+                    help="instead of the step benchmark: time kfac_invert_batch on single matrices d = 64 .. 8192 "
+                         "(10 warm-up + 100 runs each) and fit t = alpha_inv * exp(beta_inv * d)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy (reference dispatch for scaling rocprofv3 byte counters)")
     return ap.parse_args()
@@ -91,6 +94,34 @@ def cpu_baseline(layers, hp, budget_s, flops_total):
     }
 
 
+def fit_inverse_model(pk, torch, np):
+    """The paper's computation model of the inverse (Eq. inverting-model) fitted to this GPU with the
+    paper's protocol: matrices of dimension 64 .. 8192, 10 warm-up and 100 timed runs each."""
+    ctx = pk.Context(0)
+    pts = []
+    for d in (64, 128, 256, 512, 1024, 2048, 4096, 8192):
+        B = torch.randn((d, 64), device="cuda")
+        F = 0.05 * (B @ B.T) / 64.0
+        F.diagonal().add_(0.95)
+        X = torch.empty_like(F)
+        for _ in range(10):
+            ctx.kfac_invert_batch([d], [F], [X], 0.03)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(100):
+            ctx.kfac_invert_batch([d], [F], [X], 0.03)
+        e1.record()
+        torch.cuda.synchronize()
+        pts.append((d, e0.elapsed_time(e1) / 100.0 * 1e-3))
+    ds = np.array([p[0] for p in pts], dtype=np.float64)
+    ts = np.array([p[1] for p in pts], dtype=np.float64)
+    beta, lna = np.polyfit(ds, np.log(ts), 1)
+    ctx.close()
+    print(json.dumps({"fit": "t_comp(d) = alpha_inv * exp(beta_inv * d), seconds", "alpha_inv": float(np.exp(lna)),
+                      "beta_inv": float(beta), "points_d_seconds": [[int(d), round(t, 7)] for d, t in pts],
+                      "max_rel_misfit": float(np.max(np.abs(np.exp(lna + beta * ds) / ts - 1.0)))}))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -106,6 +137,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     pk.load()                                      # fails loudly when the HIP library is missing
     torch.cuda.set_device(0)
+    if args.fit_inverse_model:
+        fit_inverse_model(pk, torch, np)
+        return
     hp = shapes.config_hparams(args.config)
     layers = shapes.config_layers(args.config)
     n = len(layers)

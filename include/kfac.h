@@ -165,6 +165,30 @@ kfac_status kfac_pack_triangles(kfac_ctx* ctx, int n_mats, const int32_t* dims, 
 kfac_status kfac_unpack_triangles(kfac_ctx* ctx, int n_mats, const int32_t* dims, const float* packed,
                                   float* const* M, void* hip_stream);
 
+/*
+ * Load-balancing placement of the inversions on several workers (Sec. IV-B, Algorithm 1) with
+ * the paper's two cost models; pure host, no context needed.
+ *     t_comp(d) = alpha_inv * exp(beta_inv * d)              (Eq. inverting-model)
+ *     t_comm(d) = alpha_bcast + beta_bcast * d (d + 1) / 2   (Eq. broadcast-model)
+ * Tensors are visited in descending dimension (ties in input order).  One whose inverse is cheaper
+ * to compute than to receive (t_comp < t_comm) is computed by every worker and not communicated:
+ * owner[i] = -1, and every worker's bucket grows.  Otherwise it goes to the worker with the smallest
+ * bucket (lowest index on ties): owner[i] = that worker.  A bucket grows by d ** weight_power
+ * (1: as the algorithm is printed; 2: as the text describes the balance; 3: proportional to the
+ * arithmetic of the inverse).
+ * overall_time (may be NULL) receives the objective of the problem statement: the maximum over
+ * workers of the summed t_comp of its tensors plus the summed t_comm of those it has to send.
+ * Returns INVALID_ARG for NULL dims/model/owner, n_mats < 0, n_workers < 1, d < 1,
+ * weight_power outside 1..3, negative or non-finite coefficients.  n_mats == 0 is a no-op.
+ */
+typedef struct {
+  double alpha_inv, beta_inv;
+  double alpha_bcast, beta_bcast;
+  int32_t weight_power;
+} kfac_cost_model;
+kfac_status kfac_place_inversions(int n_mats, const int32_t* dims, int n_workers, const kfac_cost_model* model,
+                                  int32_t* owner, double* overall_time);
+
 /* Schedule statistics of the most recent call of each kind on this context (pure host;
  * for tests and benchmarks).  Fields that do not apply are 0. */
 typedef struct {

@@ -15,7 +15,7 @@ EXPORTS = [
     "kfac_layer_dA", "kfac_layer_dG", "kfac_layer_rows",
     "kfac_workspace_bytes_factors", "kfac_workspace_bytes_invert", "kfac_workspace_bytes_precondition",
     "kfac_update_factors", "kfac_invert_batch", "kfac_check_info", "kfac_precondition",
-    "kfac_packed_elems", "kfac_pack_triangles", "kfac_unpack_triangles",
+    "kfac_packed_elems", "kfac_pack_triangles", "kfac_unpack_triangles", "kfac_place_inversions",
     "kfac_get_plan_stats", "kfac_timing_enable", "kfac_timing_read",
 ]
 
@@ -35,6 +35,11 @@ class KfacError(RuntimeError):
 class layer_struct(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("kind", "n", "c_in", "h", "w", "c_out", "kh", "kw", "stride", "pad", "rows", "has_bias")]
+
+
+class cost_model(C.Structure):
+    _fields_ = [("alpha_inv", C.c_double), ("beta_inv", C.c_double), ("alpha_bcast", C.c_double),
+                ("beta_bcast", C.c_double), ("weight_power", C.c_int32)]
 
 
 class plan_stats(C.Structure):
@@ -93,6 +98,8 @@ def load():
     lib.kfac_pack_triangles.restype = C.c_int
     lib.kfac_unpack_triangles.argtypes = [vp, C.c_int, i32p, vp, fpp, vp]
     lib.kfac_unpack_triangles.restype = C.c_int
+    lib.kfac_place_inversions.argtypes = [C.c_int, i32p, C.c_int, C.POINTER(cost_model), i32p, C.POINTER(C.c_double)]
+    lib.kfac_place_inversions.restype = C.c_int
     lib.kfac_get_plan_stats.argtypes = [vp, C.c_int, C.POINTER(plan_stats)]
     lib.kfac_get_plan_stats.restype = None
     lib.kfac_timing_enable.argtypes = [vp, C.c_uint32]
@@ -140,6 +147,19 @@ def _stream_handle(stream) -> Optional[int]:
     if isinstance(stream, int):
         return stream or None
     return int(stream.cuda_stream) or None
+
+
+def place_inversions(dims, n_workers, alpha_inv, beta_inv, alpha_bcast, beta_bcast, weight_power=1, check=True):
+    """(status, owner list, overall time) of kfac_place_inversions (pure host, no context)."""
+    lib = load()
+    n = len(dims)
+    m = cost_model(alpha_inv, beta_inv, alpha_bcast, beta_bcast, weight_power)
+    owner = (C.c_int32 * max(n, 1))()
+    t = C.c_double()
+    st = lib.kfac_place_inversions(n, _i32_array(dims) if n else None, n_workers, C.byref(m), owner, C.byref(t))
+    if check and st != 0:
+        raise KfacError(st, lib.kfac_last_error(None).decode())
+    return st, [int(owner[i]) for i in range(n)], t.value
 
 
 class Context:

@@ -1319,6 +1319,46 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   return KFAC_OK;
 }
 
+// ----------------------------------------------------------------------------- placement
+kfac_status kfac_place_inversions(int n, const int32_t* dims, int n_workers, const kfac_cost_model* model,
+                                  int32_t* owner, double* overall_time) {
+  if (n < 0) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_place_inversions: n_mats < 0");
+  if (n_workers < 1) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_place_inversions: n_workers < 1");
+  if (!model) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_place_inversions: model is NULL");
+  const double coef[4] = {model->alpha_inv, model->beta_inv, model->alpha_bcast, model->beta_bcast};
+  for (double c : coef)
+    if (!(c >= 0.0) || std::isinf(c)) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_place_inversions: coefficients must be finite and >= 0");
+  if (model->weight_power < 1 || model->weight_power > 3)
+    return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_place_inversions: weight_power must be 1, 2 or 3");
+  if (n == 0) {
+    if (overall_time) *overall_time = 0.0;
+    return KFAC_OK;
+  }
+  if (!dims || !owner) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_place_inversions: dims or owner is NULL");
+  for (int i = 0; i < n; ++i)
+    if (dims[i] < 1) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_place_inversions: dims[" + std::to_string(i) + "] < 1");
+  auto comp = [&](int d) { return model->alpha_inv * std::exp(model->beta_inv * double(d)); };
+  auto comm = [&](int d) { return model->alpha_bcast + model->beta_bcast * (double(d) * (double(d) + 1.0) / 2.0); };
+  std::vector<int> order(n);
+  for (int i = 0; i < n; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return dims[a] > dims[b]; });
+  std::vector<double> bucket(n_workers, 0.0), busy(n_workers, 0.0);
+  for (int i : order) {
+    const double w = std::pow(double(dims[i]), double(model->weight_power));
+    if (comp(dims[i]) < comm(dims[i])) {
+      owner[i] = -1;
+      for (int p = 0; p < n_workers; ++p) { bucket[p] += w; busy[p] += comp(dims[i]); }
+    } else {
+      const int p = int(std::min_element(bucket.begin(), bucket.end()) - bucket.begin());
+      owner[i] = p;
+      bucket[p] += w;
+      busy[p] += comp(dims[i]) + comm(dims[i]);
+    }
+  }
+  if (overall_time) *overall_time = *std::max_element(busy.begin(), busy.end());
+  return KFAC_OK;
+}
+
 // ----------------------------------------------------------------------------- packed triangles
 size_t kfac_packed_elems(int n, const int32_t* dims, int64_t* offsets) {
   if (n <= 0 || !dims) return 0;

@@ -120,3 +120,28 @@ def test_packed_triangles_host_side(hctx):
     assert hctx.kfac_pack_triangles([5, 6], [1, 2], None, check=False) == bad
     assert hctx.kfac_unpack_triangles([5, 6], None, [1, 2], check=False) == bad
     assert hctx.kfac_pack_triangles([], None, None) == 0
+
+
+def test_place_inversions_matches_the_oracle():
+    """Host logic of the library against the oracle's Algorithm 1 on the ResNet-50 dimensions and on
+    random instances, for the three bucket weights; plus argument validation."""
+    import numpy as np
+    from oracle import placement as pl
+    ls = shapes.config_layers("r50")
+    rng = np.random.default_rng(5)
+    cases = [([l.dA for l in ls] + [l.dG for l in ls], 8), ([l.dA for l in ls] + [l.dG for l in ls], 64)]
+    cases += [([int(d) for d in rng.integers(1, 6000, int(rng.integers(1, 60)))], int(rng.integers(1, 17))) for _ in range(20)]
+    ai, bi, ab, bb = 2.0e-4, 9.0e-4, 1.5e-3, 2.0e-9            # seconds; orders of magnitude of the paper's fits
+    for dims, P in cases:
+        for wp in (1, 2, 3):
+            st, owner, t = pk.place_inversions(dims, P, ai, bi, ab, bb, wp)
+            want = pl.lbp(dims, P, lambda d: pl.t_comp(d, ai, bi), lambda d: pl.t_comm(d, ab, bb), wp)
+            assert owner == want
+            t_want = pl.overall_time(want, dims, P, lambda d: pl.t_comp(d, ai, bi), lambda d: pl.t_comm(d, ab, bb))
+            assert abs(t - t_want) <= 1e-12 * max(1.0, t_want)
+    bad = pk.KFAC_ERR_INVALID_ARG
+    assert pk.place_inversions([4, 0], 2, ai, bi, ab, bb, check=False)[0] == bad
+    assert pk.place_inversions([4, 5], 0, ai, bi, ab, bb, check=False)[0] == bad
+    assert pk.place_inversions([4, 5], 2, -1.0, bi, ab, bb, check=False)[0] == bad
+    assert pk.place_inversions([4, 5], 2, ai, bi, ab, bb, 4, check=False)[0] == bad
+    assert pk.place_inversions([], 2, ai, bi, ab, bb)[0] == 0
