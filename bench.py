@@ -28,6 +28,7 @@ WORKLOAD_NAMES = {
     "r152": "r152: ResNet-152-shaped layer set, batch 32, 224x224 input (156 layers, 312 factor matrices)",
     "bertl": "bertl: BERT-large linear layers, 24 blocks, 4096 tokens (144 layers, 288 factor matrices)",
     "d201": "d201: DenseNet-201-shaped layer set, batch 16, 224x224 input (201 layers, 402 factor matrices)",
+    "iv4": "iv4: Inception-v4-shaped layer set, batch 16, 224x224 input (150 layers, 300 factor matrices)",
 }
 
 

@@ -63,7 +63,8 @@ typedef struct kfac_ctx kfac_ctx; /* opaque: workspace + cached schedules only *
 typedef struct {
   int32_t kind;     /* 0 linear : act [rows, c_in],   gout [rows, c_out]   row-major
                        1 conv2d : act [n, c_in, h, w], gout [n, c_out, oh, ow] NCHW, dilation 1, groups 1 */
-  int32_t n, c_in, h, w, c_out, kh, kw, stride, pad; /* n,h,w,kh,kw,stride,pad: conv only */
+  int32_t n, c_in, h, w, c_out, kh, kw, stride, pad_h, pad_w; /* n,h,w,kh,kw,stride,pad_*: conv only;
+                       zero padding of the height / of the width (they differ for 1x7-style windows) */
   int32_t rows;     /* linear only; a convolution has rows = n*oh*ow */
   int32_t has_bias; /* 1: a ones column is appended LAST to the activations,
                           dA = c_in*kh*kw + has_bias                           */

@@ -53,7 +53,7 @@ def im2col_rows(layer, act) -> np.ndarray:
     Linear layer: a-bar = [a, 1] (ones column last when has_bias).
     Convolution (square or rectangular kernel, zero padding, dilation 1, groups 1):
     row r = (n*OH + oy)*OW + ox is the receptive field of output pixel (n, oy, ox);
-    column q = (c*kh + i)*kw + j holds a[n, c, oy*stride - pad + i, ox*stride - pad + j]
+    column q = (c*kh + i)*kw + j holds a[n, c, oy*stride - pad_h + i, ox*stride - pad_w + j]
     (0 outside the image), so columns are ordered like a weight tensor
     [C_out, C_in, kh, kw] flattened to [C_out, C_in*kh*kw]; ones column last.
     """
@@ -64,10 +64,11 @@ def im2col_rows(layer, act) -> np.ndarray:
     else:
         n, c, h, w = layer.n, layer.c_in, layer.h, layer.w
         assert a.shape == (n, c, h, w)
-        kh, kw, s, p = layer.kh, layer.kw, layer.stride, layer.pad
+        kh, kw, s = layer.kh, layer.kw, layer.stride
+        ph, pw = layer.ph, layer.pw                 # zero padding of the height / of the width
         oh, ow = layer.oh, layer.ow
-        ap = np.zeros((n, c, h + 2 * p, w + 2 * p), dtype=np.float64)
-        ap[:, :, p:p + h, p:p + w] = a
+        ap = np.zeros((n, c, h + 2 * ph, w + 2 * pw), dtype=np.float64)
+        ap[:, :, ph:ph + h, pw:pw + w] = a
         patches = np.empty((n, oh, ow, c, kh, kw), dtype=np.float64)
         for i in range(kh):
             for j in range(kw):

@@ -34,7 +34,7 @@ class KfacError(RuntimeError):
 
 class layer_struct(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ("kind", "n", "c_in", "h", "w", "c_out", "kh", "kw", "stride", "pad", "rows", "has_bias")]
+                ("kind", "n", "c_in", "h", "w", "c_out", "kh", "kw", "stride", "pad_h", "pad_w", "rows", "has_bias")]
 
 
 class cost_model(C.Structure):
@@ -112,8 +112,18 @@ def load():
 
 def make_layer(l) -> layer_struct:
     """From any object with the fields of synth.shapes.Layer (or a dict)."""
-    g = (lambda k: l[k]) if isinstance(l, dict) else (lambda k: getattr(l, k))
-    return layer_struct(*[int(g(n)) for n, _ in layer_struct._fields_])
+    has = (lambda k: k in l) if isinstance(l, dict) else (lambda k: hasattr(l, k))
+    get = (lambda k: l[k]) if isinstance(l, dict) else (lambda k: getattr(l, k))
+
+    def field(name):
+        # objects that carry one `pad` (and optionally `pad_w`, negative = same) are accepted too
+        if name == "pad_h" and not has("pad_h"):
+            return get("pad")
+        if name == "pad_w" and (not has("pad_w") or int(get("pad_w")) < 0):
+            return get("pad_h") if has("pad_h") else get("pad")
+        return get(name)
+
+    return layer_struct(*[int(field(n)) for n, _ in layer_struct._fields_])
 
 
 def _ptr(x) -> Optional[int]:

@@ -263,9 +263,9 @@ bool layer_valid(const kfac_layer& L, std::string* why) {
   if (L.n < 1 || L.h < 1 || L.w < 1) return bad("conv layer needs n, h, w >= 1");
   if (L.kh < 1 || L.kw < 1 || int64_t(L.kh) * L.kw > 63) return bad("conv window must have 1..63 taps");
   if (L.stride < 1) return bad("conv stride must be >= 1");
-  if (L.pad < 0 || L.pad > 127) return bad("conv pad must be in 0..127");
-  if (L.h + 2 * L.pad < L.kh || L.w + 2 * L.pad < L.kw) return bad("conv output is empty");
-  const int64_t oh = (L.h + 2 * L.pad - L.kh) / L.stride + 1, ow = (L.w + 2 * L.pad - L.kw) / L.stride + 1;
+  if (L.pad_h < 0 || L.pad_h > 127 || L.pad_w < 0 || L.pad_w > 127) return bad("conv pads must be in 0..127");
+  if (L.h + 2 * L.pad_h < L.kh || L.w + 2 * L.pad_w < L.kw) return bad("conv output is empty");
+  const int64_t oh = (L.h + 2 * L.pad_h - L.kh) / L.stride + 1, ow = (L.w + 2 * L.pad_w - L.kw) / L.stride + 1;
   const int64_t lim = (int64_t(1) << 31) - 1;
   if (int64_t(L.n) * oh * ow > lim) return bad("conv rows n*oh*ow exceed 2^31-1");
   if (int64_t(L.c_in) * L.h * L.w > lim || int64_t(L.c_out) * oh * ow > lim) return bad("one sample exceeds 2^31-1 elements");
@@ -275,8 +275,8 @@ bool layer_valid(const kfac_layer& L, std::string* why) {
   return true;
 }
 
-int conv_oh(const kfac_layer& L) { return (L.h + 2 * L.pad - L.kh) / L.stride + 1; }
-int conv_ow(const kfac_layer& L) { return (L.w + 2 * L.pad - L.kw) / L.stride + 1; }
+int conv_oh(const kfac_layer& L) { return (L.h + 2 * L.pad_h - L.kh) / L.stride + 1; }
+int conv_ow(const kfac_layer& L) { return (L.w + 2 * L.pad_w - L.kw) / L.stride + 1; }
 int64_t rows_of(const kfac_layer& L) { return L.kind == 0 ? L.rows : int64_t(L.n) * conv_oh(L) * conv_ow(L); }
 int dA_of(const kfac_layer& L) { return (L.kind == 0 ? L.c_in : L.c_in * L.kh * L.kw) + L.has_bias; }
 
@@ -297,12 +297,12 @@ Operand act_operand(const kfac_layer& L) {
     return o;
   }
   o.bytes = uint32_t(int64_t(L.n) * L.c_in * L.h * L.w * 4);
-  if (L.kh == 1 && L.kw == 1 && L.pad == 0) o.type = (L.stride == 1 && vec_enabled() && (L.h * L.w) % 4 == 0) ? OP_CONV11V : OP_CONV11;
+  if (L.kh == 1 && L.kw == 1 && L.pad_h == 0 && L.pad_w == 0) o.type = (L.stride == 1 && vec_enabled() && (L.h * L.w) % 4 == 0) ? OP_CONV11V : OP_CONV11;
   else if (L.kh == 3 && L.kw == 3) o.type = OP_CONV33;
   else if (L.kh == 7 && L.kw == 7) o.type = OP_CONV77;
   else o.type = OP_CONVGEN;
   o.C = L.c_in; o.H = L.h; o.W = L.w; o.OH = conv_oh(L); o.OW = conv_ow(L);
-  o.stride = L.stride; o.pad_h = o.pad_w = L.pad; o.KH = L.kh; o.KW = L.kw;
+  o.stride = L.stride; o.pad_h = L.pad_h; o.pad_w = L.pad_w; o.KH = L.kh; o.KW = L.kw;
   o.dOW = make_fastdiv(uint32_t(o.OW));
   o.dOHW = make_fastdiv(uint32_t(o.OH) * uint32_t(o.OW));
   return o;
@@ -436,7 +436,7 @@ bool lag_enabled() {
   return on;
 }
 bool lag_eligible(const kfac_layer& L) {
-  return lag_enabled() && L.kind == 1 && L.kh == 3 && L.kw == 3 && L.stride == 1 && L.pad == 1 && L.c_in >= LAG_MIN_C;
+  return lag_enabled() && L.kind == 1 && L.kh == 3 && L.kw == 3 && L.stride == 1 && L.pad_h == 1 && L.pad_w == 1 && L.c_in >= LAG_MIN_C;
 }
 
 // View of the activations through a KH x KW window of lags over the pixel window [y0, y1] x [x0, x1]

@@ -29,18 +29,27 @@ class Layer:
     kh: int = 1
     kw: int = 1
     stride: int = 1
-    pad: int = 0
+    pad: int = 0       # zero padding of the height (and of the width unless pad_w is given)
+    pad_w: int = -1    # zero padding of the width; -1 = same as pad
     rows: int = 0      # linear: number of rows (batch, or batch*seq)
     has_bias: int = 1  # 1 -> a ones column is appended last to the activations
     name: str = ""
 
     @property
+    def ph(self) -> int:
+        return self.pad
+
+    @property
+    def pw(self) -> int:
+        return self.pad if self.pad_w < 0 else self.pad_w
+
+    @property
     def oh(self) -> int:
-        return (self.h + 2 * self.pad - self.kh) // self.stride + 1
+        return (self.h + 2 * self.ph - self.kh) // self.stride + 1
 
     @property
     def ow(self) -> int:
-        return (self.w + 2 * self.pad - self.kw) // self.stride + 1
+        return (self.w + 2 * self.pw - self.kw) // self.stride + 1
 
     @property
     def R(self) -> int:
@@ -129,6 +138,61 @@ def densenet_layers(blocks=(6, 12, 48, 32), growth=32, bn_size=4, batch=16, imag
     return ls
 
 
+def inception_v4_layers(batch=16, image=224, classes=1000, conv_bias=1) -> List[Layer]:
+    """Inception-v4: stem (unpadded 3x3 convolutions, one padded; a 1x7 / 7x1 pair), 4 x Inception-A,
+    Reduction-A, 7 x Inception-B, Reduction-B, 3 x Inception-C, linear classifier.  Windows such as
+    1x7 are padded along their long side only; pooling branches contribute no preconditioned layer
+    except their 1x1 projections."""
+    ls: List[Layer] = []
+    sz = lambda r, k, s, p: (r + 2 * p - k) // s + 1
+
+    def add(name, cin, res, cout, kh, kw, stride=1, ph=0, pw=0):
+        ls.append(Layer(kind=CONV2D, n=batch, c_in=cin, h=res, w=res, c_out=cout, kh=kh, kw=kw, stride=stride,
+                        pad=ph, pad_w=pw, has_bias=conv_bias, name=name))
+
+    r = image
+    add("stem.c1", 3, r, 32, 3, 3, 2); r = sz(r, 3, 2, 0)
+    add("stem.c2", 32, r, 32, 3, 3); r = sz(r, 3, 1, 0)
+    add("stem.c3", 32, r, 64, 3, 3, 1, 1, 1)
+    add("stem.3a", 64, r, 96, 3, 3, 2); r = sz(r, 3, 2, 0)            # beside a 3x3/2 max-pool: 64 + 96 = 160
+    add("stem.4a.b0c1", 160, r, 64, 1, 1)
+    add("stem.4a.b0c2", 64, r, 96, 3, 3)
+    add("stem.4a.b1c1", 160, r, 64, 1, 1)
+    add("stem.4a.b1c2", 64, r, 64, 1, 7, 1, 0, 3)
+    add("stem.4a.b1c3", 64, r, 64, 7, 1, 1, 3, 0)
+    add("stem.4a.b1c4", 64, r, 96, 3, 3); r = sz(r, 3, 1, 0)          # 96 + 96 = 192
+    add("stem.5a", 192, r, 192, 3, 3, 2); r = sz(r, 3, 2, 0)          # beside a max-pool: 384
+    for b in range(4):
+        t = f"A{b}."
+        add(t + "b0", 384, r, 96, 1, 1)
+        add(t + "b1c1", 384, r, 64, 1, 1); add(t + "b1c2", 64, r, 96, 3, 3, 1, 1, 1)
+        add(t + "b2c1", 384, r, 64, 1, 1); add(t + "b2c2", 64, r, 96, 3, 3, 1, 1, 1); add(t + "b2c3", 96, r, 96, 3, 3, 1, 1, 1)
+        add(t + "b3", 384, r, 96, 1, 1)
+    add("RA.b0", 384, r, 384, 3, 3, 2)
+    add("RA.b1c1", 384, r, 192, 1, 1); add("RA.b1c2", 192, r, 224, 3, 3, 1, 1, 1); add("RA.b1c3", 224, r, 256, 3, 3, 2)
+    r = sz(r, 3, 2, 0)                                                  # 384 + 256 + 384 (pool) = 1024
+    for b in range(7):
+        t = f"B{b}."
+        add(t + "b0", 1024, r, 384, 1, 1)
+        add(t + "b1c1", 1024, r, 192, 1, 1); add(t + "b1c2", 192, r, 224, 1, 7, 1, 0, 3); add(t + "b1c3", 224, r, 256, 7, 1, 1, 3, 0)
+        add(t + "b2c1", 1024, r, 192, 1, 1); add(t + "b2c2", 192, r, 192, 7, 1, 1, 3, 0); add(t + "b2c3", 192, r, 224, 1, 7, 1, 0, 3)
+        add(t + "b2c4", 224, r, 224, 7, 1, 1, 3, 0); add(t + "b2c5", 224, r, 256, 1, 7, 1, 0, 3)
+        add(t + "b3", 1024, r, 128, 1, 1)
+    add("RB.b0c1", 1024, r, 192, 1, 1); add("RB.b0c2", 192, r, 192, 3, 3, 2)
+    add("RB.b1c1", 1024, r, 256, 1, 1); add("RB.b1c2", 256, r, 256, 1, 7, 1, 0, 3); add("RB.b1c3", 256, r, 320, 7, 1, 1, 3, 0)
+    add("RB.b1c4", 320, r, 320, 3, 3, 2)
+    r = sz(r, 3, 2, 0)                                                  # 192 + 320 + 1024 (pool) = 1536
+    for b in range(3):
+        t = f"C{b}."
+        add(t + "b0", 1536, r, 256, 1, 1)
+        add(t + "b1c1", 1536, r, 384, 1, 1); add(t + "b1c2a", 384, r, 256, 1, 3, 1, 0, 1); add(t + "b1c2b", 384, r, 256, 3, 1, 1, 1, 0)
+        add(t + "b2c1", 1536, r, 384, 1, 1); add(t + "b2c2", 384, r, 448, 3, 1, 1, 1, 0); add(t + "b2c3", 448, r, 512, 1, 3, 1, 0, 1)
+        add(t + "b2c4a", 512, r, 256, 1, 3, 1, 0, 1); add(t + "b2c4b", 512, r, 256, 3, 1, 1, 1, 0)
+        add(t + "b3", 1536, r, 256, 1, 1)
+    ls.append(linear(batch, 1536, classes, 1, name="fc"))
+    return ls
+
+
 def bert_large_layers(blocks=24, hidden=1024, ffn=4096, tokens=32 * 128) -> List[Layer]:
     ls = []
     for b in range(blocks):
@@ -147,6 +211,7 @@ CONFIGS = {
     "r152":  dict(cid=4, xi=0.95, gamma=0.03, relu=True),
     "bertl": dict(cid=5, xi=0.95, gamma=0.01, relu=False),
     "d201":  dict(cid=6, xi=0.95, gamma=0.03, relu=True),
+    "iv4":   dict(cid=7, xi=0.95, gamma=0.03, relu=True),
 }
 
 
@@ -163,6 +228,8 @@ def config_layers(name: str, batch: int | None = None) -> List[Layer]:
         return bert_large_layers()
     if name == "d201":
         return densenet_layers(batch=batch or 16)
+    if name == "iv4":
+        return inception_v4_layers(batch=batch or 16)
     raise KeyError(name)
 
 

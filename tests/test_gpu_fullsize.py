@@ -120,14 +120,14 @@ def sampled_layers(layers, cap=28):
     than `cap` (DenseNet: every dense layer has its own input width), an even subsample of them."""
     first = {}
     for i, l in enumerate(layers):
-        first.setdefault((l.kind, l.dA, l.dG, l.R, l.kh, l.stride), i)
+        first.setdefault((l.kind, l.dA, l.dG, l.R, l.kh, l.kw, l.stride), i)
     idx = sorted(first.values())
     if len(idx) > cap:
         idx = [idx[round(k * (len(idx) - 1) / (cap - 1))] for k in range(cap)]
     return sorted(set(idx) | {len(layers) - 1})
 
 
-@pytest.mark.parametrize("name", ["r152", "bertl", "d201"])
+@pytest.mark.parametrize("name", ["r152", "bertl", "d201", "iv4"])
 def test_large_sets_sampled_against_oracle(ctx, name):
     t0 = time.perf_counter()
     hp, layers, ins, out = gpu_step(ctx, name)

@@ -91,6 +91,19 @@ CONV_CASES = [
 ]
 
 
+@pytest.mark.parametrize("kh,kw,ph,pw,s,cin", [(1, 7, 0, 3, 1, 20), (7, 1, 3, 0, 1, 20), (1, 3, 0, 1, 1, 70), (3, 1, 1, 0, 1, 70), (3, 5, 0, 2, 2, 9)])
+def test_conv_factors_rectangular_pads(ctx, kh, kw, ph, pw, s, cin):
+    """1x7 / 7x1 / 1x3 / 3x1 windows padded along their long side only (Inception-style layers)."""
+    rng = np.random.default_rng(kh * 10 + kw)
+    layer = shapes.Layer(kind=1, n=3, c_in=cin, h=12, w=12, c_out=6, kh=kh, kw=kw, stride=s, pad=ph, pad_w=pw, has_bias=1)
+    a = np.maximum(rng.standard_normal(layer.act_shape), 0).astype(np.float32)
+    g = (1e-3 * rng.standard_normal(layer.gout_shape)).astype(np.float32)
+    A0, G0 = np.eye(layer.dA), np.eye(layer.dG)
+    A_d, G_d = run_factors(ctx, [layer], [a], [g], [A0], [G0], 0.9)
+    check_factor(A_d[0], oracle.update_factor_A(layer, a, A0, 0.9), "A")
+    check_factor(G_d[0], oracle.update_factor_G(layer, g, G0, 0.9), "G")
+
+
 @pytest.mark.parametrize("n,cin,h,w,cout,kh,kw,s,p,bias", CONV_CASES)
 def test_conv_factors(ctx, n, cin, h, w, cout, kh, kw, s, p, bias):
     rng = np.random.default_rng(n * 1000 + cin * 10 + kh)

@@ -24,8 +24,8 @@ def brute_rows(layer, a):
                 for c in range(layer.c_in):
                     for i in range(layer.kh):
                         for j in range(layer.kw):
-                            y = oy * layer.stride - layer.pad + i
-                            x = ox * layer.stride - layer.pad + j
+                            y = oy * layer.stride - layer.ph + i
+                            x = ox * layer.stride - layer.pw + j
                             inside = 0 <= y < layer.h and 0 <= x < layer.w
                             row.append(float(a[n, c, y, x]) if inside else 0.0)
                 if layer.has_bias:
@@ -58,6 +58,19 @@ def test_conv_factor_matches_bruteforce(k, s, p, bias):
     got_rows = oracle.im2col_rows(layer, a)
     assert got_rows.shape == (layer.R, layer.dA)
     np.testing.assert_array_equal(got_rows, np.array(rows))            # exact: pure data movement
+    np.testing.assert_allclose(oracle.factor_from_rows(got_rows), brute_factor(rows), rtol=1e-13, atol=1e-15)
+
+
+@pytest.mark.parametrize("kh,kw,ph,pw,s", [(1, 7, 0, 3, 1), (7, 1, 3, 0, 1), (1, 3, 0, 1, 1), (3, 1, 1, 0, 1), (3, 5, 0, 2, 2)])
+def test_rectangular_windows_with_different_pads_match_bruteforce(kh, kw, ph, pw, s):
+    """Windows like 1x7 are padded along their long side only."""
+    rng = np.random.default_rng(kh * 10 + kw)
+    layer = shapes.Layer(kind=1, n=2, c_in=3, h=6, w=8, c_out=4, kh=kh, kw=kw, stride=s, pad=ph, pad_w=pw, has_bias=1)
+    assert (layer.oh, layer.ow) == ((6 + 2 * ph - kh) // s + 1, (8 + 2 * pw - kw) // s + 1)
+    a = rng.standard_normal(layer.act_shape).astype(np.float32)
+    rows = brute_rows(layer, a)
+    got_rows = oracle.im2col_rows(layer, a)
+    np.testing.assert_array_equal(got_rows, np.array(rows))
     np.testing.assert_allclose(oracle.factor_from_rows(got_rows), brute_factor(rows), rtol=1e-13, atol=1e-15)
 
 

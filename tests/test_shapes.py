@@ -47,6 +47,23 @@ def test_densenet201_matches_paper_table():
     assert sum(l.kind == 1 and l.kh == 3 and l.dA == 1153 for l in cfg) == 98
 
 
+def test_inception_v4_matches_paper_table():
+    L, As, Gs, _, _ = _gold()["inceptionv4"]
+    ls = shapes.inception_v4_layers(conv_bias=0)
+    assert len(ls) == L
+    tri = lambda d: d * (d + 1) // 2
+    assert abs(sum(tri(l.c_in * l.kh * l.kw) for l in ls) / 1e6 - As) < 0.06
+    assert abs(sum(tri(l.dG) for l in ls) / 1e6 - Gs) < 0.06
+    cfg = shapes.config_layers("iv4")
+    assert len(cfg) == 150 and cfg[0].n == 16
+    by = {l.name: l for l in cfg}
+    # 224 -> 111 -> 109 -> 54 -> 52 -> 25 (Inception-A) -> 12 (B) -> 5 (C); padded 1x7 / 7x1 keep the size
+    assert (by["stem.c2"].h, by["stem.3a"].h, by["stem.4a.b0c1"].h, by["stem.5a"].h) == (111, 109, 54, 52)
+    assert (by["A0.b0"].h, by["B0.b0"].h, by["C0.b0"].h) == (25, 12, 5)
+    l17 = by["B3.b1c2"]
+    assert (l17.kh, l17.kw, l17.ph, l17.pw, l17.oh, l17.ow) == (1, 7, 0, 3, 12, 12)
+
+
 def test_r50_config_dims():
     ls = shapes.config_layers("r50")
     assert len(ls) == 54
