@@ -1045,20 +1045,31 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       P = InvertPlan{};
     }
     P.dims.assign(dims, dims + n);
-    // Load-balanced placement of the matrices on the groups (the paper's Algorithm 1 without its
-    // communication term, weighted by the true cost d^3): largest first, each to the lightest group.
-    // Matrices that fit one pivot block (d <= NB) need a single launch and all go to group 0.
+    // Placement of the matrices on the lockstep groups.  The matrices with the longest chains (more
+    // than half the largest number of outer blocks) form group 0: they decide how long the call
+    // takes, and kept apart they are not held back by the steps of the many shorter matrices, whose
+    // groups finish early and fill the machine meanwhile.  The other matrices are spread over the
+    // remaining groups by the paper's Algorithm 1 without its communication term and with the true
+    // cost d^3 as weight: largest first, each to the lightest group.  Matrices that fit one pivot
+    // block (d <= NB) need a single launch and all go to group 0.
     std::vector<int> by_size(n);
     for (int i = 0; i < n; ++i) by_size[i] = i;
     std::stable_sort(by_size.begin(), by_size.end(), [&](int a, int b) { return dims[a] > dims[b]; });
-    int n_large = 0;
-    for (int i = 0; i < n; ++i) n_large += dims[i] > NB;
+    int n_large = 0, max_nob = 0, n_long = 0;
+    for (int i = 0; i < n; ++i)
+      if (dims[i] > NB) { ++n_large; max_nob = std::max(max_nob, inv_nob(dims[i], ctx->inv_agg)); }
+    auto is_long = [&](int i) { return dims[i] > NB && 2 * inv_nob(dims[i], ctx->inv_agg) > max_nob; };
+    for (int i = 0; i < n; ++i) n_long += is_long(i);
     const int G = std::max(1, std::min(ctx->inv_groups, n_large));
+    const bool split = G >= 2 && n_long > 0 && n_long < n_large;   // otherwise: plain balancing over all groups
     P.groups.assign(G, InvertGroup{});
     std::vector<double> load(G, 0.0);
     for (int i : by_size) {
       int g = 0;
-      if (dims[i] > NB) g = int(std::min_element(load.begin(), load.end()) - load.begin());
+      if (dims[i] > NB) {
+        if (split) g = is_long(i) ? 0 : 1 + int(std::min_element(load.begin() + 1, load.end()) - (load.begin() + 1));
+        else g = int(std::min_element(load.begin(), load.end()) - load.begin());
+      }
       P.groups[g].idx.push_back(i);
       load[g] += double(dims[i]) * dims[i] * dims[i];
     }
