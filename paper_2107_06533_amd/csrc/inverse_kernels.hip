@@ -60,48 +60,67 @@ constexpr int WP = SB + 1;      // pitch of a wave's staging sub-block
 // pivot (0 if none).
 template <int KM>
 __device__ __forceinline__ float row_bcast(float x) {   // lane KM of every 16-lane row, to the whole row
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + KM, 0xF, 0xF, false));
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x150 + KM, 0xF, 0xF, true));
 }
 
+// Step K gets column K (ci0, ci1: the lane's two rows) and the pivot p as arguments; it fetches
+// those of step K + 1 itself as soon as the column of step K + 1 has been updated, ahead of the
+// other seven columns, so that the cross-lane reads are in flight during the rest of the update.
 template <int K>
-__device__ __forceinline__ void sweep32_step(float (&r)[16], int m, int g, int& bad) {
+__device__ __forceinline__ void sweep32_step(float (&r)[16], int m, int g, int& bad, float ci0, float ci1, float p) {
   constexpr int ka = K >> 4, km = K & 15, kg = K >> 3, kb = K & 7;
-  const int src = (16 * kg + m) << 2;
-  const float ci0 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, r[kb])));
-  const float ci1 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, r[8 + kb])));
-  const float p = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[8 * ka + kb]), 16 * kg + km));
+  constexpr int K1 = (K + 1) & 31, ka1 = K1 >> 4, km1 = K1 & 15, kg1 = K1 >> 3, kb1 = K1 & 7;
   if (!(p > 0.f) && bad == 0) bad = K + 1;
   float ip = __builtin_amdgcn_rcpf(p);
   ip = fmaf(fmaf(-p, ip, 1.f), ip, ip);   // one Newton step on the hardware reciprocal
   const float w0 = ci0 * ip, w1 = ci1 * ip;
   // the lane that holds row k: r - (1 - 1/p) r = r / p, the swept pivot row
   const bool prow = m == km;
-  const float wu0 = (prow && ka == 0) ? 1.f - ip : w0;
-  const float wu1 = (prow && ka == 1) ? 1.f - ip : w1;
-#pragma unroll
-  for (int b = 0; b < 8; ++b) {
+  const float nwu0 = (prow && ka == 0) ? ip - 1.f : -w0;
+  const float nwu1 = (prow && ka == 1) ? ip - 1.f : -w1;
+  auto upd = [&](int b) {
     const float c = row_bcast<km>(r[8 * ka + b]);   // row k, this lane's column b (read before it is updated)
-    r[b] = fmaf(-wu0, c, r[b]);
-    r[8 + b] = fmaf(-wu1, c, r[8 + b]);
+    r[b] = fmaf(c, nwu0, r[b]);
+    r[8 + b] = fmaf(c, nwu1, r[8 + b]);
+  };
+  float nci0 = 0.f, nci1 = 0.f, np = 1.f;
+  if constexpr (K + 1 < 32) {
+    upd(kb1);
+    const int src = (16 * kg1 + m) << 2;
+    nci0 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, r[kb1])));
+    nci1 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, r[8 + kb1])));
+    np = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[8 * ka1 + kb1]), 16 * kg1 + km1));
+    __builtin_amdgcn_sched_barrier(0);
   }
+#pragma unroll
+  for (int b = 0; b < 8; ++b)
+    if (K + 1 >= 32 || b != kb1) upd(b);
   if (g == kg) {   // pivot column
     r[kb] = (prow && ka == 0) ? -ip : w0;
     r[8 + kb] = (prow && ka == 1) ? -ip : w1;
   }
-  if constexpr (K + 1 < 32) sweep32_step<K + 1>(r, m, g, bad);
+  if constexpr (K + 1 < 32) sweep32_step<K + 1>(r, m, g, bad, nci0, nci1, np);
 }
 
 __device__ __forceinline__ void sweep32(float (&r)[16], int lane, int& bad) {
-  sweep32_step<0>(r, lane & 15, lane >> 4, bad);
+  const int m = lane & 15;
+  const float ci0 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(m << 2, __builtin_bit_cast(int, r[0])));
+  const float ci1 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(m << 2, __builtin_bit_cast(int, r[8])));
+  const float p = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[0]), 0));
+  sweep32_step<0>(r, m, lane >> 4, bad, ci0, ci1, p);
 #pragma unroll
   for (int t = 0; t < 16; ++t) r[t] = -r[t];
 }
 
-__global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__ mats, const MatJob* __restrict__ jobs,
-                                                      int mat0, int step, float gamma, int small) {
-  __shared__ float S[NB * SP];
-  __shared__ float stage[4][SB * WP];
-  const InvMat Mx = mats[jobs ? jobs[blockIdx.x].mat : mat0 + (int)blockIdx.x];   // a job list, or consecutive matrices
+constexpr int PIVOT_LDS_FLOATS = NB * SP + 4 * SB * WP;
+
+// fuse = 1 (small = 0, step > 0): the block has not yet received the rank-NB update of the previous
+// pivot block of the same matrix; its panels (Wt, Zt: k-major, NB rows) are applied here first,
+// block -= Wt^T Zt restricted to the block's columns, so that the update launch can leave this
+// block out and run beside this kernel instead of before it.
+__device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gamma, int small, int fuse, float* __restrict__ smem) {
+  float* S = smem;
+  float (*stage)[SB * WP] = reinterpret_cast<float (*)[SB * WP]>(smem + NB * SP);
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int li = lane & 31, lh = lane >> 5;
   const int d = Mx.d, ld = small ? Mx.d : Mx.ld;
@@ -132,6 +151,42 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
     }
   }
   __syncthreads();
+
+  if (fuse) {
+    // the ten 32 x 32 sub-blocks of the lower triangle, dealt to the four waves; operands come
+    // straight from the k-major panels (lane (i, h) reads row 2q + h, column i: coalesced)
+    gcf_ptr Wp = as_global((const float*)Mx.Wt) + k0;
+    gcf_ptr Zp = as_global((const float*)Mx.Zt) + k0;
+    const uint32_t ldp = (uint32_t)Mx.ldp;
+    for (int blk = w; blk < 10; blk += 4) {
+      const int bi = blk < 1 ? 0 : blk < 3 ? 1 : blk < 6 ? 2 : 3;
+      const int bj = blk - bi * (bi + 1) / 2;
+      f32x16 acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+      for (int qb = 0; qb < 4; ++qb) {
+        float a[16], b[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const uint32_t row = (uint32_t)(2 * (qb * 16 + q) + lh) * ldp;
+          a[q] = Wp[row + (uint32_t)(bi * SB + li)];
+          b[q] = Zp[row + (uint32_t)(bj * SB + li)];
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q], b[q], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = bi * SB + mfma_row(v, lane), j = bj * SB + mfma_col(lane);
+        if (j > i) continue;               // diagonal sub-blocks: lower half, mirrored like the load
+        const float x = S[i * SP + j] - acc[v];
+        S[i * SP + j] = x;
+        S[j * SP + i] = x;
+      }
+    }
+    __syncthreads();
+  }
 
   int bad = 0;
   for (int kb = 0; kb < nsb; ++kb) {
@@ -230,6 +285,31 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
       Q[i * NB + j] = in ? -v : 0.f;
       if (in) X[(size_t)(k0 + i) * ld + k0 + j] = v;
     }
+  }
+}
+
+__global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__ mats, const MatJob* __restrict__ jobs,
+                                                      int mat0, int step, float gamma, int small) {
+  __shared__ float smem[PIVOT_LDS_FLOATS];
+  const InvMat Mx = mats[jobs ? jobs[blockIdx.x].mat : mat0 + (int)blockIdx.x];   // a job list, or consecutive matrices
+  pivot_body(Mx, step, gamma, small, 0, smem);
+}
+
+// One launch for two things that do not depend on each other: workgroups [0, npiv) sweep pivot
+// block `step` of their matrices (applying the previous block's update to it themselves, fuse = 1),
+// the others run the previous block's rank-NB update on every other tile.
+__global__ __launch_bounds__(NT) void gj_pivot_update_kernel(const InvMat* __restrict__ mats, const MatJob* __restrict__ pjobs,
+                                                             int npiv, int step, float gamma,
+                                                             const TileDesc* __restrict__ descs,
+                                                             const TileJob* __restrict__ ujobs, int nupd) {
+  __shared__ float smem[PIVOT_LDS_FLOATS > TILE_LDS_FLOATS ? PIVOT_LDS_FLOATS : TILE_LDS_FLOATS];
+  const int g = blockIdx.x;
+  if (g < npiv) {
+    const InvMat Mx = mats[pjobs[g].mat];
+    pivot_body(Mx, step, gamma, 0, 1, smem);
+  } else if (g - npiv < nupd) {
+    const TileJob J = ujobs[g - npiv];
+    run_tile<KMajorLoader, KMajorLoader, true>(descs[J.desc], J, smem);
   }
 }
 
@@ -531,6 +611,12 @@ void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma
 void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s) {
   if (nmats <= 0) return;
   hipLaunchKernelGGL(gj_pivot_kernel, dim3(nmats), dim3(NT), 0, s, mats, (const MatJob*)jobs, mat0, step, gamma, small);
+}
+void launch_gj_pivot_update(const InvMat* mats, const void* pjobs, int npiv, int step, float gamma,
+                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s) {
+  if (npiv <= 0 && nupd <= 0) return;
+  hipLaunchKernelGGL(gj_pivot_update_kernel, dim3(npiv + nupd), dim3(NT), 0, s, mats, (const MatJob*)pjobs, npiv, step, gamma,
+                     descs, ujobs, nupd);
 }
 void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s) {
   if (njobs <= 0) return;

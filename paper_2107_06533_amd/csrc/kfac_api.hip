@@ -131,6 +131,7 @@ struct kfac_ctx {
   int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
   int inv_groups = 2;                     // matrix groups swept concurrently
   int inv_agg = 4;                        // pivot blocks per aggregated (rank agg*128) update
+  int inv_fuse = 0;                       // 1: a pivot block applies the previous block's update to itself (one launch fewer per step)
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
   hipStream_t inv_side[MAX_INV_GROUPS] = {};     // every group's side stream for the off-chain updates
   hipEvent_t inv_fork = nullptr, inv_join[MAX_INV_GROUPS] = {};
@@ -615,7 +616,7 @@ InvWsLayout inv_ws_layout(int ldp, int agg) {
   return L;
 }
 
-InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
+InvertSchedule schedule_invert(int n, const int32_t* dims, int agg, bool fuse = false) {
   InvertSchedule S;
   S.order.resize(n);
   for (int i = 0; i < n; ++i) S.order[i] = i;
@@ -669,17 +670,25 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg) {
         for (int bi = 0; bi < nsub; ++bi)
           for (int bj = 0; bj <= bi; ++bj) {
             if (bi == t || bj == t) continue;
+            S.stats.mfma_flops += int64_t(ceil_div(kb, KC) * KC) * active_blocks(dimB, dimB, bi, bj, true) * 32 * 32 * 2;
+            if (fuse && bi == t + 1 && bj == t + 1) continue;   // the next pivot block: updated by its own sweep kernel
             TileJob j{};
             j.desc = v; j.bi = bi; j.bj = bj; j.kbeg = 0; j.kend = kb; j.part = -1;
             S.sub_upd.push_back(j);
-            S.stats.mfma_flops += int64_t(ceil_div(kb, KC) * KC) * active_blocks(dimB, dimB, bi, bj, true) * 32 * 32 * 2;
           }
         S.stats.mfma_flops += int64_t(nsub - 1) * NB * 16 * 32 * 32 * 2;   // panel products
       }
       S.sub_pivot_off[st + 1] = int(S.sub_pivot.size());
       S.sub_panel_off[st + 1] = int(S.sub_panel.size());
       S.sub_upd_off[st + 1] = int(S.sub_upd.size());
-      launches += (S.sub_pivot_off[st + 1] > S.sub_pivot_off[st]) + (S.sub_panel_off[st + 1] > S.sub_panel_off[st]) + (S.sub_upd_off[st + 1] > S.sub_upd_off[st]);
+    }
+    for (int t = 0; t < aw; ++t) {   // fused: first pivot alone, panel, update together with the next pivot
+      const int st = b * aw + t;
+      const bool piv = S.sub_pivot_off[st + 1] > S.sub_pivot_off[st];
+      const bool piv_next = t + 1 < aw && S.sub_pivot_off[st + 2] > S.sub_pivot_off[st + 1];
+      const bool upd = S.sub_upd_off[st + 1] > S.sub_upd_off[st];
+      launches += (S.sub_panel_off[st + 1] > S.sub_panel_off[st]);
+      launches += fuse ? (t == 0 && piv) + (piv && (piv_next || upd)) : piv + upd;
     }
     // ---- steps 2-4 for the matrices that have more than one outer block.  The gather/scatter and
     // panel-product jobs of the rows of the NEXT outer block come first in their lists: the chain
@@ -798,6 +807,7 @@ kfac_status kfac_create(kfac_ctx** out, int device) {
     const int v = std::atoi(e);
     if (v >= 1 && v <= 16) c->inv_agg = v;
   }
+  if (const char* e = std::getenv("KFAC_INV_FUSE")) c->inv_fuse = std::atoi(e) != 0;
   if (const char* e = std::getenv("KFAC_KJOB")) {
     const int v = std::atoi(e);
     if (v >= KC) c->kjob = std::min(v, MAX_JOB_ROWS);
@@ -1078,7 +1088,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     for (InvertGroup& Gp : P.groups) {
       std::vector<int32_t> gd;
       for (int i : Gp.idx) gd.push_back(dims[i]);
-      InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), ctx->inv_agg);
+      InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), ctx->inv_agg, ctx->inv_fuse != 0);
       Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.n_ob = S.n_ob; Gp.n_views = S.n_views;
       Gp.view_off = S.view_off; Gp.n_in_ob = S.n_in_ob; Gp.sub_pivot_off = S.sub_pivot_off;
       Gp.sub_panel_off = S.sub_panel_off; Gp.sub_upd_off = S.sub_upd_off;
@@ -1218,8 +1228,8 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   // The groups are issued outer block by outer block so that their kernels interleave in time.
   // Chain of a group (its main stream), per outer block b: sweep of the diagonal sub-matrix, QB,
   // gather of the block column, then only what the next diagonal sub-matrix needs: panel product
-  // and scatter for the rows of the next outer block, update of the next diagonal sub-matrix.
-  // Side stream: panel product and scatter for all other rows, then the other two update lists.
+  // for the rows of the next outer block, update of the next diagonal sub-matrix.
+  // Side stream: panel product for all other rows, every scatter, then the other two update lists.
   // Cross-stream order, by what the kernels touch:
   //   QB(b), gather(b)   rewrite QB, which the side's panel product (b-1) reads, and read tiles
   //                      that UPD_COL(b-1) wrote                        -> chain waits for ev_col[b-1]
@@ -1242,11 +1252,14 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       if (b >= Gp.n_ob) continue;
       hipStream_t gs = gstream(g), side = ctx->inv_side[g];
       const InvMat* views = d_views[g];
+      // Sweep of the diagonal sub-matrices: pivot block t, its panel, then ONE launch holding both
+      // the update by block t of every tile but the next pivot block and the sweep of pivot block
+      // t + 1 (which applies that update to itself): the two are independent.
       for (int t = 0; t < aw; ++t) {
         const int stp = b * aw + t;
         const int npiv = Gp.sub_pivot_off[stp + 1] - Gp.sub_pivot_off[stp];
         if (npiv == 0) break;
-        {
+        if (t == 0 || !ctx->inv_fuse) {
           ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
           launch_gj_pivot(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp], 0, npiv, t, gamma, 0, gs);
         }
@@ -1255,10 +1268,16 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
           launch_gj_panel(views, static_cast<const MatJobH*>(Gp.d_sub_panel) + Gp.sub_panel_off[stp],
                           Gp.sub_panel_off[stp + 1] - Gp.sub_panel_off[stp], t, gs);
         }
-        if (Gp.sub_upd_off[stp + 1] > Gp.sub_upd_off[stp]) {
+        const int npiv_next = t + 1 < aw ? Gp.sub_pivot_off[stp + 2] - Gp.sub_pivot_off[stp + 1] : 0;
+        const int nupd = Gp.sub_upd_off[stp + 1] - Gp.sub_upd_off[stp];
+        const TileJob* uj = static_cast<const TileJob*>(Gp.d_sub_upd) + Gp.sub_upd_off[stp];
+        if (ctx->inv_fuse && npiv_next > 0) {
+          ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
+          launch_gj_pivot_update(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp + 1], npiv_next, t + 1, gamma,
+                                 d_descs[g], uj, nupd, gs);
+        } else if (nupd > 0) {
           ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, gs);
-          launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_sub_upd) + Gp.sub_upd_off[stp],
-                           Gp.sub_upd_off[stp + 1] - Gp.sub_upd_off[stp], 0, gs);
+          launch_tile_gemm(d_descs[g], uj, nupd, 0, gs);
         }
       }
       const MatJobH* mvj = static_cast<const MatJobH*>(Gp.d_mv);
@@ -1279,7 +1298,10 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         if (bp1 > bp0) {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
           launch_tile_gemm(d_descs[g], bpj + bp0, bp1 - bp0, 0, gs);
-          launch_gj_move(d_moves[g] + 1, mvj + mv0, mv1 - mv0, kch, 1, gs);
+        }
+        if (bp1 > bp0) {   // the chain wrote part of the W panel
+          HIP_TRY(ctx, ensure_event(Gp.ev_chain[b]));
+          HIP_TRY(ctx, hipEventRecord(Gp.ev_chain[b], gs));
         }
       }
       const bool has_diag = Gp.upd_off[UPD_DIAG][b + 1] > Gp.upd_off[UPD_DIAG][b];
@@ -1296,10 +1318,12 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         launch_tile_gemm(d_descs[g], bpj + bp1, bp2 - bp1, 0, side);
         launch_gj_move(d_moves[g] + 1, mvj + mv1, mv2 - mv1, kch, 1, side);
       }
-      if (bp1 > bp0) {   // the chain wrote part of the W panel
-        HIP_TRY(ctx, ensure_event(Gp.ev_chain[b]));
-        HIP_TRY(ctx, hipEventRecord(Gp.ev_chain[b], gs));
+      if (bp1 > bp0) {
         HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_chain[b], 0));
+        // its scatter into the matrix is read by nothing before the next outer block's gather
+        // (which waits for ev_col[b]), so it leaves the chain
+        ScopedTiming tm(ctx, KFAC_K_INV_PANEL, side);
+        launch_gj_move(d_moves[g] + 1, mvj + mv0, mv1 - mv0, kch, 1, side);
       }
       upd_launch(g, UPD_COL, b, side);
       HIP_TRY(ctx, ensure_event(Gp.ev_col[b]));
