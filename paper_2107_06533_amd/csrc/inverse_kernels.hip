@@ -114,6 +114,50 @@ __device__ __forceinline__ void sweep32(float (&r)[16], int lane, int& bad) {
 
 constexpr int PIVOT_LDS_FLOATS = NB * SP + 4 * SB * WP;
 
+// block -= Wt^T Zt on the ten 32 x 32 sub-blocks of the block's lower triangle (mirrored into the
+// upper one), Wt/Zt k-major with NB rows.  Wave WV takes the sub-blocks
+//   0: (0,0) (1,0) (2,0)    1: (3,0) (3,1) (3,2)    2: (1,1) (2,1)    3: (2,2) (3,3)
+// so that it needs at most four 32-column operand panels; all of them are requested before the
+// first product (operands come straight from memory: lane (i, h) reads row 2q + h, column i), so
+// the wave pays the memory latency once.
+template <int WV>
+__device__ __forceinline__ void own_update(float* __restrict__ S, gcf_ptr Wp, gcf_ptr Zp, uint32_t ldp, int lane) {
+  constexpr int NA = WV == 0 ? 3 : WV == 1 ? 1 : 2;    // row panels (from Wt)
+  constexpr int NZ = WV == 1 ? 3 : WV == 3 ? 2 : 1;    // column panels (from Zt)
+  constexpr int A0 = WV == 0 ? 0 : WV == 1 ? 3 : WV == 2 ? 1 : 2;
+  constexpr int Z0 = WV == 0 ? 0 : WV == 1 ? 0 : WV == 2 ? 1 : 2;
+  constexpr int NJ = WV < 2 ? 3 : 2;
+  const int li = lane & 31, lh = lane >> 5;
+  float a[NA][64], b[NZ][64];
+  const uint32_t base = (uint32_t)lh * ldp + (uint32_t)li;
+#pragma unroll
+  for (int x = 0; x < (NA > NZ ? NA : NZ); ++x)
+#pragma unroll
+    for (int q = 0; q < 64; ++q) {
+      if (x < NA) a[x][q] = Wp[base + (uint32_t)(2 * q) * ldp + (uint32_t)((A0 + x) * SB)];
+      if (x < NZ) b[x][q] = Zp[base + (uint32_t)(2 * q) * ldp + (uint32_t)((Z0 + x) * SB)];
+    }
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    constexpr bool zfix = WV == 0 || WV == 2;          // one column panel, rows vary
+    const int ia = WV == 1 ? 0 : k, iz = zfix ? 0 : k;
+    const int bi = A0 + ia, bj = Z0 + iz;
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+    for (int q = 0; q < 64; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ia][q], b[iz][q], acc, 0, 0, 0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int i = bi * SB + mfma_row(v, lane), j = bj * SB + mfma_col(lane);
+      if (j > i) continue;               // diagonal sub-blocks: lower half, mirrored like the load
+      const float x = S[i * SP + j] - acc[v];
+      S[i * SP + j] = x;
+      S[j * SP + i] = x;
+    }
+  }
+}
+
 // fuse = 1 (small = 0, step > 0): the block has not yet received the rank-NB update of the previous
 // pivot block of the same matrix; its panels (Wt, Zt: k-major, NB rows) are applied here first,
 // block -= Wt^T Zt restricted to the block's columns, so that the update launch can leave this
@@ -129,61 +173,63 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
   const int nsb = (n + SB - 1) / SB;
   const float damp = small ? gamma : 0.f;
 
-  // lower triangle -> full symmetric block in LDS, identity past n.  Loads go out in batches of
-  // 32 per thread (range-checked buffer loads; skipped elements cost no memory traffic).
+  // lower triangle -> full symmetric block in LDS, identity past n (range-checked buffer loads;
+  // skipped elements cost no memory traffic).  Thread t owns column j = t % 128 and every second row.
   const rsrc_t rs_src = make_rsrc(small ? Mx.F : Mx.X, small ? (uint32_t)d * (uint32_t)d * 4u : Mx.xelems * 4u);
+  {
+    const int j = t & (NB - 1), i0 = t >> 7;
+    const uint32_t row2 = 2u * (uint32_t)ld * 4u;
+    if (n == NB) {   // a whole block: all 64 loads of the thread in flight at once
+      float v[64];
+      uint32_t off = ((uint32_t)(k0 + i0) * (uint32_t)ld + (uint32_t)(k0 + j)) * 4u;
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    float v[32];
+      for (int u = 0; u < 64; ++u) {
+        v[u] = buf_load(rs_src, j <= i0 + 2 * u ? off : OOB_OFFSET);
+        off += row2;
+      }
+      int la = i0 * SP + j, lb = j * SP + i0;
 #pragma unroll
-    for (int u = 0; u < 32; ++u) {
-      const int i = (t >> 7) + 2 * (b * 32 + u), j = t & (NB - 1);
-      v[u] = buf_load(rs_src, (i < n && j <= i) ? ((uint32_t)(k0 + i) * (uint32_t)ld + (uint32_t)(k0 + j)) * 4u : OOB_OFFSET);
-    }
+      for (int u = 0; u < 64; ++u) {
+        const int i = i0 + 2 * u;
+        if (j <= i) {
+          const float x = i == j ? v[u] + damp : v[u];
+          S[la] = x;
+          S[lb] = x;
+        }
+        la += 2 * SP;
+        lb += 2;
+      }
+    } else {
 #pragma unroll
-    for (int u = 0; u < 32; ++u) {
-      const int i = (t >> 7) + 2 * (b * 32 + u), j = t & (NB - 1);
-      if (j > i) continue;
-      float x = v[u];
-      if (i == j) x = i < n ? x + damp : 1.f;
-      S[i * SP + j] = x;
-      S[j * SP + i] = x;
+      for (int b = 0; b < 2; ++b) {
+        float v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+          const int i = i0 + 2 * (b * 32 + u);
+          v[u] = buf_load(rs_src, (i < n && j <= i) ? ((uint32_t)(k0 + i) * (uint32_t)ld + (uint32_t)(k0 + j)) * 4u : OOB_OFFSET);
+        }
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+          const int i = i0 + 2 * (b * 32 + u);
+          if (j > i) continue;
+          float x = v[u];
+          if (i == j) x = i < n ? x + damp : 1.f;
+          S[i * SP + j] = x;
+          S[j * SP + i] = x;
+        }
+      }
     }
   }
   __syncthreads();
 
   if (fuse) {
-    // the ten 32 x 32 sub-blocks of the lower triangle, dealt to the four waves; operands come
-    // straight from the k-major panels (lane (i, h) reads row 2q + h, column i: coalesced)
     gcf_ptr Wp = as_global((const float*)Mx.Wt) + k0;
     gcf_ptr Zp = as_global((const float*)Mx.Zt) + k0;
-    const uint32_t ldp = (uint32_t)Mx.ldp;
-    for (int blk = w; blk < 10; blk += 4) {
-      const int bi = blk < 1 ? 0 : blk < 3 ? 1 : blk < 6 ? 2 : 3;
-      const int bj = blk - bi * (bi + 1) / 2;
-      f32x16 acc;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-#pragma unroll
-      for (int qb = 0; qb < 4; ++qb) {
-        float a[16], b[16];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const uint32_t row = (uint32_t)(2 * (qb * 16 + q) + lh) * ldp;
-          a[q] = Wp[row + (uint32_t)(bi * SB + li)];
-          b[q] = Zp[row + (uint32_t)(bj * SB + li)];
-        }
-#pragma unroll
-        for (int q = 0; q < 16; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q], b[q], acc, 0, 0, 0);
-      }
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = bi * SB + mfma_row(v, lane), j = bj * SB + mfma_col(lane);
-        if (j > i) continue;               // diagonal sub-blocks: lower half, mirrored like the load
-        const float x = S[i * SP + j] - acc[v];
-        S[i * SP + j] = x;
-        S[j * SP + i] = x;
-      }
+    switch (w) {
+      case 0: own_update<0>(S, Wp, Zp, (uint32_t)Mx.ldp, lane); break;
+      case 1: own_update<1>(S, Wp, Zp, (uint32_t)Mx.ldp, lane); break;
+      case 2: own_update<2>(S, Wp, Zp, (uint32_t)Mx.ldp, lane); break;
+      default: own_update<3>(S, Wp, Zp, (uint32_t)Mx.ldp, lane); break;
     }
     __syncthreads();
   }
@@ -272,18 +318,42 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
     else if (bad && *Mx.info == 0) *Mx.info = Mx.info_base + k0 + bad;   // first failing sweep wins (zeroed by the init kernel)
   }
 
-  gf_ptr X = as_global(Mx.X);
-  gf_ptr Q = as_global(Mx.Q);
+  // Result: the lower triangle mirrored (exactly symmetric).  small: X = +inverse.  Otherwise
+  // Q = +inverse, zero padded, and the swept block (-inverse) back into X.
+  const int j = t & (NB - 1), i0 = t >> 7;
+  if (n == NB) {
+    const rsrc_t rs_q = make_rsrc(Mx.Q, small ? 0u : NB * NB * 4u);
+    const rsrc_t rs_out = make_rsrc(Mx.X, small ? (uint32_t)d * (uint32_t)d * 4u : Mx.xelems * 4u);
+    uint32_t offq = (uint32_t)(i0 * NB + j) * 4u;
+    uint32_t offx = ((uint32_t)(k0 + i0) * (uint32_t)ld + (uint32_t)(k0 + j)) * 4u;
+    const uint32_t row2 = 2u * (uint32_t)ld * 4u;
+    int la = i0 * SP + j, lb = j * SP + i0;
+#pragma unroll 16
+    for (int u = 0; u < 64; ++u) {
+      const float v = S[i0 + 2 * u >= j ? la : lb];
+      if (small) {
+        buf_store(rs_out, offx, -v);
+      } else {
+        buf_store(rs_q, offq, -v);
+        buf_store(rs_out, offx, v);
+      }
+      la += 2 * SP; lb += 2;
+      offq += 2u * NB * 4u; offx += row2;
+    }
+  } else {
+    gf_ptr X = as_global(Mx.X);
+    gf_ptr Q = as_global(Mx.Q);
 #pragma unroll 8
-  for (int e = t; e < NB * NB; e += NT) {
-    const int i = e >> 7, j = e & (NB - 1);
-    const bool in = i < n && j < n;
-    const float v = i >= j ? S[i * SP + j] : S[j * SP + i];
-    if (small) {
-      if (in) X[(size_t)i * ld + j] = -v;
-    } else {
-      Q[i * NB + j] = in ? -v : 0.f;
-      if (in) X[(size_t)(k0 + i) * ld + k0 + j] = v;
+    for (int e = t; e < NB * NB; e += NT) {
+      const int i = e >> 7, jj = e & (NB - 1);
+      const bool in = i < n && jj < n;
+      const float v = i >= jj ? S[i * SP + jj] : S[jj * SP + i];
+      if (small) {
+        if (in) X[(size_t)i * ld + jj] = -v;
+      } else {
+        Q[i * NB + jj] = in ? -v : 0.f;
+        if (in) X[(size_t)(k0 + i) * ld + k0 + jj] = v;
+      }
     }
   }
 }

@@ -65,6 +65,7 @@ struct InvertGroup {
   std::vector<int> idx;              // caller indices of the group's matrices
   std::vector<int> order;            // sorted position -> position in idx (large first, descending d)
   int n_large = 0, n_small = 0, n_ob = 0, n_views = 0;
+  int agg = 4;                       // pivot blocks per outer block in this group
   std::vector<int> view_off, n_in_ob;            // [outer block]
   std::vector<int> sub_pivot_off, sub_panel_off, sub_upd_off;   // [outer block * (agg + 1) + sub-step (+1)]
   std::vector<int> qm_off, mv_off, bp_off;       // [outer block (+1)]
@@ -131,7 +132,8 @@ struct kfac_ctx {
   int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
   int inv_groups = 2;                     // matrix groups swept concurrently
   int inv_agg = 4;                        // pivot blocks per aggregated (rank agg*128) update
-  int inv_fuse = 0;                       // 1: a pivot block applies the previous block's update to itself (one launch fewer per step)
+  int inv_agg_chain = 6;                  // the same for a latency-bound group (fewer outer steps on the critical path)
+  int inv_fuse = 1;                       // 1: a pivot block applies the previous block's update to itself (one launch fewer per step)
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
   hipStream_t inv_side[MAX_INV_GROUPS] = {};     // every group's side stream for the off-chain updates
   hipEvent_t inv_fork = nullptr, inv_join[MAX_INV_GROUPS] = {};
@@ -805,7 +807,11 @@ kfac_status kfac_create(kfac_ctx** out, int device) {
   }
   if (const char* e = std::getenv("KFAC_INV_AGG")) {
     const int v = std::atoi(e);
-    if (v >= 1 && v <= 16) c->inv_agg = v;
+    if (v >= 1 && v <= 16) c->inv_agg = c->inv_agg_chain = v;
+  }
+  if (const char* e = std::getenv("KFAC_INV_AGG_CHAIN")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= 16) c->inv_agg_chain = v;
   }
   if (const char* e = std::getenv("KFAC_INV_FUSE")) c->inv_fuse = std::atoi(e) != 0;
   if (const char* e = std::getenv("KFAC_KJOB")) {
@@ -860,7 +866,10 @@ size_t kfac_workspace_bytes_invert(const kfac_ctx* ctx, int n, const int32_t* di
   if (n <= 0 || !dims) return 0;
   for (int i = 0; i < n; ++i)
     if (dims[i] < 1) return 0;
-  return size_t(schedule_invert(n, dims, ctx ? ctx->inv_agg : 4).stats.ws_bytes);   // independent of how the matrices are grouped
+  // independent of how the matrices are grouped, but not of the outer block size a group gets: the larger of the two
+  const size_t a = size_t(schedule_invert(n, dims, ctx ? ctx->inv_agg : 4).stats.ws_bytes);
+  const size_t b = size_t(schedule_invert(n, dims, ctx ? ctx->inv_agg_chain : 6).stats.ws_bytes);
+  return std::max(a, b);
 }
 
 size_t kfac_workspace_bytes_precondition(const kfac_ctx*, int n, const int32_t* dG, const int32_t* dA) {
@@ -1056,7 +1065,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     }
     P.dims.assign(dims, dims + n);
     // Placement of the matrices on the lockstep groups.  The matrices with the longest chains (more
-    // than half the largest number of outer blocks) form group 0: they decide how long the call
+    // than 0.6 of the largest number of pivot blocks) form group 0: they decide how long the call
     // takes, and kept apart they are not held back by the steps of the many shorter matrices, whose
     // groups finish early and fill the machine meanwhile.  The other matrices are spread over the
     // remaining groups by the paper's Algorithm 1 without its communication term and with the true
@@ -1065,10 +1074,10 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     std::vector<int> by_size(n);
     for (int i = 0; i < n; ++i) by_size[i] = i;
     std::stable_sort(by_size.begin(), by_size.end(), [&](int a, int b) { return dims[a] > dims[b]; });
-    int n_large = 0, max_nob = 0, n_long = 0;
+    int n_large = 0, max_nblk = 0, n_long = 0;
     for (int i = 0; i < n; ++i)
-      if (dims[i] > NB) { ++n_large; max_nob = std::max(max_nob, inv_nob(dims[i], ctx->inv_agg)); }
-    auto is_long = [&](int i) { return dims[i] > NB && 2 * inv_nob(dims[i], ctx->inv_agg) > max_nob; };
+      if (dims[i] > NB) { ++n_large; max_nblk = std::max(max_nblk, ceil_div(dims[i], NB)); }
+    auto is_long = [&](int i) { return dims[i] > NB && 5 * ceil_div(dims[i], NB) > 3 * max_nblk; };
     for (int i = 0; i < n; ++i) n_long += is_long(i);
     const int G = std::max(1, std::min(ctx->inv_groups, n_large));
     const bool split = G >= 2 && n_long > 0 && n_long < n_large;   // otherwise: plain balancing over all groups
@@ -1088,7 +1097,21 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     for (InvertGroup& Gp : P.groups) {
       std::vector<int32_t> gd;
       for (int i : Gp.idx) gd.push_back(dims[i]);
-      InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), ctx->inv_agg, ctx->inv_fuse != 0);
+      // Outer block size of the group.  A group whose longest chain of dependent launches outlasts
+      // its arithmetic is latency-bound and gets the larger outer blocks (fewer outer steps, more
+      // of the work in the diagonal sub-matrix sweeps); a throughput-bound group keeps the smaller
+      // ones, whose rank-128 sub-updates are a smaller share of the work.  Estimates from timings
+      // on MI355X: 90 us per pivot block, 300 us per outer block, 100 TFLOP/s for the products.
+      {
+        double flops = 0.0, chain = 0.0;
+        for (int32_t d : gd) {
+          if (d <= NB) continue;
+          flops += double(d) * d * d;
+          chain = std::max(chain, ceil_div(d, NB) * 90e-6 + inv_nob(d, ctx->inv_agg) * 300e-6);
+        }
+        Gp.agg = chain > flops / 100e12 ? ctx->inv_agg_chain : ctx->inv_agg;
+      }
+      InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), Gp.agg, ctx->inv_fuse != 0);
       Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.n_ob = S.n_ob; Gp.n_views = S.n_views;
       Gp.view_off = S.view_off; Gp.n_in_ob = S.n_in_ob; Gp.sub_pivot_off = S.sub_pivot_off;
       Gp.sub_panel_off = S.sub_panel_off; Gp.sub_upd_off = S.sub_upd_off;
@@ -1147,9 +1170,9 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   std::vector<const PanelMove*> d_moves(G);
   std::vector<const TileDesc*> d_descs(G);
   float* wsf = static_cast<float*>(ctx->ws[WS_INVERT]);
-  const int agg = ctx->inv_agg, aw = agg + 1;
   for (int g = 0; g < G; ++g) {
     InvertGroup& Gp = P.groups[g];
+    const int agg = Gp.agg, aw = agg + 1;
     const int ng = int(Gp.idx.size()), nv = Gp.n_views;
     const size_t mats_bytes = sizeof(InvMat) * size_t(ng);
     const size_t views_bytes = sizeof(InvMat) * size_t(nv);
@@ -1252,6 +1275,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       if (b >= Gp.n_ob) continue;
       hipStream_t gs = gstream(g), side = ctx->inv_side[g];
       const InvMat* views = d_views[g];
+      const int aw = Gp.agg + 1;
       // Sweep of the diagonal sub-matrices: pivot block t, its panel, then ONE launch holding both
       // the update by block t of every tile but the next pivot block and the sweep of pivot block
       // t + 1 (which applies that update to itself): the two are independent.
