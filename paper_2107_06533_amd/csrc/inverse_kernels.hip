@@ -50,7 +50,6 @@ __global__ __launch_bounds__(NT) void gj_init_kernel(const InvMat* __restrict__ 
 //            padded to NB x NB) and the swept block (-inverse) back into X.
 constexpr int SB = 32;          // sub-block order
 constexpr int SP = NB + 1;      // LDS row pitch of the block (odd: conflict-free rows and columns)
-constexpr int WP = SB + 1;      // pitch of a wave's staging sub-block
 
 // In-register sweep of a 32 x 32 SPD sub-block.  Lane 16 g + m holds rows m and m + 16 of the
 // column group 8g .. 8g+7:  r[8a + b] = D[m + 16a][8g + b].  Step k needs row k (for the lane's
@@ -112,7 +111,7 @@ __device__ __forceinline__ void sweep32(float (&r)[16], int lane, int& bad) {
   for (int t = 0; t < 16; ++t) r[t] = -r[t];
 }
 
-constexpr int PIVOT_LDS_FLOATS = NB * SP + 4 * SB * WP;
+constexpr int PIVOT_LDS_FLOATS = NB * SP;
 
 // block -= Wt^T Zt on the ten 32 x 32 sub-blocks of the block's lower triangle (mirrored into the
 // upper one), Wt/Zt k-major with NB rows.  Wave WV takes the sub-blocks
@@ -164,7 +163,6 @@ __device__ __forceinline__ void own_update(float* __restrict__ S, gcf_ptr Wp, gc
 // block out and run beside this kernel instead of before it.
 __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gamma, int small, int fuse, float* __restrict__ smem) {
   float* S = smem;
-  float (*stage)[SB * WP] = reinterpret_cast<float (*)[SB * WP]>(smem + NB * SP);
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int li = lane & 31, lh = lane >> 5;
   const int d = Mx.d, ld = small ? Mx.d : Mx.ld;
@@ -236,55 +234,51 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
 
   int bad = 0;
   for (int kb = 0; kb < nsb; ++kb) {
-    // (A) inverse of the diagonal sub-block, in every wave; the result goes through the wave's
-    // staging block to reach the operand layout dinv[q] = D^-1[li][2q + lh]
-    float dinv[16];
-    {
-      const int m = lane & 15, g = lane >> 4;
-      float r[16];
+    // (A) inverse of the diagonal sub-block, in every wave (r: +D^-1 in the sweep's layout)
+    const int m = lane & 15, g = lane >> 4;
+    float r[16];
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 8; ++b) r[8 * a + b] = S[(kb * SB + m + 16 * a) * SP + kb * SB + 8 * g + b];
-      int bad_k = 0;
-      sweep32(r, lane, bad_k);
-      if (bad_k && bad == 0) bad = kb * SB + bad_k;
-      float* st = stage[w];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 8; ++b) st[(m + 16 * a) * WP + 8 * g + b] = r[8 * a + b];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-      for (int q = 0; q < 16; ++q) dinv[q] = st[li * WP + 2 * q + lh];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
+      for (int b = 0; b < 8; ++b) r[8 * a + b] = S[(kb * SB + m + 16 * a) * SP + kb * SB + 8 * g + b];
+    int bad_k = 0;
+    sweep32(r, lane, bad_k);
+    if (bad_k && bad == 0) bad = kb * SB + bad_k;
 
-    // (B) panel and update of sub-block row w
+    // (B) panel and update of sub-block row w.  Sub-block (kb, w) is read by nobody during this
+    // step and ends as W_w^T: the wave first uses it to turn D^-1 into the operand layout
+    // dinv[q] = D^-1[li][2q + lh], then stores W_w^T there and reads -W_w back as an operand.
     f32x16 wacc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) wacc[v] = 0.f;
     const bool work = (w != kb) && (w < nsb);
     if (work) {
-      float z[16];
+      float* st = S + (kb * SB) * SP + w * SB;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) st[(m + 16 * a) * SP + 8 * g + b] = r[8 * a + b];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      float dinv[16], z[16];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) dinv[q] = st[li * SP + 2 * q + lh];
 #pragma unroll
       for (int q = 0; q < 16; ++q) z[q] = S[(w * SB + li) * SP + kb * SB + 2 * q + lh];
 #pragma unroll
       for (int q = 0; q < 16; ++q) wacc = __builtin_amdgcn_mfma_f32_32x32x2f32(z[q], dinv[q], wacc, 0, 0, 0);
-      // accumulator layout -> operand layout through the wave's staging sub-block
-      float* st = stage[w];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();   // every lane has read dinv before the sub-block is rewritten
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-      for (int v = 0; v < 16; ++v) st[mfma_row(v, lane) * WP + mfma_col(lane)] = wacc[v];
+      for (int v = 0; v < 16; ++v) st[mfma_col(lane) * SP + mfma_row(v, lane)] = wacc[v];
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       float wn[16];
 #pragma unroll
-      for (int q = 0; q < 16; ++q) wn[q] = -st[li * WP + 2 * q + lh];
+      for (int q = 0; q < 16; ++q) wn[q] = -st[(2 * q + lh) * SP + li];
       for (int j = 0; j < nsb; ++j) {
         if (j == kb) continue;
         float zj[16];
@@ -299,17 +293,15 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
         for (int v = 0; v < 16; ++v) S[(w * SB + mfma_row(v, lane)) * SP + j * SB + mfma_col(lane)] = acc[v];
       }
     }
-    __syncthreads();   // every read of the old sub-block column kb is done
+    __syncthreads();   // every read of the old sub-block column kb (and of the diagonal sub-block) is done
     if (work) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = mfma_row(v, lane), c = mfma_col(lane);
-        S[(w * SB + r) * SP + kb * SB + c] = wacc[v];
-        S[(kb * SB + c) * SP + w * SB + r] = wacc[v];
-      }
+      for (int v = 0; v < 16; ++v) S[(w * SB + mfma_row(v, lane)) * SP + kb * SB + mfma_col(lane)] = wacc[v];
     } else if (w == kb) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q) S[(kb * SB + li) * SP + kb * SB + 2 * q + lh] = -dinv[q];
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) S[(kb * SB + m + 16 * a) * SP + kb * SB + 8 * g + b] = -r[8 * a + b];
     }
     __syncthreads();
   }
