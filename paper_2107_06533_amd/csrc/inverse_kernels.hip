@@ -38,11 +38,13 @@ __global__ __launch_bounds__(NT) void gj_init_kernel(const InvMat* __restrict__ 
 // The block lives in LDS as 4 x 4 sub-blocks of 32 x 32 and is swept sub-block by sub-block:
 //   (A) every wave inverts the 32 x 32 diagonal sub-block D in registers (redundantly, so no
 //       exchange between waves is needed) by the scalar sweep, 16 fused multiply-adds per lane and
-//       step (see sweep32_step), and turns the result into the operand layout of
-//       v_mfma_f32_32x32x2_f32 (lane (i, h) = i + 32 h holds D^-1[i][2t + h], t = 0..15);
+//       step (see sweep32_step);
 //   (B) wave w != kb owns sub-block row w:  W_w = Z_w D^-1  (Z_w = old sub-block (w, kb)), then
-//       S_wj -= W_w Z_j^T for j != kb, all on the matrix cores; after a barrier it stores W_w into
-//       sub-block (w, kb) and its transpose into (kb, w); wave kb stores -D^-1.
+//       S_wj -= W_w Z_j^T for j != kb, all on the matrix cores (v_mfma_f32_32x32x2_f32: lane
+//       (i, h) = i + 32 h supplies element [i][2q + h] of an operand in step q).  Sub-block (kb, w),
+//       which no wave reads during the step, serves the wave as scratch for the two layout changes
+//       (D^-1 and W_w into operand layout) and ends as W_w^T; after a barrier the wave stores W_w
+//       into sub-block (w, kb), and wave kb stores -D^-1.
 // Sub-blocks past n are identity and are skipped.  The lower triangle is mirrored on the way out,
 // so the result is exactly symmetric.
 // small = 1: block = F + gamma I (whole matrix, d <= NB), result written to X as +inverse.

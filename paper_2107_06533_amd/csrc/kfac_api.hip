@@ -66,6 +66,7 @@ struct InvertGroup {
   std::vector<int> order;            // sorted position -> position in idx (large first, descending d)
   int n_large = 0, n_small = 0, n_ob = 0, n_views = 0;
   int agg = 4;                       // pivot blocks per outer block in this group
+  bool latency_bound = false;        // the chain of dependent launches outlasts the group's arithmetic
   std::vector<int> view_off, n_in_ob;            // [outer block]
   std::vector<int> sub_pivot_off, sub_panel_off, sub_upd_off;   // [outer block * (agg + 1) + sub-step (+1)]
   std::vector<int> qm_off, mv_off, bp_off;       // [outer block (+1)]
@@ -133,6 +134,8 @@ struct kfac_ctx {
   int inv_groups = 2;                     // matrix groups swept concurrently
   int inv_agg = 4;                        // pivot blocks per aggregated (rank agg*128) update
   int inv_agg_chain = 6;                  // the same for a latency-bound group (fewer outer steps on the critical path)
+  int inv_side_pad = 16384;               // extra LDS per workgroup of a latency-bound group's off-chain products: one workgroup
+                                          // per compute unit, so that the chain's kernels always find a free slot
   int inv_fuse = 1;                       // 1: a pivot block applies the previous block's update to itself (one launch fewer per step)
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
   hipStream_t inv_side[MAX_INV_GROUPS] = {};     // every group's side stream for the off-chain updates
@@ -813,6 +816,7 @@ kfac_status kfac_create(kfac_ctx** out, int device) {
     const int v = std::atoi(e);
     if (v >= 1 && v <= 16) c->inv_agg_chain = v;
   }
+  if (const char* e = std::getenv("KFAC_SIDE_PAD")) c->inv_side_pad = std::max(0, std::atoi(e));
   if (const char* e = std::getenv("KFAC_INV_FUSE")) c->inv_fuse = std::atoi(e) != 0;
   if (const char* e = std::getenv("KFAC_KJOB")) {
     const int v = std::atoi(e);
@@ -1109,7 +1113,8 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
           flops += double(d) * d * d;
           chain = std::max(chain, ceil_div(d, NB) * 90e-6 + inv_nob(d, ctx->inv_agg) * 300e-6);
         }
-        Gp.agg = chain > flops / 100e12 ? ctx->inv_agg_chain : ctx->inv_agg;
+        Gp.latency_bound = chain > flops / 100e12;
+        Gp.agg = Gp.latency_bound ? ctx->inv_agg_chain : ctx->inv_agg;
       }
       InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), Gp.agg, ctx->inv_fuse != 0);
       Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.n_ob = S.n_ob; Gp.n_views = S.n_views;
@@ -1262,12 +1267,12 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   //   UPD_COL/REST(b)    read the chain's part of the W panel           -> side waits for ev_chain[b]
   std::vector<int> last_col(G, -1), last_rest(G, -1);    // outer block of the group's latest side-stream work
   auto ensure_event = [&](hipEvent_t& e) { return e ? hipSuccess : hipEventCreateWithFlags(&e, hipEventDisableTiming); };
-  auto upd_launch = [&](int g, int kind, int b, hipStream_t st) {
+  auto upd_launch = [&](int g, int kind, int b, hipStream_t st, int pad = 0) {
     InvertGroup& Gp = P.groups[g];
     const int o0 = Gp.upd_off[kind][b], cnt = Gp.upd_off[kind][b + 1] - o0;
     if (cnt <= 0) return;
     ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, st);
-    launch_tile_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_upd[kind]) + o0, cnt, 0, st);
+    launch_tile_gemm_pad(d_descs[g], static_cast<const TileJob*>(Gp.d_upd[kind]) + o0, cnt, pad, st);
   };
   for (int b = 0; b < max_ob; ++b)
     for (int g = 0; g < G; ++g) {
@@ -1275,6 +1280,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       if (b >= Gp.n_ob) continue;
       hipStream_t gs = gstream(g), side = ctx->inv_side[g];
       const InvMat* views = d_views[g];
+      const int side_pad = Gp.latency_bound ? ctx->inv_side_pad : 0;
       const int aw = Gp.agg + 1;
       // Sweep of the diagonal sub-matrices: pivot block t, its panel, then ONE launch holding both
       // the update by block t of every tile but the next pivot block and the sweep of pivot block
@@ -1339,7 +1345,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_gather[b], 0));
       if (bp2 > bp1) {
         ScopedTiming tm(ctx, KFAC_K_INV_PANEL, side);
-        launch_tile_gemm(d_descs[g], bpj + bp1, bp2 - bp1, 0, side);
+        launch_tile_gemm_pad(d_descs[g], bpj + bp1, bp2 - bp1, side_pad, side);
         launch_gj_move(d_moves[g] + 1, mvj + mv1, mv2 - mv1, kch, 1, side);
       }
       if (bp1 > bp0) {
@@ -1349,12 +1355,12 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
         ScopedTiming tm(ctx, KFAC_K_INV_PANEL, side);
         launch_gj_move(d_moves[g] + 1, mvj + mv0, mv1 - mv0, kch, 1, side);
       }
-      upd_launch(g, UPD_COL, b, side);
+      upd_launch(g, UPD_COL, b, side, side_pad);
       HIP_TRY(ctx, ensure_event(Gp.ev_col[b]));
       HIP_TRY(ctx, hipEventRecord(Gp.ev_col[b], side));
       last_col[g] = b;
       if (has_rest) {
-        upd_launch(g, UPD_REST, b, side);
+        upd_launch(g, UPD_REST, b, side, side_pad);
         HIP_TRY(ctx, ensure_event(Gp.ev_rest[b]));
         HIP_TRY(ctx, hipEventRecord(Gp.ev_rest[b], side));
         last_rest[g] = b;

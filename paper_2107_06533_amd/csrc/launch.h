@@ -6,6 +6,7 @@ namespace kfac {
 
 void launch_tile_any(const TileDesc* descs, const TileJob* jobs, int njobs, int xcd_order, hipStream_t s);
 void launch_tile_gemm(const TileDesc* descs, const TileJob* jobs, int njobs, int xcd_order, hipStream_t s);
+void launch_tile_gemm_pad(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, hipStream_t s);
 void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs, hipStream_t s);
 void launch_lag_assemble(const LagAsm* lags, const LagJob* jobs, int njobs, hipStream_t s);
 

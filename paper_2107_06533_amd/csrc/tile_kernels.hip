@@ -200,6 +200,11 @@ void launch_tile_gemm(const TileDesc* descs, const TileJob* jobs, int njobs, int
   hipLaunchKernelGGL(tile_gemm_kernel, dim3(grid), dim3(NT), 0, s, descs, jobs, njobs, xcd_order);
 }
 
+void launch_tile_gemm_pad(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(tile_gemm_kernel, dim3(njobs), dim3(NT), pad_bytes, s, descs, jobs, njobs, 0);
+}
+
 void launch_lag_assemble(const LagAsm* lags, const LagJob* jobs, int njobs, hipStream_t s) {
   if (njobs <= 0) return;
   hipLaunchKernelGGL(lag_assemble_kernel, dim3(njobs), dim3(NT), 0, s, lags, jobs, njobs);
