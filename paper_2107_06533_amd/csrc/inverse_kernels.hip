@@ -55,8 +55,7 @@ constexpr int SP = NB + 1;      // LDS row pitch of the block (odd: conflict-fre
 
 // In-register sweep of a 32 x 32 SPD sub-block.  Lane 16 g + m holds rows m and m + 16 of the
 // column group 8g .. 8g+7:  r[8a + b] = D[m + 16a][8g + b].  Step k needs row k (for the lane's
-// eight columns: a broadcast inside the lane's 16-lane row, folded into the multiply-add as a DPP
-// operand) and column k (for the lane's two rows: two cross-lane reads from column group k / 8).
+// eight columns: a DPP broadcast inside the lane's 16-lane row) and column k (for the lane's two rows: two cross-lane reads from column group k / 8).
 // Returns +D^-1 in the same layout; `bad` receives the 1-based index of the first non-positive
 // pivot (0 if none).
 template <int KM>

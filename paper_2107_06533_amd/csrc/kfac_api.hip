@@ -568,7 +568,8 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
 // (agg*128 rows).  For outer block b, with D its diagonal sub-matrix and Z the rest of its block
 // column:
 //   1. D is swept in place by the one-level algorithm (pivot, panel, rank-128 update, only on the
-//      <= agg x agg tiles of D): D <- -D^-1;
+//      <= agg x agg tiles of D): D <- -D^-1.  With `fuse` the update of the next pivot block is left
+//      to that block's own sweep kernel, which then shares a launch with the rest of the update;
 //   2. QB = D^-1 as a full symmetric matrix;  Zt = Z^T gathered k-major;
 //   3. Wt = QB Zt (one GEMM with K = agg*128), scattered back into the block column;
 //   4. every tile outside the outer block gets  M_ij -= W_i Z_j^T  (K = agg*128), in three lists:
