@@ -379,10 +379,15 @@ __global__ __launch_bounds__(NT) void gj_pivot_update_kernel(const InvMat* __res
 // ---- panel: Zt = old block column `step` (as [NB][ldp], k-major), Wt = Q * Zt, X panel <- W -----
 // One job per 128-row tile `it` of the block column (it != step).  Tiles above the pivot live in
 // block row `step` of the lower triangle (read along rows), tiles below in block column `step`.
-__global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restrict__ mats,
-                                                         const MatJob* __restrict__ jobs, int njobs, int step) {
-  __shared__ float Qs[PANEL];
-  __shared__ float Zs[PANEL];
+__global__ __launch_bounds__(NT) void gj_panel_kernel(const InvMat* __restrict__ mats,
+                                                      const MatJob* __restrict__ jobs, int njobs, int step) {
+  // All loads of the 128-deep contraction (4 k chunks of Q and of the tile) are requested up front:
+  // the kernel sits on the critical path with few workgroups, so it pays the memory latency once
+  // instead of once per chunk.  The chunks then pass through two LDS buffers (the footprint of a
+  // product workgroup, so the kernel fits beside one on a compute unit).
+  constexpr int NCH = NB / KC;
+  __shared__ float Qs[2 * PANEL];
+  __shared__ float Zs[2 * PANEL];
   const int g = blockIdx.x;
   if (g >= njobs) return;
   const MatJob J = jobs[g];
@@ -412,47 +417,48 @@ __global__ __launch_bounds__(NT, 2) void gj_panel_kernel(const InvMat* __restric
   const uint32_t cut = (uint32_t)(k0 + kb) * ld;
   const rsrc_t rs_x = make_rsrc(Mx.X, (above && cut < Mx.xelems ? cut : Mx.xelems) * 4u);
   const uint32_t d4 = ld * 4u;
-  float rq[NU], rz[NU];
-  auto issue = [&](int kk0) {
+  float rq[NCH][NU], rz[NCH][NU];
 #pragma unroll
-    for (int u = 0; u < NU; ++u) rq[u] = buf_load(rs_q, (uint32_t)((kk0 + kp + 2 * u) * NB + ml) * 4u);
+  for (int c = 0; c < NCH; ++c) {
+    const int kk0 = c * KC;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) rq[c][u] = buf_load(rs_q, (uint32_t)((kk0 + kp + 2 * u) * NB + ml) * 4u);
     if (above) {
       const uint32_t base = (uint32_t)(k0 + kk0 + kp) * d4 + (uint32_t)(i0 + ml) * 4u;
 #pragma unroll
-      for (int u = 0; u < NU; ++u) rz[u] = buf_load(rs_x, base + (uint32_t)(2 * u) * d4);
+      for (int u = 0; u < NU; ++u) rz[c][u] = buf_load(rs_x, base + (uint32_t)(2 * u) * d4);
     } else {
       const int kk = kk0 + kl;
       const uint32_t base = kk < kb ? (uint32_t)(k0 + kk) * 4u : OOB_OFFSET;
 #pragma unroll
       for (int u = 0; u < NU; ++u)     // rows past the (sub-)matrix read 0
-        rz[u] = buf_load(rs_x, i0 + mg + MG * u < d ? base + (uint32_t)(i0 + mg + MG * u) * d4 : OOB_OFFSET);
+        rz[c][u] = buf_load(rs_x, i0 + mg + MG * u < d ? base + (uint32_t)(i0 + mg + MG * u) * d4 : OOB_OFFSET);
     }
-  };
-
+  }
   Acc4 acc;
   acc_zero(acc);
   gf_ptr Zt = as_global(Mx.Zt);
-  issue(0);
-  for (int kk0 = 0; kk0 < NB; kk0 += KC) {
-    __syncthreads();   // previous chunk fully consumed
 #pragma unroll
-    for (int u = 0; u < NU; ++u) Qs[lds_idx(ml, kp + 2 * u)] = rq[u];
+  for (int c = 0; c < NCH; ++c) {
+    float* Qc = Qs + (c & 1) * PANEL;
+    float* Zc = Zs + (c & 1) * PANEL;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) Qc[lds_idx(ml, kp + 2 * u)] = rq[c][u];
     if (above) {
 #pragma unroll
-      for (int u = 0; u < NU; ++u) Zs[lds_idx(ml, kp + 2 * u)] = rz[u];
+      for (int u = 0; u < NU; ++u) Zc[lds_idx(ml, kp + 2 * u)] = rz[c][u];
     } else {
 #pragma unroll
-      for (int u = 0; u < NU; ++u) Zs[lds_idx(mg + MG * u, kl)] = rz[u];
+      for (int u = 0; u < NU; ++u) Zc[lds_idx(mg + MG * u, kl)] = rz[c][u];
     }
-    if (kk0 + KC < NB) issue(kk0 + KC);   // next chunk's loads fly during this chunk's MFMAs
-    __syncthreads();
+    __syncthreads();   // chunk c staged; the other buffer (chunk c - 1) may still be read by slower waves
 #pragma unroll
-    for (int u = 0; u < NU; ++u) Zt[(size_t)(slot * NB + kk0 + kp + 2 * u) * ldp + i0 + ml] = Zs[lds_idx(ml, kp + 2 * u)];
+    for (int u = 0; u < NU; ++u) Zt[(size_t)(slot * NB + c * KC + kp + 2 * u) * ldp + i0 + ml] = Zc[lds_idx(ml, kp + 2 * u)];
     switch (pat) {
-      case PAT_FULL: mma_ktile<PAT_FULL>(Qs, Zs, acc, wm, wn, lane); break;
-      case PAT_ROW1: mma_ktile<PAT_ROW1>(Qs, Zs, acc, wm, wn, lane); break;
-      case PAT_COL1: mma_ktile<PAT_COL1>(Qs, Zs, acc, wm, wn, lane); break;
-      case PAT_ONE: mma_ktile<PAT_ONE>(Qs, Zs, acc, wm, wn, lane); break;
+      case PAT_FULL: mma_ktile<PAT_FULL>(Qc, Zc, acc, wm, wn, lane); break;
+      case PAT_ROW1: mma_ktile<PAT_ROW1>(Qc, Zc, acc, wm, wn, lane); break;
+      case PAT_COL1: mma_ktile<PAT_COL1>(Qc, Zc, acc, wm, wn, lane); break;
+      case PAT_ONE: mma_ktile<PAT_ONE>(Qc, Zc, acc, wm, wn, lane); break;
       default: break;
     }
   }
