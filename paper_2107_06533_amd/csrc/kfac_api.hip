@@ -74,6 +74,8 @@ struct InvertGroup {
   std::vector<int> upd_off[3];                   // [UPD_DIAG / UPD_COL / UPD_REST][outer block (+1)]
   std::vector<size_t> ws_off;        // per large matrix: float offset of its workspace inside the group's region
   void* d_init = nullptr; int n_init = 0;
+  int n_init_first = 0;              // leading init jobs: the tiles of the first outer block's diagonal sub-matrix
+  hipEvent_t ev_start = nullptr, ev_init = nullptr;   // side stream: fork at the start of a call, rest of the init done
   void* d_finish = nullptr; int n_finish = 0;
   void* d_sub_pivot = nullptr; void* d_sub_panel = nullptr; void* d_sub_upd = nullptr;
   void* d_qm = nullptr; void* d_mv = nullptr; void* d_bp = nullptr;
@@ -411,6 +413,8 @@ void release(InvertPlan& p) {
     for (hipEvent_t e : g.ev_gather) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : g.ev_col) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : g.ev_rest) if (e) (void)hipEventDestroy(e);
+    if (g.ev_start) (void)hipEventDestroy(g.ev_start);
+    if (g.ev_init) (void)hipEventDestroy(g.ev_init);
   }
   p = InvertPlan{};
 }
@@ -583,7 +587,7 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
 // still has that step.
 struct InvertSchedule {
   std::vector<int> order;
-  int n_large = 0, n_small = 0, n_ob = 0, n_views = 0;
+  int n_large = 0, n_small = 0, n_ob = 0, n_views = 0, n_init_first = 0;
   std::vector<int> nblk, ldp, nob;
   std::vector<size_t> ws_off;
   std::vector<int> view_off, n_in_ob, sub_pivot_off, sub_panel_off, sub_upd_off, qm_off, mv_off, bp_off, mv_mid, bp_mid;
@@ -637,11 +641,20 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg, bool fuse = 
     S.ws_off[m] = S.ws_floats;
     S.ws_floats += inv_ws_layout(S.ldp[m], agg).total;
     S.n_ob = std::max(S.n_ob, S.nob[m]);
-    for (int bi = 0; bi < S.nblk[m]; ++bi)
-      for (int bj = 0; bj <= bi; ++bj) S.init.push_back({m, bi, bj, 0});
     const int t32 = ceil_div(d, 32);
     for (int bi = 0; bi < t32; ++bi)
       for (int bj = 0; bj <= bi; ++bj) S.finish.push_back({m, bi, bj, 0});
+  }
+  // init jobs: the tiles of the first outer block's diagonal sub-matrix first (the sweep starts on
+  // them; the others are copied on the side stream meanwhile)
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int m = 0; m < S.n_large; ++m) {
+      const int e0 = inv_ob_end(dims[S.order[m]], agg, 0);
+      for (int bi = 0; bi < S.nblk[m]; ++bi)
+        for (int bj = 0; bj <= bi; ++bj)
+          if ((bi < e0) == (pass == 0)) S.init.push_back({m, bi, bj, 0});
+    }
+    if (pass == 0) S.n_init_first = int(S.init.size());
   }
   S.view_off.assign(S.n_ob + 1, 0); S.n_in_ob.assign(S.n_ob, 0);
   for (int b = 0; b < S.n_ob; ++b) {
@@ -1075,7 +1088,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     // groups finish early and fill the machine meanwhile.  The other matrices are spread over the
     // remaining groups by the paper's Algorithm 1 without its communication term and with the true
     // cost d^3 as weight: largest first, each to the lightest group.  Matrices that fit one pivot
-    // block (d <= NB) need a single launch and all go to group 0.
+    // block (d <= NB) need a single launch and all go to the last group.
     std::vector<int> by_size(n);
     for (int i = 0; i < n; ++i) by_size[i] = i;
     std::stable_sort(by_size.begin(), by_size.end(), [&](int a, int b) { return dims[a] > dims[b]; });
@@ -1089,7 +1102,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     P.groups.assign(G, InvertGroup{});
     std::vector<double> load(G, 0.0);
     for (int i : by_size) {
-      int g = 0;
+      int g = split ? G - 1 : 0;   // matrices of one pivot block: a single launch, kept off the long chain
       if (dims[i] > NB) {
         if (split) g = is_long(i) ? 0 : 1 + int(std::min_element(load.begin() + 1, load.end()) - (load.begin() + 1));
         else g = int(std::min_element(load.begin(), load.end()) - load.begin());
@@ -1126,7 +1139,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       Gp.ws_off = S.ws_off;
       Gp.ev_chain.assign(S.n_ob, nullptr); Gp.ev_col.assign(S.n_ob, nullptr); Gp.ev_rest.assign(S.n_ob, nullptr);
       Gp.ev_gather.assign(S.n_ob, nullptr);
-      Gp.n_init = int(S.init.size()); Gp.n_finish = int(S.finish.size());
+      Gp.n_init = int(S.init.size()); Gp.n_init_first = S.n_init_first; Gp.n_finish = int(S.finish.size());
       Gp.ws_floats = S.ws_floats;
       Gp.ws_base = P.ws_floats;
       P.ws_floats += S.ws_floats;
@@ -1251,7 +1264,19 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
     }
     if (Gp.n_large) {
       ScopedTiming tm(ctx, KFAC_K_INV_INIT, gs);
-      launch_gj_init(d_mats[g], Gp.d_init, Gp.n_init, gamma, gs);
+      launch_gj_init(d_mats[g], Gp.d_init, Gp.n_init_first, gamma, gs);
+    }
+    if (Gp.n_init > Gp.n_init_first) {   // the other tiles: on the side stream, beside the first diagonal sweep
+      hipStream_t side = ctx->inv_side[g];
+      if (!Gp.ev_start) HIP_TRY(ctx, hipEventCreateWithFlags(&Gp.ev_start, hipEventDisableTiming));
+      if (!Gp.ev_init) HIP_TRY(ctx, hipEventCreateWithFlags(&Gp.ev_init, hipEventDisableTiming));
+      HIP_TRY(ctx, hipEventRecord(Gp.ev_start, gs));
+      HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_start, 0));
+      {
+        ScopedTiming tm(ctx, KFAC_K_INV_INIT, side);
+        launch_gj_init(d_mats[g], static_cast<const MatJobH*>(Gp.d_init) + Gp.n_init_first, Gp.n_init - Gp.n_init_first, gamma, side);
+      }
+      HIP_TRY(ctx, hipEventRecord(Gp.ev_init, side));
     }
   }
   // The groups are issued outer block by outer block so that their kernels interleave in time.
@@ -1318,6 +1343,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       const int kch = aw * NB / 32;
       const bool has_panel = Gp.qm_off[b + 1] > Gp.qm_off[b];
       if (has_panel) {
+        if (b == 0 && Gp.n_init > Gp.n_init_first) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_init, 0));   // first touch of tiles outside D_0
         if (last_col[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_col[last_col[g]], 0));
         {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
