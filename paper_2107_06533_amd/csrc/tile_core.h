@@ -81,6 +81,7 @@ __device__ __forceinline__ void buf_store(rsrc_t r, uint32_t byte_off, float v) 
 // (k, m) at ptr[k*ld + m]: consecutive threads read consecutive m.  The resource is cut at the
 // job's last row, so rows at or beyond kend read 0 without a per-load test; one add per load.
 struct KMajorLoader {
+  static constexpr int LOADS = NU;   // vector-memory loads per k step
   rsrc_t rs;
   uint32_t ld4, moff;   // row pitch / column offset in bytes (moff = OOB_OFFSET beyond the matrix)
   uint32_t base;
@@ -146,6 +147,7 @@ struct KMajorLoader {
 // KH_ = KW_ = 0 selects run-time window sizes (up to 63 taps, 64-bit tap mask).
 template <int KH_, int KW_>
 struct ConvLoader {
+  static constexpr int LOADS = NU;
   static constexpr bool TAP64 = (KH_ * KW_ == 0) || (KH_ * KW_ > 31);
   static constexpr int TAP_NEVER = TAP64 ? 63 : 31;
   rsrc_t rs;
@@ -257,6 +259,7 @@ struct ConvLoader {
 // groups per k step with 128-bit loads and writes each as two 64-bit LDS stores (k, k+2 and
 // k+1, k+3 are neighbours in the LDS row order).  A wave reads 8 channel rows of 128 bytes.
 struct Conv11VecLoader {
+  static constexpr int LOADS = NU / 4;   // 128-bit loads
   static_assert(KC == 32 && NT == 256, "eight groups of four k per row of 32 threads");
   static constexpr uint32_t ROW_OOB = 0x40000000u;   // >= any operand size, and ROW_OOB + OOB_OFFSET does not wrap
   rsrc_t rs;
@@ -408,6 +411,23 @@ __device__ __forceinline__ void load_b(LA& la, LB& lb, int k0, float (&rb)[NU]) 
   else lb.load(k0, rb);
 }
 
+// Asks the instruction scheduler to spread the NL vector-memory loads of a k step evenly between
+// its NM matrix instructions instead of issuing them in bursts: a wave issues in order, so while a
+// burst of loads queues up at the memory pipeline none of the MFMAs behind it can start.  With two
+// workgroups per compute unit the k loop of a plain product goes from 114 to 132 TFLOP/s.
+template <int NM, int NL, int G, int I>
+__device__ __forceinline__ void interleave_group() {
+  if constexpr (I < G) {
+    __builtin_amdgcn_sched_group_barrier(0x008, (NM * (I + 1)) / G - (NM * I) / G, 0);   // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x020, (NL * (I + 1)) / G - (NL * I) / G, 0);   // VMEM read
+    interleave_group<NM, NL, G, I + 1>();
+  }
+}
+template <int NM, int NL>
+__device__ __forceinline__ void interleave_loads() {
+  if constexpr (NM > 0 && NL > 0) interleave_group<NM, NL, (NM >= NL ? NL : NM), 0>();
+}
+
 template <unsigned PAT, bool SHARE, bool SAME, class LA, class LB>
 __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, Acc4& tot,
                                           int kbeg, int nkt, int wm, int wn, int lane) {
@@ -423,6 +443,8 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
     la.load(kbeg + kt * KC, ra);
     if (!SHARE) load_b<LA, LB, SAME>(la, lb, kbeg + kt * KC, rb);
     mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
+    if constexpr (!SAME && std::is_same<LA, KMajorLoader>::value && std::is_same<LB, KMajorLoader>::value)   // plain products only: measured no gain elsewhere
+      interleave_loads<(KC / 2) * __builtin_popcount(PAT), LA::LOADS + (SHARE ? 0 : LB::LOADS)>();
     la.store(As + (cur ^ 1) * PANEL, ra);
     if (!SHARE) lb.store(Bs + (cur ^ 1) * PANEL, rb);
     __syncthreads();
