@@ -442,18 +442,25 @@ __global__ __launch_bounds__(NT) void gj_panel_kernel(const InvMat* __restrict__
   for (int c = 0; c < NCH; ++c) {
     float* Qc = Qs + (c & 1) * PANEL;
     float* Zc = Zs + (c & 1) * PANEL;
+    // rows kp + 2u, u = 4g .. 4g+3, are the contiguous positions 8g + 4kp .. +3 of row ml (16-byte stores)
 #pragma unroll
-    for (int u = 0; u < NU; ++u) Qc[lds_idx(ml, kp + 2 * u)] = rq[c][u];
+    for (int gq = 0; gq < NU / 4; ++gq)
+      *reinterpret_cast<f32x4*>(Qc + ml * PK + 8 * gq + 4 * kp) = f32x4{rq[c][4 * gq], rq[c][4 * gq + 1], rq[c][4 * gq + 2], rq[c][4 * gq + 3]};
     if (above) {
 #pragma unroll
-      for (int u = 0; u < NU; ++u) Zc[lds_idx(ml, kp + 2 * u)] = rz[c][u];
+      for (int gq = 0; gq < NU / 4; ++gq)
+        *reinterpret_cast<f32x4*>(Zc + ml * PK + 8 * gq + 4 * kp) = f32x4{rz[c][4 * gq], rz[c][4 * gq + 1], rz[c][4 * gq + 2], rz[c][4 * gq + 3]};
     } else {
 #pragma unroll
       for (int u = 0; u < NU; ++u) Zc[lds_idx(mg + MG * u, kl)] = rz[c][u];
     }
     __syncthreads();   // chunk c staged; the other buffer (chunk c - 1) may still be read by slower waves
 #pragma unroll
-    for (int u = 0; u < NU; ++u) Zt[(size_t)(slot * NB + c * KC + kp + 2 * u) * ldp + i0 + ml] = Zc[lds_idx(ml, kp + 2 * u)];
+    for (int gq = 0; gq < NU / 4; ++gq) {
+      const f32x4 zv = *reinterpret_cast<const f32x4*>(Zc + ml * PK + 8 * gq + 4 * kp);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) Zt[(size_t)(slot * NB + c * KC + kp + 2 * (4 * gq + e)) * ldp + i0 + ml] = zv[e];
+    }
     switch (pat) {
       case PAT_FULL: mma_ktile<PAT_FULL>(Qc, Zc, acc, wm, wn, lane); break;
       case PAT_ROW1: mma_ktile<PAT_ROW1>(Qc, Zc, acc, wm, wn, lane); break;
