@@ -254,6 +254,21 @@ def main():
                      "bound": "hbm", "peak_gbps": 8000.0,
                      "pack_frac": round(pack_bytes / pack_ms / 1e6 / 8000.0, 4),
                      "unpack_frac": round(unpack_bytes / unpack_ms / 1e6 / 8000.0, 4)}
+        # inverse with the packed triangles written by the same kernels, against inverse + pack
+        ev_q = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for _ in range(2):
+            ctx.kfac_invert_batch_packed(dims, A_d + G_d, XA_d + XG_d, pbuf, hp["gamma"], info, stream=stream)
+        ev_q[0].record(stream)
+        for _ in range(reps):
+            ctx.kfac_invert_batch_packed(dims, A_d + G_d, XA_d + XG_d, pbuf, hp["gamma"], info, stream=stream)
+        ev_q[1].record(stream)
+        for _ in range(reps):
+            ctx.kfac_invert_batch(dims, A_d + G_d, XA_d + XG_d, hp["gamma"], info, stream=stream)
+            ctx.kfac_pack_triangles(dims, XA_d + XG_d, pbuf, stream=stream)
+        ev_q[2].record(stream)
+        torch.cuda.synchronize()
+        packed_io["invert_packed_ms"] = round(ev_q[0].elapsed_time(ev_q[1]) / reps, 4)
+        packed_io["invert_then_pack_ms"] = round(ev_q[1].elapsed_time(ev_q[2]) / reps, 4)
         del pbuf
         step()          # the unpack above overwrote the inverses: restore a consistent state
         torch.cuda.synchronize()

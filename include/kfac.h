@@ -127,6 +127,17 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n_mats, const int32_t* dims,
                               const float* const* F, float* const* X,
                               float gamma, int32_t* info_dev, void* hip_stream);
 
+/*
+ * The same call with a second output: `packed` (device buffer of kfac_packed_elems(n_mats, dims)
+ * floats, owned by the caller) receives the packed upper triangles of the inverses, in the layout of
+ * kfac_pack_triangles (the form in which the paper sends an inverse to the other workers, Sec. V-B),
+ * written by the kernels that write X_i: bit-identical to kfac_pack_triangles applied to X afterwards,
+ * without the extra pass.  INVALID_ARG additionally for packed == NULL.
+ */
+kfac_status kfac_invert_batch_packed(kfac_ctx* ctx, int n_mats, const int32_t* dims,
+                                     const float* const* F, float* const* X, float* packed,
+                                     float gamma, int32_t* info_dev, void* hip_stream);
+
 /* Synchronise `hip_stream`, copy info_dev[0..n) to info_host (may be NULL) and return
  * KFAC_ERR_NOT_SPD if any entry is non-zero, else KFAC_OK. */
 kfac_status kfac_check_info(kfac_ctx* ctx, int n, const int32_t* info_dev, int32_t* info_host,

@@ -14,7 +14,7 @@ EXPORTS = [
     "kfac_create", "kfac_destroy", "kfac_last_error",
     "kfac_layer_dA", "kfac_layer_dG", "kfac_layer_rows",
     "kfac_workspace_bytes_factors", "kfac_workspace_bytes_invert", "kfac_workspace_bytes_precondition",
-    "kfac_update_factors", "kfac_invert_batch", "kfac_check_info", "kfac_precondition",
+    "kfac_update_factors", "kfac_invert_batch", "kfac_invert_batch_packed", "kfac_check_info", "kfac_precondition",
     "kfac_packed_elems", "kfac_pack_triangles", "kfac_unpack_triangles", "kfac_place_inversions",
     "kfac_get_plan_stats", "kfac_timing_enable", "kfac_timing_read",
 ]
@@ -88,6 +88,8 @@ def load():
     lib.kfac_update_factors.restype = C.c_int
     lib.kfac_invert_batch.argtypes = [vp, C.c_int, i32p, fpp, fpp, C.c_float, vp, vp]
     lib.kfac_invert_batch.restype = C.c_int
+    lib.kfac_invert_batch_packed.argtypes = [vp, C.c_int, i32p, fpp, fpp, vp, C.c_float, vp, vp]
+    lib.kfac_invert_batch_packed.restype = C.c_int
     lib.kfac_check_info.argtypes = [vp, C.c_int, vp, i32p, vp]
     lib.kfac_check_info.restype = C.c_int
     lib.kfac_precondition.argtypes = [vp, C.c_int, i32p, i32p, fpp, fpp, fpp, fpp, vp]
@@ -217,6 +219,15 @@ class Context:
         n = len(dims)
         st = self.lib.kfac_invert_batch(self.h, n, _i32_array(dims) if n else None, _ptr_array(F, n),
                                         _ptr_array(X, n), float(gamma), _ptr(info), _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def kfac_invert_batch_packed(self, dims, F, X, packed, gamma: float, info=None, stream=None, check: bool = True) -> int:
+        n = len(dims)
+        st = self.lib.kfac_invert_batch_packed(self.h, n, _i32_array(dims) if n else None, _ptr_array(F, n),
+                                               _ptr_array(X, n), _ptr(packed), float(gamma), _ptr(info),
+                                               _stream_handle(stream))
         if check:
             self._check(st)
         return st

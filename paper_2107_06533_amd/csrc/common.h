@@ -135,6 +135,7 @@ struct InvMat {
   float* Q;         // inverse pivot block [NB][NB]
   float* QB;        // sub-matrix views: full symmetric inverse of the swept view, [d][ldp]
   int32_t* info;    // may be null
+  float* P;         // whole matrices only, may be null: packed upper triangle of the result, d(d+1)/2 floats
   int32_t d, ld, ldp;
   int32_t info_base;   // row of the whole matrix at which this view starts
   uint32_t xelems;     // floats from X to the end of the allocation behind it (buffer range checks)

@@ -326,6 +326,8 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
       const float v = S[i0 + 2 * u >= j ? la : lb];
       if (small) {
         buf_store(rs_out, offx, -v);
+        const int i = i0 + 2 * u;
+        if (Mx.P && j >= i) Mx.P[(size_t)i * d - (size_t)i * (i - 1) / 2 + (j - i)] = -v;
       } else {
         buf_store(rs_q, offq, -v);
         buf_store(rs_out, offx, v);
@@ -343,6 +345,7 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
       const float v = i >= jj ? S[i * SP + jj] : S[jj * SP + i];
       if (small) {
         if (in) X[(size_t)i * ld + jj] = -v;
+        if (in && Mx.P && jj >= i) Mx.P[(size_t)i * d - (size_t)i * (i - 1) / 2 + (jj - i)] = -v;
       } else {
         Q[i * NB + jj] = in ? -v : 0.f;
         if (in) X[(size_t)(k0 + i) * ld + k0 + jj] = v;
@@ -518,6 +521,8 @@ __global__ __launch_bounds__(NT) void gj_finish_kernel(const InvMat* __restrict_
     const int lj = ty + 8 * r;             // row of the mirrored tile = column index of the source
     const int j = j0 + lj, i = i0 + tx;    // writes X[j][i] = X[i][j], i > j
     if (i < d && j < d && i > j) Mx.X[(size_t)j * d + i] = tile[tx][lj];
+    // packed upper triangle, row j: element (j, i), i >= j, at j*d - j(j-1)/2 + (i - j)
+    if (Mx.P && i < d && j < d && i >= j) Mx.P[(size_t)j * d - (size_t)j * (j - 1) / 2 + (i - j)] = tile[tx][lj];
   }
 }
 

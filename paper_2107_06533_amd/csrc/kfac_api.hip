@@ -1057,8 +1057,10 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
 }
 
 // ----------------------------------------------------------------------------------- inverse
-kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const float* const* F,
-                              float* const* X, float gamma, int32_t* info_dev, void* hip_stream) {
+// kfac_invert_batch and kfac_invert_batch_packed: `packed` (may be NULL) additionally receives the
+// packed upper triangles of the inverses, written by the kernels that write the inverses.
+static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, const float* const* F,
+                                     float* const* X, float gamma, int32_t* info_dev, float* packed, void* hip_stream) {
   if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: ctx is NULL");
   if (n < 0) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch: n_mats < 0");
   if (n == 0) return KFAC_OK;
@@ -1164,6 +1166,8 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   }
   if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
 
+  std::vector<size_t> packed_off(n, 0);   // float offset of matrix i's triangle in `packed`
+  for (int i = 1; i < n; ++i) packed_off[i] = packed_off[i - 1] + size_t(dims[i - 1]) * (size_t(dims[i - 1]) + 1) / 2;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   kfac_status st = ensure_ws(ctx, WS_INVERT, P.ws_floats * sizeof(float));
   if (st != KFAC_OK) return st;
@@ -1208,6 +1212,7 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
       InvMat& M = hm[m];
       M.F = F[o]; M.X = X[o]; M.d = M.ld = dims[o];
       M.info = info_dev ? info_dev + o : nullptr;
+      M.P = packed ? packed + packed_off[o] : nullptr;
       M.xelems = uint32_t(M.d) * uint32_t(M.d);
       M.ldp = NB;
       if (m >= Gp.n_large) continue;
@@ -1409,6 +1414,17 @@ kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const f
   }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
+}
+
+kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const float* const* F,
+                              float* const* X, float gamma, int32_t* info_dev, void* hip_stream) {
+  return invert_batch_impl(ctx, n, dims, F, X, gamma, info_dev, nullptr, hip_stream);
+}
+
+kfac_status kfac_invert_batch_packed(kfac_ctx* ctx, int n, const int32_t* dims, const float* const* F,
+                                     float* const* X, float* packed, float gamma, int32_t* info_dev, void* hip_stream) {
+  if (ctx && n > 0 && !packed) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_invert_batch_packed: packed is NULL");
+  return invert_batch_impl(ctx, n, dims, F, X, gamma, info_dev, packed, hip_stream);
 }
 
 // ----------------------------------------------------------------------------- placement

@@ -73,6 +73,11 @@ def test_invert_validation(hctx):
     assert call(X=(1,)) == pk.KFAC_ERR_INVALID_ARG            # aliasing
     assert call(F=(None,)) == pk.KFAC_ERR_INVALID_ARG
     assert hctx.kfac_invert_batch([], None, None, 0.1) == pk.KFAC_OK
+    # the variant with a packed second output: same checks, and the buffer is required
+    assert hctx.kfac_invert_batch_packed([3], [1], [2], 5, 0.1, check=False) == pk.KFAC_ERR_DEVICE
+    assert hctx.kfac_invert_batch_packed([3], [1], [2], None, 0.1, check=False) == pk.KFAC_ERR_INVALID_ARG
+    assert hctx.kfac_invert_batch_packed([0], [1], [2], 5, 0.1, check=False) == pk.KFAC_ERR_INVALID_ARG
+    assert hctx.kfac_invert_batch_packed([], None, None, None, 0.1) == pk.KFAC_OK
 
 
 def test_precondition_validation(hctx):

@@ -375,6 +375,29 @@ def test_packed_round_trip_of_a_whole_factor_set(ctx):
         assert torch.equal(packed[o:o + d * (d + 1) // 2], M[iu[0], iu[1]]), f"d={d}"
 
 
+def test_invert_batch_packed_output(ctx):
+    """kfac_invert_batch_packed: the packed triangles written with the inverses are, bit for bit, the
+    oracle's packing of the inverses the same call returns, and those meet the usual bar."""
+    import torch
+    dims = [1, 3, 31, 33, 64, 128, 129, 257, 300, 641, 1025]
+    gamma = 0.03
+    Fs = [spd(d, d + 7, 5.0) + 0.5 * np.eye(d) for d in dims]
+    F_d = [dev(F.astype(np.float32)) for F in Fs]
+    X_d = [torch.full_like(f, float("nan")) for f in F_d]
+    tot, off = ctx.packed_elems(dims)
+    packed = torch.full((tot,), float("nan"), device="cuda")
+    info = torch.full((len(dims),), -7, dtype=torch.int32, device="cuda")
+    ctx.kfac_invert_batch_packed(dims, F_d, X_d, packed, gamma, info)
+    torch.cuda.synchronize()
+    assert int(info.abs().sum()) == 0
+    got = packed.cpu().numpy()
+    for d, Fd, Xd, o in zip(dims, F_d, X_d, off):
+        X32 = Xd.cpu().numpy()
+        assert np.array_equal(got[o:o + oracle.packed_size(d)], oracle.pack_upper(X32)), f"d={d}: packed != pack_upper(X)"
+        assert inv_residual(host64(Fd), gamma, X32.astype(np.float64)) <= TOL_INVERSE, f"d={d}"
+    assert ctx.kfac_invert_batch_packed(dims, F_d, X_d, None, gamma, info, check=False) == 1   # packed is required
+
+
 # ------------------------------------------------------------------------------ stale inverses
 def test_precondition_with_last_inverses_while_inverting(ctx):
     """Inverse update interval > 1 on one GPU: the new inverses are computed on one stream while the
