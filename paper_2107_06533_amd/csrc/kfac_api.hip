@@ -785,9 +785,11 @@ PrecondSchedule schedule_precond(int n, const int32_t* dG, const int32_t* dA) {
       for (int bj = 0; bj < Tn; ++bj) {
         const int ab = active_blocks(dG[l], dA[l], bi, bj, false);
         TileJob j{};
-        j.bi = bi; j.bj = bj; j.kbeg = 0; j.part = -1;
+        j.kbeg = 0; j.part = -1;
+        j.bi = bj; j.bj = bi;              // first product: the intermediate is written transposed, [dA, dG]
         j.desc = 2 * l; j.kend = dG[l];
         t1.push_back({j, int64_t(dG[l]) * ab});
+        j.bi = bi; j.bj = bj;
         j.desc = 2 * l + 1; j.kend = dA[l];
         t2.push_back({j, int64_t(dA[l]) * ab});
         S.stats.mfma_flops += (int64_t(ceil_div(dG[l], KC)) + ceil_div(dA[l], KC)) * KC * ab * 32 * 32 * 2;
@@ -1612,15 +1614,15 @@ kfac_status kfac_precondition(kfac_ctx* ctx, int n, const int32_t* dG, const int
   float* wsf = static_cast<float*>(ctx->ws[WS_PRECOND]);
   for (int l = 0; l < n; ++l) {
     float* T = wsf + P.t_off[l];
-    TileDesc& D1 = descs[2 * l];       // T = Ginv . V : a(k, i) = Ginv[i][k]
+    TileDesc& D1 = descs[2 * l];       // T^T = V^T . Ginv^T : a(k, j) = V[k][j], b(k, i) = Ginv[i][k]
     D1 = TileDesc{};
-    D1.a = transposed_operand(Ginv[l], dG[l], dG[l]);
-    D1.b = rowmajor_operand(gradW[l], dG[l], dA[l], dA[l]);
-    D1.out = T; D1.ldo = dA[l]; D1.M = dG[l]; D1.N = dA[l];
+    D1.a = rowmajor_operand(gradW[l], dG[l], dA[l], dA[l]);
+    D1.b = transposed_operand(Ginv[l], dG[l], dG[l]);
+    D1.out = T; D1.ldo = dG[l]; D1.M = dA[l]; D1.N = dG[l];
     D1.sym = 0; D1.mirror = MIRROR_NONE; D1.alpha = 1.f; D1.beta = 0.f;
-    TileDesc& D2 = descs[2 * l + 1];   // out = T . Ainv
+    TileDesc& D2 = descs[2 * l + 1];   // out = T . Ainv : a(k, i) = T^T[k][i], b(k, j) = Ainv[k][j], both as stored
     D2 = TileDesc{};
-    D2.a = transposed_operand(T, dA[l], dG[l]);
+    D2.a = rowmajor_operand(T, dA[l], dG[l], dG[l]);
     D2.b = rowmajor_operand(Ainv[l], dA[l], dA[l], dA[l]);
     D2.out = out[l]; D2.ldo = dA[l]; D2.M = dG[l]; D2.N = dA[l];
     D2.sym = 0; D2.mirror = MIRROR_NONE; D2.alpha = 1.f; D2.beta = 0.f;

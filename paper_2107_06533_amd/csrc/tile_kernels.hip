@@ -41,10 +41,10 @@ __global__ __launch_bounds__(NT, 2) void tile_gemm_kernel(const TileDesc* __rest
   const TileJob J = jobs[g];
   if (J.desc < 0) return;   // padding of an XCD segment
   const TileDesc& D = descs[J.desc];
-  if (D.a.type == OP_KMAJOR)
+  if (D.b.type == OP_KMAJOR)
     run_tile<KMajorLoader, KMajorLoader, true>(D, J, smem);
   else
-    run_tile<ConvLoader<1, 1>, KMajorLoader, true>(D, J, smem);
+    run_tile<KMajorLoader, ConvLoader<1, 1>, true>(D, J, smem);   // second operand stored [N, K] (read transposed)
 }
 
 // out = beta*out + alpha * (partial[part0] + partial[part0+1] + ...) in slot order (deterministic).
