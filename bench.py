@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--fit-inverse-model", action="store_true",
                     help="instead of the step benchmark: time kfac_invert_batch on single matrices d = 64 .. 8192 "
                          "(10 warm-up + 100 runs each) and fit t = alpha_inv * exp(beta_inv * d)")
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
+                    help="set a tuning option of the context (kfac_set_option; names in paper_2107_06533_amd.OPTIONS), for A/B runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy (reference dispatch for scaling rocprofv3 byte counters)")
     return ap.parse_args()
@@ -165,6 +167,9 @@ def main():
     setup_s = time.perf_counter() - t0
 
     ctx = pk.Context(0)
+    for kv in args.opt:
+        name, _, val = kv.partition("=")
+        ctx.set_option(name, int(val))
     stream = torch.cuda.current_stream()
 
     def step():
@@ -209,8 +214,7 @@ def main():
             call_ms[k] += e[k].elapsed_time(e[k + 1]) / args.steps
     dom_ms, dom_n = ctx.timing_read("factor_tiles")
     ctx.timing_enable([])
-    if not os.environ.get("KFAC_BENCH_NOCHECK"):
-        assert int(info.abs().sum()) == 0, "a factor was reported not positive definite"
+    assert int(info.abs().sum()) == 0, "a factor was reported not positive definite"
     assert dom_n == args.steps
 
     # ---- per-kernel breakdown (extra, untimed pass with every kernel class bracketed)

@@ -29,7 +29,8 @@
  *   - Arithmetic is fp32 throughout (fp32 MFMA, fp32 accumulation).
  *   - Limits (checked, KFAC_ERR_INVALID_ARG): every activation / gradient tensor holds at
  *     most 2^28 elements (1 GiB; operands are addressed with 32-bit byte offsets), convolution
- *     windows have at most 63 taps, matrices to invert have d <= 16384.
+ *     windows have at most 63 taps, every factor dimension (dA, dG, the d of a matrix to invert or
+ *     to precondition with) is at most 16384.
  *   - kfac_invert_batch also launches on internal streams of the context (default priority),
  *     forked from and joined back into `hip_stream` with events before the call returns; the
  *     work is complete when `hip_stream` is.  The first call for a new set of shapes builds and
@@ -76,6 +77,30 @@ typedef struct {
 kfac_status kfac_create(kfac_ctx** out, int device);
 void kfac_destroy(kfac_ctx* ctx);
 const char* kfac_last_error(const kfac_ctx* ctx); /* never NULL; ctx may be NULL */
+
+/*
+ * Tuning options of a context.  They change how the work is scheduled (launch structure, summation
+ * order inside the stated tolerances), never what is computed; the defaults are the measured best on
+ * the benchmark workloads.  A context reads no environment variable.  Setting an option discards the
+ * cached schedules of the context (the next call of each kind plans again); set options between
+ * calls, not while work of this context is in flight.
+ * Returns INVALID_ARG for a NULL ctx, an unknown option or a value outside the stated range.
+ */
+typedef enum {
+  KFAC_OPT_INV_GROUPS = 0,    /* 1..4   [2]     groups of matrices kfac_invert_batch sweeps concurrently           */
+  KFAC_OPT_INV_AGG = 1,       /* 1..16  [4]     pivot blocks per outer block, throughput-bound group               */
+  KFAC_OPT_INV_AGG_CHAIN = 2, /* 1..16  [6]     the same for a group bound by its chain of dependent launches      */
+  KFAC_OPT_INV_FUSE = 3,      /* 0/1    [1]     pivot block applies the previous block's update to itself          */
+  KFAC_OPT_INV_SIDE_PAD = 4,  /* 0..65536 [16384] bytes of unused LDS added to off-chain products (occupancy)      */
+  KFAC_OPT_FACTOR_LAG = 5,    /* 0/1    [1]     3x3/stride 1/pad 1 activation factors from products over pixel lags */
+  KFAC_OPT_FACTOR_VEC11 = 6,  /* 0/1    [1]     128-bit loads for 1x1 windows over whole images                    */
+  KFAC_OPT_FACTOR_XCD = 7,    /* 0/1    [0]     factor jobs dealt to the 8 XCDs in contiguous segments             */
+  KFAC_OPT_FACTOR_KJOB = 8,   /* 32..8192 [8192] longest run of rows one factor tile job accumulates               */
+  KFAC_OPT_INV_CHAIN_PAD = 9, /* 0..65536 [0]   bytes of unused LDS added to the chain kernels of such a group              */
+  KFAC_OPT_COUNT = 10
+} kfac_option;
+kfac_status kfac_set_option(kfac_ctx* ctx, int option, int value);
+kfac_status kfac_get_option(const kfac_ctx* ctx, int option, int* value);
 
 /* Factor dimensions implied by a layer (pure host). Return 0 for an invalid layer. */
 int32_t kfac_layer_dA(const kfac_layer* layer);

@@ -17,7 +17,12 @@ EXPORTS = [
     "kfac_update_factors", "kfac_invert_batch", "kfac_invert_batch_packed", "kfac_check_info", "kfac_precondition",
     "kfac_packed_elems", "kfac_pack_triangles", "kfac_unpack_triangles", "kfac_place_inversions",
     "kfac_get_plan_stats", "kfac_timing_enable", "kfac_timing_read",
+    "kfac_set_option", "kfac_get_option",
 ]
+
+# kfac_option, in the order of the header
+OPTIONS = ["inv_groups", "inv_agg", "inv_agg_chain", "inv_fuse", "inv_side_pad",
+           "factor_lag", "factor_vec11", "factor_xcd", "factor_kjob", "inv_chain_pad"]
 
 KERNEL_CLASSES = ["factor_tiles", "factor_reduce", "inv_small", "inv_init", "inv_pivot", "inv_panel",
                   "inv_update", "inv_finish", "precond_left", "precond_right", "tri_pack"]
@@ -108,6 +113,10 @@ def load():
     lib.kfac_timing_enable.restype = None
     lib.kfac_timing_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
     lib.kfac_timing_read.restype = C.c_int
+    lib.kfac_set_option.argtypes = [vp, C.c_int, C.c_int]
+    lib.kfac_set_option.restype = C.c_int
+    lib.kfac_get_option.argtypes = [vp, C.c_int, C.POINTER(C.c_int)]
+    lib.kfac_get_option.restype = C.c_int
     _LIB = lib
     return lib
 
@@ -268,6 +277,18 @@ class Context:
         off = (C.c_int64 * (n + 1))()
         tot = int(self.lib.kfac_packed_elems(n, _i32_array(dims) if n else None, off))
         return tot, [int(v) for v in off]
+
+    def set_option(self, name: str, value: int, check: bool = True) -> int:
+        """name: one of OPTIONS (kfac_option without its prefix, lower case)."""
+        st = self.lib.kfac_set_option(self.h, OPTIONS.index(name), int(value))
+        if check:
+            self._check(st)
+        return st
+
+    def get_option(self, name: str) -> int:
+        v = C.c_int()
+        self._check(self.lib.kfac_get_option(self.h, OPTIONS.index(name), C.byref(v)))
+        return v.value
 
     # -- host-side queries -------------------------------------------------------------------
     def workspace_bytes_factors(self, layers) -> int:

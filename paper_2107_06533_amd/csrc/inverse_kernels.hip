@@ -689,19 +689,19 @@ void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma
   if (njobs <= 0) return;
   hipLaunchKernelGGL(gj_init_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, gamma);
 }
-void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s) {
+void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s, int lds_pad) {
   if (nmats <= 0) return;
-  hipLaunchKernelGGL(gj_pivot_kernel, dim3(nmats), dim3(NT), 0, s, mats, (const MatJob*)jobs, mat0, step, gamma, small);
+  hipLaunchKernelGGL(gj_pivot_kernel, dim3(nmats), dim3(NT), lds_pad, s, mats, (const MatJob*)jobs, mat0, step, gamma, small);
 }
 void launch_gj_pivot_update(const InvMat* mats, const void* pjobs, int npiv, int step, float gamma,
-                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s) {
+                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s, int lds_pad) {
   if (npiv <= 0 && nupd <= 0) return;
-  hipLaunchKernelGGL(gj_pivot_update_kernel, dim3(npiv + nupd), dim3(NT), 0, s, mats, (const MatJob*)pjobs, npiv, step, gamma,
+  hipLaunchKernelGGL(gj_pivot_update_kernel, dim3(npiv + nupd), dim3(NT), lds_pad, s, mats, (const MatJob*)pjobs, npiv, step, gamma,
                      descs, ujobs, nupd);
 }
-void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s) {
+void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s, int lds_pad) {
   if (njobs <= 0) return;
-  hipLaunchKernelGGL(gj_panel_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, step);
+  hipLaunchKernelGGL(gj_panel_kernel, dim3(njobs), dim3(NT), lds_pad, s, mats, (const MatJob*)jobs, njobs, step);
 }
 void launch_gj_qmirror(const InvMat* mats, const void* jobs, int njobs, hipStream_t s) {
   if (njobs <= 0) return;

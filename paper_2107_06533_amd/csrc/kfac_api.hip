@@ -132,13 +132,21 @@ struct kfac_ctx {
   // may run at the same time on different streams
   void* ws[3] = {nullptr, nullptr, nullptr};
   size_t ws_cap[3] = {0, 0, 0};
-  int kjob = MAX_JOB_ROWS;                // longest contraction run of one factor tile job (rows)
-  int inv_groups = 2;                     // matrix groups swept concurrently
-  int inv_agg = 4;                        // pivot blocks per aggregated (rank agg*128) update
-  int inv_agg_chain = 6;                  // the same for a latency-bound group (fewer outer steps on the critical path)
-  int inv_side_pad = 16384;               // extra LDS per workgroup of a latency-bound group's off-chain products: one workgroup
-                                          // per compute unit, so that the chain's kernels always find a free slot
-  int inv_fuse = 1;                       // 1: a pivot block applies the previous block's update to itself (one launch fewer per step)
+  // tuning options (kfac_set_option); the defaults are the measured best for the benchmark workloads
+  int opt[KFAC_OPT_COUNT] = {
+      /* INV_GROUPS     */ 2,       // lockstep groups of matrices swept concurrently
+      /* INV_AGG        */ 4,       // pivot blocks per outer block (rank agg*128 updates), throughput-bound group
+      /* INV_AGG_CHAIN  */ 6,       // the same for a latency-bound group (fewer outer steps on the critical path)
+      /* INV_FUSE       */ 1,       // a pivot block applies the previous block's update to itself (one launch fewer per step)
+      /* INV_SIDE_PAD   */ 16384,   // unused LDS added to the off-chain products of a latency-bound group: one workgroup
+                                    // per compute unit, so that the chain's kernels always find a free slot
+      /* FACTOR_LAG     */ 1,       // lag products for 3x3 / stride 1 / pad 1 activation factors
+      /* FACTOR_VEC11   */ 1,       // 128-bit loader for 1x1 windows over whole images
+      /* FACTOR_XCD     */ 0,       // XCD-aware arrangement of the factor jobs (measured slower)
+      /* FACTOR_KJOB    */ MAX_JOB_ROWS,   // longest contraction run of one factor tile job (rows)
+      /* INV_CHAIN_PAD  */ 0,       // unused LDS added to the kernels of a latency-bound group's chain: with the side pad,
+                                    // no workgroup of the call shares a compute unit with a chain workgroup
+  };
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
   hipStream_t inv_side[MAX_INV_GROUPS] = {};     // every group's side stream for the off-chain updates
   hipEvent_t inv_fork = nullptr, inv_join[MAX_INV_GROUPS] = {};
@@ -156,6 +164,9 @@ kfac_status fail(kfac_ctx* ctx, kfac_status st, const std::string& msg) {
   if (ctx) ctx->err = msg; else g_noctx_err = msg;
   return st;
 }
+
+struct FactorOpts;
+FactorOpts factor_opts(const kfac_ctx* c);
 
 // Brackets the launches issued during its lifetime with a pair of events (when the class is enabled).
 struct ScopedTiming {
@@ -262,7 +273,12 @@ bool layer_valid(const kfac_layer& L, std::string* why) {
   if (L.has_bias != 0 && L.has_bias != 1) return bad("layer.has_bias must be 0 or 1");
   if (L.c_in < 1 || L.c_out < 1) return bad("layer.c_in and layer.c_out must be positive");
   const int64_t max_elems = (int64_t(1) << 28);   // operands are addressed with 32-bit byte offsets, at most 1 GiB each
+  // factor dimensions: the kernels address a factor with 32-bit byte offsets, and the other two calls
+  // accept matrices up to this order
+  const int64_t max_dim = 16384;
+  if (L.c_out > max_dim) return bad("factor dimension dG exceeds 16384");
   if (L.kind == 0) {
+    if (int64_t(L.c_in) + L.has_bias > max_dim) return bad("factor dimension dA exceeds 16384");
     if (L.rows < 1) return bad("linear layer needs rows >= 1");
     if (int64_t(L.rows) * L.c_in > max_elems || int64_t(L.rows) * L.c_out > max_elems)
       return bad("linear layer tensor exceeds 1 GiB");
@@ -277,7 +293,7 @@ bool layer_valid(const kfac_layer& L, std::string* why) {
   const int64_t lim = (int64_t(1) << 31) - 1;
   if (int64_t(L.n) * oh * ow > lim) return bad("conv rows n*oh*ow exceed 2^31-1");
   if (int64_t(L.c_in) * L.h * L.w > lim || int64_t(L.c_out) * oh * ow > lim) return bad("one sample exceeds 2^31-1 elements");
-  if (int64_t(L.c_in) * L.kh * L.kw + 1 > (1 << 20)) return bad("factor dimension exceeds 2^20");
+  if (int64_t(L.c_in) * L.kh * L.kw + L.has_bias > max_dim) return bad("factor dimension dA exceeds 16384");
   if (int64_t(L.n) * L.c_in * L.h * L.w > max_elems || int64_t(L.n) * L.c_out * oh * ow > max_elems)
     return bad("conv layer tensor exceeds 1 GiB");
   return true;
@@ -288,12 +304,13 @@ int conv_ow(const kfac_layer& L) { return (L.w + 2 * L.pad_w - L.kw) / L.stride 
 int64_t rows_of(const kfac_layer& L) { return L.kind == 0 ? L.rows : int64_t(L.n) * conv_oh(L) * conv_ow(L); }
 int dA_of(const kfac_layer& L) { return (L.kind == 0 ? L.c_in : L.c_in * L.kh * L.kw) + L.has_bias; }
 
-bool vec_enabled() {
-  static const bool on = [] { const char* e = std::getenv("KFAC_VEC11"); return !(e && e[0] == '0'); }();
-  return on;
-}
+// The options that shape a factor schedule.
+struct FactorOpts {
+  int kjob = MAX_JOB_ROWS;
+  bool lag = true, vec = true, xcd = false;
+};
 
-Operand act_operand(const kfac_layer& L) {
+Operand act_operand(const kfac_layer& L, bool vec) {
   Operand o{};
   o.K = int32_t(rows_of(L));
   o.M = dA_of(L);
@@ -305,7 +322,7 @@ Operand act_operand(const kfac_layer& L) {
     return o;
   }
   o.bytes = uint32_t(int64_t(L.n) * L.c_in * L.h * L.w * 4);
-  if (L.kh == 1 && L.kw == 1 && L.pad_h == 0 && L.pad_w == 0) o.type = (L.stride == 1 && vec_enabled() && (L.h * L.w) % 4 == 0) ? OP_CONV11V : OP_CONV11;
+  if (L.kh == 1 && L.kw == 1 && L.pad_h == 0 && L.pad_w == 0) o.type = (L.stride == 1 && vec && (L.h * L.w) % 4 == 0) ? OP_CONV11V : OP_CONV11;
   else if (L.kh == 3 && L.kw == 3) o.type = OP_CONV33;
   else if (L.kh == 7 && L.kw == 7) o.type = OP_CONV77;
   else o.type = OP_CONVGEN;
@@ -316,7 +333,7 @@ Operand act_operand(const kfac_layer& L) {
   return o;
 }
 
-Operand gout_operand(const kfac_layer& L) {
+Operand gout_operand(const kfac_layer& L, bool vec) {
   Operand o{};
   o.K = int32_t(rows_of(L));
   o.M = L.c_out;
@@ -330,7 +347,7 @@ Operand gout_operand(const kfac_layer& L) {
   o.bytes = uint32_t(o.K * int64_t(L.c_out) * 4);
   // [n, c_out, oh, ow] read through a 1x1 window: k = (n, oy, ox), m = channel
   o.C = L.c_out; o.H = conv_oh(L); o.W = conv_ow(L); o.OH = o.H; o.OW = o.W;
-  o.type = (vec_enabled() && (o.H * o.W) % 4 == 0) ? OP_CONV11V : OP_CONV11;
+  o.type = (vec && (o.H * o.W) % 4 == 0) ? OP_CONV11V : OP_CONV11;
   o.stride = 1; o.pad_h = o.pad_w = 0; o.KH = 1; o.KW = 1;
   o.dOW = make_fastdiv(uint32_t(o.OW));
   o.dOHW = make_fastdiv(uint32_t(o.OH) * uint32_t(o.OW));
@@ -391,13 +408,6 @@ std::vector<TileJob> xcd_arrange(const std::vector<std::vector<TileJob>>& groups
   return out;
 }
 
-bool xcd_enabled() {
-  // off by default: with jobs sorted longest first, dealing contiguous segments to the XCDs measured
-  // 2 % slower on the ResNet-50 set than plain index order
-  static const bool on = std::getenv("KFAC_XCD") && std::atoi(std::getenv("KFAC_XCD")) != 0;
-  return on;
-}
-
 // ------------------------------------------------------------------------------- factor plan
 void release(FactorPlan& p) {
   free_dev(p.d_jobs); free_dev(p.d_rjobs); free_dev(p.d_ljobs); free_table(p.tab);
@@ -441,12 +451,8 @@ struct FactorSchedule {
 // Activation factors of 3x3 / stride 1 / pad 1 convolutions with enough channels are built from
 // lag products (about a third of the multiply-adds of the patch-matrix product, see LagAsm).
 constexpr int LAG_MIN_C = 64;
-bool lag_enabled() {
-  static const bool on = [] { const char* e = std::getenv("KFAC_LAG"); return !(e && e[0] == '0'); }();
-  return on;
-}
 bool lag_eligible(const kfac_layer& L) {
-  return lag_enabled() && L.kind == 1 && L.kh == 3 && L.kw == 3 && L.stride == 1 && L.pad_h == 1 && L.pad_w == 1 && L.c_in >= LAG_MIN_C;
+  return L.kind == 1 && L.kh == 3 && L.kw == 3 && L.stride == 1 && L.pad_h == 1 && L.pad_w == 1 && L.c_in >= LAG_MIN_C;
 }
 
 // View of the activations through a KH x KW window of lags over the pixel window [y0, y1] x [x0, x1]
@@ -465,7 +471,8 @@ Operand lag_operand(const kfac_layer& L, int type, int KH, int KW, int pad_h, in
   return o;
 }
 
-FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vector<uint8_t>& present, int kjob) {
+FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vector<uint8_t>& present, const FactorOpts& O) {
+  const int kjob = O.kjob;
   FactorSchedule S;
   S.desc_of.assign(2 * n, -1);
   for (int l = 0; l < n; ++l)
@@ -473,7 +480,7 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
       if (!present[2 * l + which]) continue;
       S.desc_of[2 * l + which] = int(S.descs.size());
       const kfac_layer& L = layers[l];
-      if (which == 0 && lag_eligible(L)) {
+      if (which == 0 && O.lag && lag_eligible(L)) {
         LagLayer lg;
         lg.layer = l; lg.desc0 = int(S.descs.size());
         const int H = L.h, W = L.w, b = L.has_bias;
@@ -483,7 +490,7 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
         for (int k = 0; k < LAG_NMAT; ++k) {
           TileDesc D{};
           const int* w = win[k];
-          const bool whole = k <= LAG_G2 && vec_enabled() && (H * W) % 4 == 0;   // whole images: four pixels per load
+          const bool whole = k <= LAG_G2 && O.vec && (H * W) % 4 == 0;   // whole images: four pixels per load
           D.a = lag_operand(L, whole ? OP_CONV11V : OP_CONV11, 1, 1, 0, 0, 0, w[0], w[1], w[2], w[3]);
           if (k == LAG_G1) D.b = lag_operand(L, OP_CONV25, 2, 5, -1, 2, 0, w[0], w[1], w[2], w[3]);
           else if (k == LAG_G2) D.b = lag_operand(L, OP_CONV13, 1, 3, 0, 0, b, w[0], w[1], w[2], w[3]);
@@ -508,7 +515,7 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
         continue;
       }
       TileDesc D{};
-      D.a = which == 0 ? act_operand(L) : gout_operand(L);
+      D.a = which == 0 ? act_operand(L, O.vec) : gout_operand(L, O.vec);
       D.b = D.a;
       D.M = D.N = D.ldo = D.a.M;
       D.sym = 1;
@@ -556,7 +563,7 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
   std::stable_sort(groups.begin(), groups.end(), [](const Group& x, const Group& y) { return x.job_cost > y.job_cost; });
   std::vector<std::vector<TileJob>> lists;
   for (auto& g : groups) lists.push_back(std::move(g.jobs));
-  if (xcd_enabled()) {
+  if (O.xcd) {
     S.jobs = xcd_arrange(lists);
   } else {
     for (auto& l : lists) S.jobs.insert(S.jobs.end(), l.begin(), l.end());
@@ -808,6 +815,15 @@ PrecondSchedule schedule_precond(int n, const int32_t* dG, const int32_t* dA) {
 
 bool finite_in(float v, float lo, float hi) { return v >= lo && v <= hi; }
 
+FactorOpts factor_opts(const kfac_ctx* c) {
+  FactorOpts O;
+  O.kjob = c->opt[KFAC_OPT_FACTOR_KJOB];
+  O.lag = c->opt[KFAC_OPT_FACTOR_LAG] != 0;
+  O.vec = c->opt[KFAC_OPT_FACTOR_VEC11] != 0;
+  O.xcd = c->opt[KFAC_OPT_FACTOR_XCD] != 0;
+  return O;
+}
+
 }  // namespace
 
 // =================================================================================== C ABI
@@ -820,24 +836,6 @@ kfac_status kfac_create(kfac_ctx** out, int device) {
   kfac_ctx* c = new kfac_ctx();
   c->device = device;
   c->host_only = device < 0;
-  if (const char* e = std::getenv("KFAC_INV_GROUPS")) {
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= MAX_INV_GROUPS) c->inv_groups = v;
-  }
-  if (const char* e = std::getenv("KFAC_INV_AGG")) {
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= 16) c->inv_agg = c->inv_agg_chain = v;
-  }
-  if (const char* e = std::getenv("KFAC_INV_AGG_CHAIN")) {
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= 16) c->inv_agg_chain = v;
-  }
-  if (const char* e = std::getenv("KFAC_SIDE_PAD")) c->inv_side_pad = std::max(0, std::atoi(e));
-  if (const char* e = std::getenv("KFAC_INV_FUSE")) c->inv_fuse = std::atoi(e) != 0;
-  if (const char* e = std::getenv("KFAC_KJOB")) {
-    const int v = std::atoi(e);
-    if (v >= KC) c->kjob = std::min(v, MAX_JOB_ROWS);
-  }
   if (!c->host_only) {
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || device >= count) {
@@ -879,7 +877,7 @@ size_t kfac_workspace_bytes_factors(const kfac_ctx* ctx, int n, const kfac_layer
   for (int l = 0; l < n; ++l)
     if (!layer_valid(layers[l], nullptr)) return 0;
   std::vector<uint8_t> present(2 * n, 1);
-  return size_t(schedule_factors(n, layers, present, ctx ? ctx->kjob : 8192).stats.ws_bytes);
+  return size_t(schedule_factors(n, layers, present, ctx ? factor_opts(ctx) : FactorOpts{}).stats.ws_bytes);
 }
 
 size_t kfac_workspace_bytes_invert(const kfac_ctx* ctx, int n, const int32_t* dims) {
@@ -887,8 +885,8 @@ size_t kfac_workspace_bytes_invert(const kfac_ctx* ctx, int n, const int32_t* di
   for (int i = 0; i < n; ++i)
     if (dims[i] < 1) return 0;
   // independent of how the matrices are grouped, but not of the outer block size a group gets: the larger of the two
-  const size_t a = size_t(schedule_invert(n, dims, ctx ? ctx->inv_agg : 4).stats.ws_bytes);
-  const size_t b = size_t(schedule_invert(n, dims, ctx ? ctx->inv_agg_chain : 6).stats.ws_bytes);
+  const size_t a = size_t(schedule_invert(n, dims, ctx ? ctx->opt[KFAC_OPT_INV_AGG] : 4).stats.ws_bytes);
+  const size_t b = size_t(schedule_invert(n, dims, ctx ? ctx->opt[KFAC_OPT_INV_AGG_CHAIN] : 6).stats.ws_bytes);
   return std::max(a, b);
 }
 
@@ -897,6 +895,29 @@ size_t kfac_workspace_bytes_precondition(const kfac_ctx*, int n, const int32_t* 
   for (int i = 0; i < n; ++i)
     if (dG[i] < 1 || dA[i] < 1) return 0;
   return size_t(schedule_precond(n, dG, dA).stats.ws_bytes);
+}
+
+kfac_status kfac_set_option(kfac_ctx* ctx, int option, int value) {
+  if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_set_option: ctx is NULL");
+  static const int lo[KFAC_OPT_COUNT] = {1, 1, 1, 0, 0, 0, 0, 0, KC, 0};
+  static const int hi[KFAC_OPT_COUNT] = {MAX_INV_GROUPS, 16, 16, 1, 65536, 1, 1, 1, MAX_JOB_ROWS, 65536};
+  if (option < 0 || option >= KFAC_OPT_COUNT) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_set_option: unknown option");
+  if (value < lo[option] || value > hi[option])
+    return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_set_option: value " + std::to_string(value) + " outside [" +
+                                               std::to_string(lo[option]) + ", " + std::to_string(hi[option]) + "]");
+  if (ctx->opt[option] == value) return KFAC_OK;
+  ctx->opt[option] = value;
+  // cached schedules were built under the old value: the next call of each kind plans again
+  ctx->fp.valid = false;
+  ctx->ip.valid = false;
+  return KFAC_OK;
+}
+
+kfac_status kfac_get_option(const kfac_ctx* ctx, int option, int* value) {
+  if (!ctx || !value || option < 0 || option >= KFAC_OPT_COUNT)
+    return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_get_option: bad arguments");
+  *value = ctx->opt[option];
+  return KFAC_OK;
 }
 
 void kfac_get_plan_stats(const kfac_ctx* ctx, int which, kfac_plan_stats* out) {
@@ -967,7 +988,7 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
                     std::memcmp(P.layers.data(), layers, sizeof(kfac_layer) * n) == 0;
   DeviceGuard guard(ctx);
   if (!same) {
-    FactorSchedule S = schedule_factors(n, layers, present, ctx->kjob);
+    FactorSchedule S = schedule_factors(n, layers, present, factor_opts(ctx));
     if (!ctx->host_only) {
       HIP_TRY(ctx, hipDeviceSynchronize());
       release(P);
@@ -1047,7 +1068,7 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
   const LagAsm* d_asms = reinterpret_cast<const LagAsm*>(static_cast<const unsigned char*>(P.tab.dev) + descs_bytes);
   {
     ScopedTiming tm(ctx, KFAC_K_FACTOR_TILES, s);
-    launch_tile_any(d_descs, static_cast<const TileJob*>(P.d_jobs), P.njobs, xcd_enabled() ? 1 : 0, s);
+    launch_tile_any(d_descs, static_cast<const TileJob*>(P.d_jobs), P.njobs, ctx->opt[KFAC_OPT_FACTOR_XCD] ? 1 : 0, s);
   }
   if (P.nrjobs || P.nljobs) {
     ScopedTiming tm(ctx, KFAC_K_FACTOR_REDUCE, s);
@@ -1101,7 +1122,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
       if (dims[i] > NB) { ++n_large; max_nblk = std::max(max_nblk, ceil_div(dims[i], NB)); }
     auto is_long = [&](int i) { return dims[i] > NB && 5 * ceil_div(dims[i], NB) > 3 * max_nblk; };
     for (int i = 0; i < n; ++i) n_long += is_long(i);
-    const int G = std::max(1, std::min(ctx->inv_groups, n_large));
+    const int G = std::max(1, std::min(ctx->opt[KFAC_OPT_INV_GROUPS], n_large));
     const bool split = G >= 2 && n_long > 0 && n_long < n_large;   // otherwise: plain balancing over all groups
     P.groups.assign(G, InvertGroup{});
     std::vector<double> load(G, 0.0);
@@ -1129,12 +1150,12 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
         for (int32_t d : gd) {
           if (d <= NB) continue;
           flops += double(d) * d * d;
-          chain = std::max(chain, ceil_div(d, NB) * 90e-6 + inv_nob(d, ctx->inv_agg) * 300e-6);
+          chain = std::max(chain, ceil_div(d, NB) * 90e-6 + inv_nob(d, ctx->opt[KFAC_OPT_INV_AGG]) * 300e-6);
         }
         Gp.latency_bound = chain > flops / 100e12;
-        Gp.agg = Gp.latency_bound ? ctx->inv_agg_chain : ctx->inv_agg;
+        Gp.agg = Gp.latency_bound ? ctx->opt[KFAC_OPT_INV_AGG_CHAIN] : ctx->opt[KFAC_OPT_INV_AGG];
       }
-      InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), Gp.agg, ctx->inv_fuse != 0);
+      InvertSchedule S = schedule_invert(int(gd.size()), gd.data(), Gp.agg, ctx->opt[KFAC_OPT_INV_FUSE] != 0);
       Gp.order = S.order; Gp.n_large = S.n_large; Gp.n_small = S.n_small; Gp.n_ob = S.n_ob; Gp.n_views = S.n_views;
       Gp.view_off = S.view_off; Gp.n_in_ob = S.n_in_ob; Gp.sub_pivot_off = S.sub_pivot_off;
       Gp.sub_panel_off = S.sub_panel_off; Gp.sub_upd_off = S.sub_upd_off;
@@ -1313,7 +1334,8 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
       if (b >= Gp.n_ob) continue;
       hipStream_t gs = gstream(g), side = ctx->inv_side[g];
       const InvMat* views = d_views[g];
-      const int side_pad = Gp.latency_bound ? ctx->inv_side_pad : 0;
+      const int side_pad = Gp.latency_bound ? ctx->opt[KFAC_OPT_INV_SIDE_PAD] : 0;
+      const int chain_pad = Gp.latency_bound ? ctx->opt[KFAC_OPT_INV_CHAIN_PAD] : 0;
       const int aw = Gp.agg + 1;
       // Sweep of the diagonal sub-matrices: pivot block t, its panel, then ONE launch holding both
       // the update by block t of every tile but the next pivot block and the sweep of pivot block
@@ -1322,25 +1344,25 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
         const int stp = b * aw + t;
         const int npiv = Gp.sub_pivot_off[stp + 1] - Gp.sub_pivot_off[stp];
         if (npiv == 0) break;
-        if (t == 0 || !ctx->inv_fuse) {
+        if (t == 0 || !ctx->opt[KFAC_OPT_INV_FUSE]) {
           ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
-          launch_gj_pivot(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp], 0, npiv, t, gamma, 0, gs);
+          launch_gj_pivot(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp], 0, npiv, t, gamma, 0, gs, chain_pad);
         }
         if (Gp.sub_panel_off[stp + 1] > Gp.sub_panel_off[stp]) {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
           launch_gj_panel(views, static_cast<const MatJobH*>(Gp.d_sub_panel) + Gp.sub_panel_off[stp],
-                          Gp.sub_panel_off[stp + 1] - Gp.sub_panel_off[stp], t, gs);
+                          Gp.sub_panel_off[stp + 1] - Gp.sub_panel_off[stp], t, gs, chain_pad);
         }
         const int npiv_next = t + 1 < aw ? Gp.sub_pivot_off[stp + 2] - Gp.sub_pivot_off[stp + 1] : 0;
         const int nupd = Gp.sub_upd_off[stp + 1] - Gp.sub_upd_off[stp];
         const TileJob* uj = static_cast<const TileJob*>(Gp.d_sub_upd) + Gp.sub_upd_off[stp];
-        if (ctx->inv_fuse && npiv_next > 0) {
+        if (ctx->opt[KFAC_OPT_INV_FUSE] && npiv_next > 0) {
           ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
           launch_gj_pivot_update(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp + 1], npiv_next, t + 1, gamma,
-                                 d_descs[g], uj, nupd, gs);
+                                 d_descs[g], uj, nupd, gs, chain_pad);
         } else if (nupd > 0) {
           ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, gs);
-          launch_tile_gemm(d_descs[g], uj, nupd, 0, gs);
+          launch_tile_gemm_pad(d_descs[g], uj, nupd, chain_pad, gs);
         }
       }
       const MatJobH* mvj = static_cast<const MatJobH*>(Gp.d_mv);
@@ -1361,7 +1383,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
         HIP_TRY(ctx, hipEventRecord(Gp.ev_gather[b], gs));
         if (bp1 > bp0) {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
-          launch_tile_gemm(d_descs[g], bpj + bp0, bp1 - bp0, 0, gs);
+          launch_tile_gemm_pad(d_descs[g], bpj + bp0, bp1 - bp0, chain_pad, gs);
         }
         if (bp1 > bp0) {   // the chain wrote part of the W panel
           HIP_TRY(ctx, ensure_event(Gp.ev_chain[b]));
@@ -1373,7 +1395,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
       const bool has_rest = Gp.upd_off[UPD_REST][b + 1] > Gp.upd_off[UPD_REST][b];
       if (has_diag) {
         if (last_rest[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_rest[last_rest[g]], 0));
-        upd_launch(g, UPD_DIAG, b, gs);
+        upd_launch(g, UPD_DIAG, b, gs, chain_pad);
       }
       if (!has_panel) continue;
       HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_gather[b], 0));

@@ -11,10 +11,10 @@ void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs,
 void launch_lag_assemble(const LagAsm* lags, const LagJob* jobs, int njobs, hipStream_t s);
 
 void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma, hipStream_t s);
-void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s);
+void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s, int lds_pad = 0);
 void launch_gj_pivot_update(const InvMat* mats, const void* pjobs, int npiv, int step, float gamma,
-                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s);
-void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s);
+                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s, int lds_pad = 0);
+void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s, int lds_pad = 0);
 void launch_gj_qmirror(const InvMat* mats, const void* jobs, int njobs, hipStream_t s);
 void launch_gj_move(const PanelMove* moves, const void* jobs, int njobs, int kchunks, int to_matrix, hipStream_t s);
 void launch_tri_pack(const PackMat* mats, const void* jobs, int njobs, float* packed, int to_full, hipStream_t s);

@@ -150,3 +150,61 @@ def test_place_inversions_matches_the_oracle():
     assert pk.place_inversions([4, 5], 2, -1.0, bi, ab, bb, check=False)[0] == bad
     assert pk.place_inversions([4, 5], 2, ai, bi, ab, bb, 4, check=False)[0] == bad
     assert pk.place_inversions([], 2, ai, bi, ab, bb)[0] == 0
+
+
+def test_factor_dimension_limit(hctx):
+    """A factor wider than 16384 would overflow the kernels' 32-bit byte offsets (d*d*4 >= 2^32 from
+    d = 32768) and could not be inverted or used by kfac_precondition anyway: rejected up front."""
+    call = lambda L: hctx.kfac_update_factors([L], [1], [1], [1], [1], 0.5, check=False)
+    assert call(shapes.linear(32, 16383, 8, 1)) == pk.KFAC_ERR_DEVICE            # dA = 16384: accepted
+    assert call(shapes.linear(32, 16384, 8, 1)) == pk.KFAC_ERR_INVALID_ARG       # dA = 16385
+    assert "dA" in hctx.last_error()
+    assert call(shapes.linear(32, 40000, 8, 1)) == pk.KFAC_ERR_INVALID_ARG       # the overflowing case itself
+    assert call(shapes.linear(32, 8, 16385, 1)) == pk.KFAC_ERR_INVALID_ARG
+    assert "dG" in hctx.last_error()
+    assert call(shapes.conv(1, 4096, 4, 4, 8, 3, 1, 1)) == pk.KFAC_ERR_INVALID_ARG   # 9 * 4096 + 1 columns
+    assert call(shapes.conv(1, 1820, 4, 4, 8, 3, 1, 1)) == pk.KFAC_ERR_DEVICE        # 16381 columns
+    lib = pk.load()
+    s = pk.make_layer(shapes.linear(32, 16384, 8, 1))
+    assert lib.kfac_layer_dA(ctypes.byref(s)) == 0
+
+
+def test_options(hctx):
+    """Options are per context, validated, and read no environment variable."""
+    c = pk.Context(-1)
+    try:
+        defaults = {"inv_groups": 2, "inv_agg": 4, "inv_agg_chain": 6, "inv_fuse": 1, "inv_side_pad": 16384,
+                    "factor_lag": 1, "factor_vec11": 1, "factor_xcd": 0, "factor_kjob": 8192, "inv_chain_pad": 0}
+        assert set(defaults) == set(pk.OPTIONS)
+        for k, v in defaults.items():
+            assert c.get_option(k) == v, k
+        for k, bad in (("inv_groups", 0), ("inv_groups", 5), ("inv_agg", 0), ("inv_agg_chain", 17), ("inv_fuse", 2),
+                       ("inv_side_pad", -1), ("factor_lag", -1), ("factor_kjob", 16), ("factor_kjob", 8193)):
+            assert c.set_option(k, bad, check=False) == pk.KFAC_ERR_INVALID_ARG, (k, bad)
+            assert c.get_option(k) == defaults[k]
+        lib = pk.load()
+        assert lib.kfac_set_option(c.h, 99, 1) == pk.KFAC_ERR_INVALID_ARG
+        assert lib.kfac_set_option(None, 0, 1) == pk.KFAC_ERR_INVALID_ARG
+        c.set_option("inv_groups", 3)
+        assert c.get_option("inv_groups") == 3 and hctx.get_option("inv_groups") == 2     # the other context is untouched
+    finally:
+        c.close()
+
+
+def test_options_change_the_schedule_not_the_environment(hctx, monkeypatch):
+    """The lag-product option changes the factor schedule of a context; environment variables do not."""
+    L = [shapes.conv(2, 64, 8, 8, 16, 3, 1, 1)]
+    monkeypatch.setenv("KFAC_LAG", "0")
+    monkeypatch.setenv("KFAC_INV_GROUPS", "1")
+    c = pk.Context(-1)
+    try:
+        assert c.get_option("factor_lag") == 1 and c.get_option("inv_groups") == 2
+        c.kfac_update_factors(L, [1], [1], [1], [1], 0.5, check=False)
+        with_lag = c.plan_stats(0)
+        c.set_option("factor_lag", 0)
+        c.kfac_update_factors(L, [1], [1], [1], [1], 0.5, check=False)
+        without = c.plan_stats(0)
+        assert with_lag["n_launches"] == 2 and without["n_launches"] == 1
+        assert with_lag["ws_bytes"] > without["ws_bytes"]
+    finally:
+        c.close()

@@ -31,21 +31,27 @@ def ctx(kfac_lib):
     c.close()
 
 
-def gpu_step(ctx, name):
-    """Upload the seeded inputs of a whole configuration and run one step as bench.py does."""
+def upload_inputs(name):
+    """Seeded inputs of a whole configuration, generated on the host and uploaded once."""
     import torch
     hp = shapes.config_hparams(name)
     layers = shapes.config_layers(name)
-    n = len(layers)
     with ThreadPoolExecutor(max_workers=8) as ex:
         ins = list(ex.map(lambda il: inputs.layer_inputs(il[1], hp["cid"], 0, il[0], hp["relu"]), enumerate(layers)))
     up = lambda x: torch.from_numpy(x).cuda()
-    a_d, g_d, v_d = [up(x[0]) for x in ins], [up(x[1]) for x in ins], [up(x[2]) for x in ins]
+    return hp, layers, ins, ([up(x[0]) for x in ins], [up(x[1]) for x in ins], [up(x[2]) for x in ins])
+
+
+def run_step(ctx, hp, layers, dev_inputs):
+    """One step as bench.py issues it, on fresh output buffers (identity factors as the running-average start)."""
+    import torch
+    a_d, g_d, v_d = dev_inputs
+    n = len(layers)
     A_d = [torch.eye(l.dA, device="cuda") for l in layers]
     G_d = [torch.eye(l.dG, device="cuda") for l in layers]
-    XA_d = [torch.empty_like(t) for t in A_d]
-    XG_d = [torch.empty_like(t) for t in G_d]
-    P_d = [torch.empty_like(v) for v in v_d]
+    XA_d = [torch.full_like(t, float("nan")) for t in A_d]
+    XG_d = [torch.full_like(t, float("nan")) for t in G_d]
+    P_d = [torch.full_like(v, float("nan")) for v in v_d]
     info = torch.full((2 * n,), -1, dtype=torch.int32, device="cuda")
     dims = [l.dA for l in layers] + [l.dG for l in layers]
     stream = torch.cuda.current_stream()
@@ -54,7 +60,13 @@ def gpu_step(ctx, name):
     ctx.kfac_precondition([l.dG for l in layers], [l.dA for l in layers], XG_d, XA_d, v_d, P_d, stream=stream)
     torch.cuda.synchronize()
     assert int(info.abs().sum()) == 0, "a factor was reported not positive definite"
-    return hp, layers, ins, dict(A=A_d, G=G_d, XA=XA_d, XG=XG_d, P=P_d, V=v_d)
+    return dict(A=A_d, G=G_d, XA=XA_d, XG=XG_d, P=P_d, V=v_d)
+
+
+def gpu_step(ctx, name):
+    """Upload the seeded inputs of a whole configuration and run one step as bench.py does."""
+    hp, layers, ins, dev_inputs = upload_inputs(name)
+    return hp, layers, ins, run_step(ctx, hp, layers, dev_inputs)
 
 
 def check_layer_against_oracle(i, l, ins_i, hp, out):
@@ -104,15 +116,43 @@ def merge(w, x):
         w[k] = max(w.get(k, 0.0), v)
 
 
-def test_r50_every_layer_against_oracle(ctx):
+@pytest.fixture(scope="module")
+def r50(kfac_lib):
+    return upload_inputs("r50")
+
+
+def test_r50_every_layer_against_oracle(ctx, r50):
     t0 = time.perf_counter()
-    hp, layers, ins, out = gpu_step(ctx, "r50")
-    print(f"\nr50: inputs + GPU step {time.perf_counter() - t0:.1f} s", flush=True)
+    hp, layers, ins, dev_inputs = r50
+    out = run_step(ctx, hp, layers, dev_inputs)
+    print(f"\nr50: GPU step {time.perf_counter() - t0:.1f} s", flush=True)
     worst = {}
     t0 = time.perf_counter()
     for i, l in enumerate(layers):
         merge(worst, check_layer_against_oracle(i, l, ins[i], hp, out))
     print(f"r50: oracle over {len(layers)} layers {time.perf_counter() - t0:.1f} s, worst {worst}", flush=True)
+
+
+@pytest.mark.parametrize("groups", [2, 1])
+def test_r50_step_is_bit_reproducible(kfac_lib, r50, groups):
+    """The whole step run three times on fresh output buffers gives the same bits every time: every
+    sum is taken in a fixed order, and no kernel reads what another stream has not finished writing
+    (kfac_invert_batch orders up to two sweep chains and two side streams with events).  Checked for
+    the default two lockstep groups and for one."""
+    import torch
+    hp, layers, ins, dev_inputs = r50
+    c = kfac_lib.Context(0)
+    try:
+        c.set_option("inv_groups", groups)
+        first = run_step(c, hp, layers, dev_inputs)
+        for rep in range(2):
+            again = run_step(c, hp, layers, dev_inputs)
+            for key in ("A", "G", "XA", "XG", "P"):
+                for i, (x, y) in enumerate(zip(first[key], again[key])):
+                    assert torch.equal(x, y), f"groups={groups} run {rep + 2}: {key}[{i}] ({layers[i].name}) differs from the first run"
+            del again
+    finally:
+        c.close()
 
 
 def sampled_layers(layers, cap=28):

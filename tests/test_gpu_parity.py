@@ -178,19 +178,22 @@ def test_invert_batch_mixed_sizes(ctx):
         np.testing.assert_array_equal(host64(Fd), F.astype(np.float32).astype(np.float64))   # F untouched
 
 
-@pytest.mark.parametrize("env", [
-    {"KFAC_INV_AGG": "4"},                               # the outer block size of a throughput-bound group
-    {"KFAC_INV_AGG": "5", "KFAC_INV_FUSE": "0"},          # separate pivot and update launches
-    {"KFAC_INV_AGG": "3", "KFAC_INV_GROUPS": "1"},
-    {"KFAC_INV_GROUPS": "3"},
+@pytest.mark.parametrize("opts", [
+    {"inv_agg": 4, "inv_agg_chain": 4},                   # the outer block size of a throughput-bound group
+    {"inv_agg": 5, "inv_agg_chain": 5, "inv_fuse": 0},    # separate pivot and update launches
+    {"inv_agg": 3, "inv_agg_chain": 3, "inv_groups": 1},
+    {"inv_groups": 3},
+    {"inv_side_pad": 0},
 ])
-def test_invert_batch_other_schedules(kfac_lib, monkeypatch, env):
-    """The schedule knobs a context reads at creation (outer block size, fused pivot/update launch,
-    number of lockstep groups) change launch structure only: every setting meets the same bar."""
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
+def test_invert_batch_other_schedules(kfac_lib, opts):
+    """The schedule options of a context (outer block size, fused pivot/update launch, number of
+    lockstep groups, occupancy of the off-chain products) change launch structure only: every
+    setting meets the same bar."""
     c = kfac_lib.Context(0)
     try:
+        for k, v in opts.items():
+            c.set_option(k, v)
+            assert c.get_option(k) == v
         dims = [5, 128, 129, 257, 513, 641, 777, 1025, 1040, 1300]
         gamma = 0.03
         Fs = [spd(d, d + 1, 5.0) + 0.5 * np.eye(d) for d in dims]
@@ -198,9 +201,9 @@ def test_invert_batch_other_schedules(kfac_lib, monkeypatch, env):
         assert np.all(info == 0)
         for d, Fd, Xd in zip(dims, F_d, X_d):
             X = host64(Xd)
-            assert np.array_equal(X, X.T), f"{env} d={d}: inverse not exactly symmetric"
+            assert np.array_equal(X, X.T), f"{opts} d={d}: inverse not exactly symmetric"
             res = inv_residual(host64(Fd), gamma, X)
-            assert res <= TOL_INVERSE, f"{env} d={d}: residual {res:.3e}"
+            assert res <= TOL_INVERSE, f"{opts} d={d}: residual {res:.3e}"
     finally:
         c.close()
 
