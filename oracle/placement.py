@@ -1,15 +1,20 @@
 """Load-balancing placement of the inversions on P workers (TEST INFRASTRUCTURE).
 
-Plain Python transcription, in the paper's notation, of what Sec. IV-B defines: the two cost
-models (Eq. inverting-model, Eq. broadcast-model), Algorithm 1 (LBP) with its rule for
-communicated / non-communicated tensors, the sequential placement it is compared with, and the
-objective (overall time) of the problem statement.  Shares no code with the library's
-kfac_place_inversions and is imported only by tests.
+Plain Python statement of what Sec. IV-B defines: the two cost models (Eq. inverting-model,
+Eq. broadcast-model), the load-balancing placement (Algorithm 1) with its rule for communicated /
+non-communicated tensors, the sequential placement it is compared with, and the objective (overall
+time) of the problem statement.  Shares no code with the library's kfac_place_inversions and is
+imported only by tests.
 
-Readings of garbled places: Algorithm 1 adds d_i to a worker's bucket while the text balances
-d_i^2; `weight_power` selects d_i ** weight_power (1 = as the listing prints, 2 = as the text says).
-The sequential placement is printed as "i % p = 0"; it is taken as round-robin, tensor i on
-worker i mod P.
+`lbp` is written from the definition, not from the printed listing: a tensor whose inverse is
+cheaper to compute than to receive is computed by everybody, which loads every worker alike and so
+never changes which worker is the lightest; the placement is therefore decided by the communicated
+tensors alone, largest first, each to the worker that carries the least so far.
+
+Readings of garbled places: Algorithm 1 adds d_i to a worker's load while the text balances d_i^2;
+`weight_power` selects d_i ** weight_power (1 = as the listing prints, 2 = as the text says).  The
+sequential placement is printed as "i % p = 0"; it is taken as round-robin, tensor i on worker
+i mod P.
 """
 from __future__ import annotations
 
@@ -29,22 +34,18 @@ def t_comm(d: int, alpha_bcast: float, beta_bcast: float) -> float:
 
 def lbp(dims: Sequence[int], P: int, est_comp: Callable[[int], float], est_comm: Callable[[int], float],
         weight_power: int = 1) -> List[int]:
-    """Algorithm 1.  Returns owner[i]: the worker that inverts tensor i, or -1 when every worker
-    does (a non-communicated tensor, chosen when its inverse is cheaper to compute than to receive)."""
-    N = len(dims)
-    owner = [0] * N
-    b = [0.0] * P                                              # bucket array: workload assigned to each worker
-    I = sorted(range(N), key=lambda i: -dims[i])               # descending dimensions (stable)
-    for i in I:
-        p = min(range(P), key=lambda q: b[q])                  # least-loaded worker (first one on ties)
-        w = float(dims[i]) ** weight_power
-        if est_comp(dims[i]) < est_comm(dims[i]):
-            owner[i] = -1
-            for q in range(P):
-                b[q] += w
-        else:
-            owner[i] = p
-            b[p] += w
+    """Load-balancing placement (Sec. IV-B, Algorithm 1).  Returns owner[i]: the worker that inverts
+    tensor i, or -1 when every worker does (a non-communicated tensor: its inverse is cheaper to
+    compute than to receive)."""
+    everybody = {i for i, d in enumerate(dims) if est_comp(d) < est_comm(d)}
+    owner = [-1] * len(dims)
+    carried = [0.0] * P          # load from communicated tensors only; the replicated ones add the same to all
+    communicated = [i for i in range(len(dims)) if i not in everybody]
+    communicated.sort(key=lambda i: dims[i], reverse=True)     # stable: equal sizes keep their input order
+    for i in communicated:
+        lightest = carried.index(min(carried))                  # lowest index among equally light workers
+        owner[i] = lightest
+        carried[lightest] += float(dims[i]) ** weight_power
     return owner
 
 
