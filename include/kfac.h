@@ -97,7 +97,9 @@ typedef enum {
   KFAC_OPT_FACTOR_XCD = 7,    /* 0/1    [0]     factor jobs dealt to the 8 XCDs in contiguous segments             */
   KFAC_OPT_FACTOR_KJOB = 8,   /* 32..8192 [8192] longest run of rows one factor tile job accumulates               */
   KFAC_OPT_INV_CHAIN_PAD = 9, /* 0..65536 [0]   bytes of unused LDS added to the chain kernels of such a group              */
-  KFAC_OPT_COUNT = 10
+  KFAC_OPT_INV_SIDE = 10,     /* 0/1    [1]     off-chain work of a group on a second internal stream                  */
+  KFAC_OPT_INV_SPLIT_LONG = 11, /* 0/1  [1]     the matrices with the longest chains form a group of their own         */
+  KFAC_OPT_COUNT = 12
 } kfac_option;
 kfac_status kfac_set_option(kfac_ctx* ctx, int option, int value);
 kfac_status kfac_get_option(const kfac_ctx* ctx, int option, int* value);

@@ -146,6 +146,8 @@ struct kfac_ctx {
       /* FACTOR_KJOB    */ MAX_JOB_ROWS,   // longest contraction run of one factor tile job (rows)
       /* INV_CHAIN_PAD  */ 0,       // unused LDS added to the kernels of a latency-bound group's chain: with the side pad,
                                     // no workgroup of the call shares a compute unit with a chain workgroup
+      /* INV_SIDE       */ 1,       // off-chain work of a group on a second stream (0: everything on the group's one stream)
+      /* INV_SPLIT_LONG */ 1,       // the matrices with the longest chains form a group of their own
   };
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
   hipStream_t inv_side[MAX_INV_GROUPS] = {};     // every group's side stream for the off-chain updates
@@ -899,8 +901,8 @@ size_t kfac_workspace_bytes_precondition(const kfac_ctx*, int n, const int32_t* 
 
 kfac_status kfac_set_option(kfac_ctx* ctx, int option, int value) {
   if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_set_option: ctx is NULL");
-  static const int lo[KFAC_OPT_COUNT] = {1, 1, 1, 0, 0, 0, 0, 0, KC, 0};
-  static const int hi[KFAC_OPT_COUNT] = {MAX_INV_GROUPS, 16, 16, 1, 65536, 1, 1, 1, MAX_JOB_ROWS, 65536};
+  static const int lo[KFAC_OPT_COUNT] = {1, 1, 1, 0, 0, 0, 0, 0, KC, 0, 0, 0};
+  static const int hi[KFAC_OPT_COUNT] = {MAX_INV_GROUPS, 16, 16, 1, 65536, 1, 1, 1, MAX_JOB_ROWS, 65536, 1, 1};
   if (option < 0 || option >= KFAC_OPT_COUNT) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_set_option: unknown option");
   if (value < lo[option] || value > hi[option])
     return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_set_option: value " + std::to_string(value) + " outside [" +
@@ -1123,7 +1125,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
     auto is_long = [&](int i) { return dims[i] > NB && 5 * ceil_div(dims[i], NB) > 3 * max_nblk; };
     for (int i = 0; i < n; ++i) n_long += is_long(i);
     const int G = std::max(1, std::min(ctx->opt[KFAC_OPT_INV_GROUPS], n_large));
-    const bool split = G >= 2 && n_long > 0 && n_long < n_large;   // otherwise: plain balancing over all groups
+    const bool split = ctx->opt[KFAC_OPT_INV_SPLIT_LONG] && G >= 2 && n_long > 0 && n_long < n_large;   // otherwise: plain balancing over all groups
     P.groups.assign(G, InvertGroup{});
     std::vector<double> load(G, 0.0);
     for (int i : by_size) {
@@ -1295,7 +1297,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
       launch_gj_init(d_mats[g], Gp.d_init, Gp.n_init_first, gamma, gs);
     }
     if (Gp.n_init > Gp.n_init_first) {   // the other tiles: on the side stream, beside the first diagonal sweep
-      hipStream_t side = ctx->inv_side[g];
+      hipStream_t side = ctx->opt[KFAC_OPT_INV_SIDE] ? ctx->inv_side[g] : gs;
       if (!Gp.ev_start) HIP_TRY(ctx, hipEventCreateWithFlags(&Gp.ev_start, hipEventDisableTiming));
       if (!Gp.ev_init) HIP_TRY(ctx, hipEventCreateWithFlags(&Gp.ev_init, hipEventDisableTiming));
       HIP_TRY(ctx, hipEventRecord(Gp.ev_start, gs));
@@ -1332,7 +1334,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
     for (int g = 0; g < G; ++g) {
       InvertGroup& Gp = P.groups[g];
       if (b >= Gp.n_ob) continue;
-      hipStream_t gs = gstream(g), side = ctx->inv_side[g];
+      hipStream_t gs = gstream(g), side = ctx->opt[KFAC_OPT_INV_SIDE] ? ctx->inv_side[g] : gs;
       const InvMat* views = d_views[g];
       const int side_pad = Gp.latency_bound ? ctx->opt[KFAC_OPT_INV_SIDE_PAD] : 0;
       const int chain_pad = Gp.latency_bound ? ctx->opt[KFAC_OPT_INV_CHAIN_PAD] : 0;
