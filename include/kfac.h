@@ -184,6 +184,27 @@ kfac_status kfac_precondition(kfac_ctx* ctx, int n_layers, const int32_t* dG, co
                               const float* const* gradW, float* const* out, void* hip_stream);
 
 /*
+ * kfac_precondition for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result (bit for bit),
+ * but the call allocates nothing: descriptors, job lists and the intermediate Ginv . V live in one
+ * static device array of KFAC_NOALLOC_SCRATCH_BYTES that every GPU the library runs on holds until the
+ * process ends, and the call consists of three kernel launches on hip_stream (no copies, no memsets).
+ * Limits per call (INVALID_ARG beyond them, with the figures in kfac_last_error): at most
+ * KFAC_NOALLOC_MAX_LAYERS layers, KFAC_NOALLOC_MAX_ELEMS gradient elements (sum of dG*dA) and
+ * KFAC_NOALLOC_MAX_TILES 128 x 128 output tiles (sum of ceil(dG/128)*ceil(dA/128)) over all layers.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different
+ * streams, different contexts or threads) race; issue them in one stream, or order them with events.
+ * Nothing in the array has to start at zero, and nothing is kept between calls.
+ */
+#define KFAC_NOALLOC_MAX_LAYERS 32
+#define KFAC_NOALLOC_MAX_ELEMS (7u << 20)
+#define KFAC_NOALLOC_MAX_TILES 8192
+#define KFAC_NOALLOC_SCRATCH_BYTES ((size_t)30 << 20) /* upper bound: tables (< 1 MiB) + 28 MiB of intermediates */
+kfac_status kfac_precondition_noalloc(kfac_ctx* ctx, int n_layers, const int32_t* dG, const int32_t* dA,
+                                      const float* const* Ginv, const float* const* Ainv,
+                                      const float* const* gradW, float* const* out, void* hip_stream);
+
+/*
  * Packed upper triangles: the form in which the paper communicates symmetric factors and
  * inverses between workers (Sec. IV-A: d(d+1)/2 communicated elements per factor; Sec. V-B: the
  * upper triangle including the diagonal).  The triangles of the n matrices are concatenated in one

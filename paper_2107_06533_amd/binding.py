@@ -17,7 +17,7 @@ EXPORTS = [
     "kfac_update_factors", "kfac_invert_batch", "kfac_invert_batch_packed", "kfac_check_info", "kfac_precondition",
     "kfac_packed_elems", "kfac_pack_triangles", "kfac_unpack_triangles", "kfac_place_inversions",
     "kfac_get_plan_stats", "kfac_timing_enable", "kfac_timing_read",
-    "kfac_set_option", "kfac_get_option",
+    "kfac_set_option", "kfac_get_option", "kfac_precondition_noalloc",
 ]
 
 # kfac_option, in the order of the header
@@ -99,6 +99,8 @@ def load():
     lib.kfac_check_info.restype = C.c_int
     lib.kfac_precondition.argtypes = [vp, C.c_int, i32p, i32p, fpp, fpp, fpp, fpp, vp]
     lib.kfac_precondition.restype = C.c_int
+    lib.kfac_precondition_noalloc.argtypes = [vp, C.c_int, i32p, i32p, fpp, fpp, fpp, fpp, vp]
+    lib.kfac_precondition_noalloc.restype = C.c_int
     lib.kfac_packed_elems.argtypes = [C.c_int, i32p, C.POINTER(C.c_int64)]
     lib.kfac_packed_elems.restype = C.c_size_t
     lib.kfac_pack_triangles.argtypes = [vp, C.c_int, i32p, fpp, vp, vp]
@@ -251,6 +253,15 @@ class Context:
         st = self.lib.kfac_precondition(self.h, n, _i32_array(dG) if n else None, _i32_array(dA) if n else None,
                                         _ptr_array(Ginv, n), _ptr_array(Ainv, n), _ptr_array(gradW, n),
                                         _ptr_array(out, n), _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def kfac_precondition_noalloc(self, dG, dA, Ginv, Ainv, gradW, out, stream=None, check: bool = True) -> int:
+        n = len(dG)
+        st = self.lib.kfac_precondition_noalloc(self.h, n, _i32_array(dG) if n else None, _i32_array(dA) if n else None,
+                                                _ptr_array(Ginv, n), _ptr_array(Ainv, n), _ptr_array(gradW, n),
+                                                _ptr_array(out, n), _stream_handle(stream))
         if check:
             self._check(st)
         return st

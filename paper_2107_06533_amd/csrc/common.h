@@ -10,7 +10,7 @@ struct FastDiv {
   uint32_t m, sh1, sh2;
 };
 
-inline FastDiv make_fastdiv(uint32_t d) {
+__host__ __device__ inline FastDiv make_fastdiv(uint32_t d) {
   // round-up method for invariant divisors: l = ceil(log2 d), m = floor(2^32 (2^l - d) / d) + 1
   uint32_t l = 0;
   while ((uint64_t(1) << l) < d) ++l;

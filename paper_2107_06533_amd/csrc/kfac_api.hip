@@ -1667,3 +1667,147 @@ kfac_status kfac_precondition(kfac_ctx* ctx, int n, const int32_t* dG, const int
 }
 
 }  // extern "C"
+
+// ----------------------------------------------------------------------------------- precondition, no allocation
+// kfac_precondition for callers that cannot allocate device memory (HIP graph capture, tight serving
+// loops): descriptors, job lists and the intermediate Ginv . V live in one file-scope device array;
+// the tables are written by a small kernel from arguments passed by value, so the call issues three
+// kernel launches and nothing else (no hipMalloc / hipFree / hipMemcpy / hipMemset).
+namespace {
+
+constexpr int NA_MAX_LAYERS = KFAC_NOALLOC_MAX_LAYERS;
+constexpr size_t NA_MAX_ELEMS = KFAC_NOALLOC_MAX_ELEMS;           // floats of all intermediates together
+constexpr int NA_MAX_JOBS = KFAC_NOALLOC_MAX_TILES;               // 128 x 128 output tiles of all layers together
+constexpr size_t NA_DESC_BYTES = size_t(2) * NA_MAX_LAYERS * sizeof(TileDesc);
+constexpr size_t NA_JOB_BYTES = size_t(2) * NA_MAX_JOBS * sizeof(TileJob);
+constexpr size_t NA_T_OFFSET = ((NA_DESC_BYTES + NA_JOB_BYTES + 255) / 256) * 256;
+constexpr size_t NA_SCRATCH_BYTES = NA_T_OFFSET + NA_MAX_ELEMS * sizeof(float);
+static_assert(NA_SCRATCH_BYTES <= KFAC_NOALLOC_SCRATCH_BYTES, "the header states an upper bound of the array's size");
+
+// One copy per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress: kernels get the device address looked up below, never the name.
+static __device__ __align__(256) unsigned char scratch[NA_SCRATCH_BYTES];
+
+constexpr int NA_MAX_DEVICES = 64;
+unsigned char* g_scratch_ptr[NA_MAX_DEVICES] = {};               // per device: address of its copy of `scratch`
+
+struct NoallocArgs {
+  int32_t n;
+  int32_t dG[NA_MAX_LAYERS], dA[NA_MAX_LAYERS];
+  int32_t job_off[NA_MAX_LAYERS + 1];                             // first tile of every layer
+  uint32_t t_off[NA_MAX_LAYERS];                                  // float offset of the layer's intermediate
+  const float* Ginv[NA_MAX_LAYERS];
+  const float* Ainv[NA_MAX_LAYERS];
+  const float* gradW[NA_MAX_LAYERS];
+  float* out[NA_MAX_LAYERS];
+};
+static_assert(sizeof(NoallocArgs) <= 3072, "passed by value as a kernel argument");
+
+__device__ Operand dev_rowmajor_operand(const float* p, int K, int M, int ld) {
+  Operand o{};
+  o.ptr = p; o.type = OP_KMAJOR; o.K = K; o.M = M; o.bias = 0; o.ld = ld;
+  o.bytes = uint32_t(K) * uint32_t(ld) * 4u;
+  return o;
+}
+__device__ Operand dev_transposed_operand(const float* p, int K, int M) {
+  Operand o{};
+  o.ptr = p; o.type = OP_CONV11; o.K = K; o.M = M; o.bias = 0;
+  o.bytes = uint32_t(K) * uint32_t(M) * 4u;
+  o.C = M; o.H = 1; o.W = K; o.OH = 1; o.OW = K; o.stride = 1; o.pad_h = o.pad_w = 0; o.KH = 1; o.KW = 1;
+  o.dOW = make_fastdiv(uint32_t(K));
+  o.dOHW = make_fastdiv(uint32_t(K));
+  return o;
+}
+
+// Block l writes the two descriptors and the tile jobs of layer l (the same descriptors
+// kfac_precondition builds on the host; jobs in layer order).
+__global__ void noalloc_tables_kernel(NoallocArgs a, TileDesc* descs, TileJob* jobs1, TileJob* jobs2, float* tbuf) {
+  const int l = blockIdx.x;
+  if (l >= a.n) return;
+  const int dG = a.dG[l], dA = a.dA[l];
+  float* T = tbuf + a.t_off[l];
+  if (threadIdx.x == 0) {
+    TileDesc D1{};     // T^T = V^T . Ginv^T
+    D1.a = dev_rowmajor_operand(a.gradW[l], dG, dA, dA);
+    D1.b = dev_transposed_operand(a.Ginv[l], dG, dG);
+    D1.out = T; D1.ldo = dG; D1.M = dA; D1.N = dG;
+    D1.sym = 0; D1.mirror = MIRROR_NONE; D1.alpha = 1.f; D1.beta = 0.f;
+    descs[2 * l] = D1;
+    TileDesc D2{};     // out = T . Ainv
+    D2.a = dev_rowmajor_operand(T, dA, dG, dG);
+    D2.b = dev_rowmajor_operand(a.Ainv[l], dA, dA, dA);
+    D2.out = a.out[l]; D2.ldo = dA; D2.M = dG; D2.N = dA;
+    D2.sym = 0; D2.mirror = MIRROR_NONE; D2.alpha = 1.f; D2.beta = 0.f;
+    descs[2 * l + 1] = D2;
+  }
+  const int Tn = (dA + BN - 1) / BN, ntile = a.job_off[l + 1] - a.job_off[l];
+  for (int e = threadIdx.x; e < ntile; e += blockDim.x) {
+    const int bi = e / Tn, bj = e - bi * Tn;
+    TileJob j{};
+    j.kbeg = 0; j.part = -1;
+    j.desc = 2 * l; j.bi = bj; j.bj = bi; j.kend = dG;
+    jobs1[a.job_off[l] + e] = j;
+    j.desc = 2 * l + 1; j.bi = bi; j.bj = bj; j.kend = dA;
+    jobs2[a.job_off[l] + e] = j;
+  }
+}
+
+}  // namespace
+
+extern "C" kfac_status kfac_precondition_noalloc(kfac_ctx* ctx, int n, const int32_t* dG, const int32_t* dA,
+                                                 const float* const* Ginv, const float* const* Ainv,
+                                                 const float* const* gradW, float* const* out, void* hip_stream) {
+  if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: ctx is NULL");
+  if (n < 0) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: n_layers < 0");
+  if (n == 0) return KFAC_OK;
+  if (!dG || !dA || !Ginv || !Ainv || !gradW || !out)
+    return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: NULL array argument");
+  if (n > NA_MAX_LAYERS)
+    return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: " + std::to_string(n) + " layers exceed the maximum of " +
+                                               std::to_string(NA_MAX_LAYERS) + " per call");
+  NoallocArgs a{};
+  a.n = n;
+  size_t elems = 0;
+  int64_t tiles = 0;
+  for (int l = 0; l < n; ++l) {
+    if (dG[l] < 1 || dA[l] < 1 || dG[l] > 16384 || dA[l] > 16384)
+      return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: dimension out of range at layer " + std::to_string(l));
+    if (!Ginv[l] || !Ainv[l] || !gradW[l] || !out[l])
+      return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: NULL matrix pointer at layer " + std::to_string(l));
+    if (out[l] == Ginv[l] || out[l] == Ainv[l])
+      return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: out aliases an inverse at layer " + std::to_string(l));
+    a.dG[l] = dG[l]; a.dA[l] = dA[l];
+    a.Ginv[l] = Ginv[l]; a.Ainv[l] = Ainv[l]; a.gradW[l] = gradW[l]; a.out[l] = out[l];
+    a.job_off[l] = int32_t(tiles);
+    a.t_off[l] = uint32_t(elems);
+    tiles += int64_t(ceil_div(dG[l], BM)) * ceil_div(dA[l], BN);
+    elems += size_t(dG[l]) * dA[l];
+  }
+  a.job_off[n] = int32_t(std::min<int64_t>(tiles, INT32_MAX));
+  if (elems > NA_MAX_ELEMS)
+    return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: gradients of " + std::to_string(elems) +
+                                               " elements exceed the static scratch (" + std::to_string(NA_MAX_ELEMS) + " elements per call)");
+  if (tiles > NA_MAX_JOBS)
+    return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_precondition_noalloc: " + std::to_string(tiles) + " output tiles exceed the maximum of " +
+                                               std::to_string(NA_MAX_JOBS) + " per call");
+  if (ctx->host_only) return fail(ctx, KFAC_ERR_DEVICE, "host-only context: nothing launched");
+  if (ctx->device >= NA_MAX_DEVICES) return fail(ctx, KFAC_ERR_DEVICE, "kfac_precondition_noalloc: device index too large");
+  DeviceGuard guard(ctx);
+  unsigned char*& base = g_scratch_ptr[ctx->device];
+  if (!base) {   // first call on this device: look up where this device holds its copy of the array
+    void* p = nullptr;
+    HIP_TRY(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(ctx, KFAC_ERR_DEVICE, "kfac_precondition_noalloc: the scratch array has no device address");
+    base = static_cast<unsigned char*>(p);
+  }
+  TileDesc* d_descs = reinterpret_cast<TileDesc*>(base);
+  TileJob* d_jobs1 = reinterpret_cast<TileJob*>(base + NA_DESC_BYTES);
+  TileJob* d_jobs2 = d_jobs1 + NA_MAX_JOBS;
+  float* d_t = reinterpret_cast<float*>(base + NA_T_OFFSET);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(noalloc_tables_kernel, dim3(n), dim3(256), 0, s, a, d_descs, d_jobs1, d_jobs2, d_t);
+  launch_tile_gemm(d_descs, d_jobs1, int(tiles), 0, s);
+  launch_tile_gemm(d_descs, d_jobs2, int(tiles), 0, s);
+  HIP_TRY(ctx, hipGetLastError());
+  return KFAC_OK;
+}
