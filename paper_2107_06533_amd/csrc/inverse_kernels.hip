@@ -114,6 +114,22 @@ __device__ __forceinline__ void sweep32(float (&r)[16], int lane, int& bad) {
 
 constexpr int PIVOT_LDS_FLOATS = NB * SP;
 
+#ifdef KFAC_TRACE
+// debugging aid: per-workgroup phase time stamps (100 MHz) appended behind the compute-unit words
+__device__ __forceinline__ void trace_rec(int* flags, int kind, int step, const long long (&t)[5]) {
+  if (!flags || threadIdx.x != 0) return;
+  int* cnt = flags + CU_SLOTS;
+  const int r = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (r >= 60000) return;
+  long long* rec = reinterpret_cast<long long*>(flags + CU_SLOTS + 2) + (size_t)r * 8;
+  rec[0] = kind; rec[1] = step; rec[2] = cu_slot();
+  for (int k = 0; k < 5; ++k) rec[3 + k] = t[k];
+}
+#define TRACE_T(k) tr[k] = wall_clock64()
+#else
+#define TRACE_T(k)
+#endif
+
 // block -= Wt^T Zt on the ten 32 x 32 sub-blocks of the block's lower triangle (mirrored into the
 // upper one), Wt/Zt k-major with NB rows.  Wave WV takes the sub-blocks
 //   0: (0,0) (1,0) (2,0)    1: (3,0) (3,1) (3,2)    2: (1,1) (2,1)    3: (2,2) (3,3)
@@ -162,7 +178,12 @@ __device__ __forceinline__ void own_update(float* __restrict__ S, gcf_ptr Wp, gc
 // pivot block of the same matrix; its panels (Wt, Zt: k-major, NB rows) are applied here first,
 // block -= Wt^T Zt restricted to the block's columns, so that the update launch can leave this
 // block out and run beside this kernel instead of before it.
-__device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gamma, int small, int fuse, float* __restrict__ smem) {
+__device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gamma, int small, int fuse, float* __restrict__ smem,
+                                           int* trace = nullptr) {
+#ifdef KFAC_TRACE
+  long long tr[5] = {0, 0, 0, 0, 0};
+#endif
+  TRACE_T(0);
   float* S = smem;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int li = lane & 31, lh = lane >> 5;
@@ -220,6 +241,7 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
     }
   }
   __syncthreads();
+  TRACE_T(1);
 
   if (fuse) {
     gcf_ptr Wp = as_global((const float*)Mx.Wt) + k0;
@@ -233,6 +255,7 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
     __syncthreads();
   }
 
+  TRACE_T(2);
   int bad = 0;
   for (int kb = 0; kb < nsb; ++kb) {
     // (A) inverse of the diagonal sub-block, in every wave (r: +D^-1 in the sweep's layout)
@@ -306,6 +329,7 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
     }
     __syncthreads();
   }
+  TRACE_T(3);
   if (t == 0 && Mx.info) {
     if (small) *Mx.info = bad;                                // whole matrix: sole writer
     else if (bad && *Mx.info == 0) *Mx.info = Mx.info_base + k0 + bad;   // first failing sweep wins (zeroed by the init kernel)
@@ -352,13 +376,20 @@ __device__ __forceinline__ void pivot_body(const InvMat& Mx, int step, float gam
       }
     }
   }
+#ifdef KFAC_TRACE
+  __builtin_amdgcn_s_waitcnt(0);
+  TRACE_T(4);
+  trace_rec(trace, 1 + fuse + 8 * Mx.ld, step, tr);
+#endif
 }
 
 __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__ mats, const MatJob* __restrict__ jobs,
-                                                      int mat0, int step, float gamma, int small) {
+                                                      int mat0, int step, float gamma, int small, int* cu_flags) {
   __shared__ float smem[PIVOT_LDS_FLOATS];
   const InvMat Mx = mats[jobs ? jobs[blockIdx.x].mat : mat0 + (int)blockIdx.x];   // a job list, or consecutive matrices
-  pivot_body(Mx, step, gamma, small, 0, smem);
+  cu_enter(cu_flags);
+  pivot_body(Mx, step, gamma, small, 0, smem, cu_flags);
+  cu_leave(cu_flags);
 }
 
 // One launch for two things that do not depend on each other: workgroups [0, npiv) sweep pivot
@@ -367,15 +398,18 @@ __global__ __launch_bounds__(NT) void gj_pivot_kernel(const InvMat* __restrict__
 __global__ __launch_bounds__(NT) void gj_pivot_update_kernel(const InvMat* __restrict__ mats, const MatJob* __restrict__ pjobs,
                                                              int npiv, int step, float gamma,
                                                              const TileDesc* __restrict__ descs,
-                                                             const TileJob* __restrict__ ujobs, int nupd) {
-  __shared__ float smem[PIVOT_LDS_FLOATS > TILE_LDS_FLOATS ? PIVOT_LDS_FLOATS : TILE_LDS_FLOATS];
+                                                             const TileJob* __restrict__ ujobs, int nupd, int* cu_flags, int critical) {
+  __shared__ __attribute__((aligned(16))) float smem[PIVOT_LDS_FLOATS > DL_LDS_FLOATS ? PIVOT_LDS_FLOATS : DL_LDS_FLOATS];
   const int g = blockIdx.x;
   if (g < npiv) {
     const InvMat Mx = mats[pjobs[g].mat];
-    pivot_body(Mx, step, gamma, 0, 1, smem);
+    int* const mine = critical ? cu_flags : nullptr;
+    cu_enter(mine);
+    pivot_body(Mx, step, gamma, 0, 1, smem, cu_flags);
+    cu_leave(mine);
   } else if (g - npiv < nupd) {
     const TileJob J = ujobs[g - npiv];
-    run_tile<KMajorLoader, KMajorLoader, true>(descs[J.desc], J, smem);
+    run_tile_dl<false, true>(descs[J.desc], J, smem, cu_flags);
   }
 }
 
@@ -383,7 +417,7 @@ __global__ __launch_bounds__(NT) void gj_pivot_update_kernel(const InvMat* __res
 // One job per 128-row tile `it` of the block column (it != step).  Tiles above the pivot live in
 // block row `step` of the lower triangle (read along rows), tiles below in block column `step`.
 __global__ __launch_bounds__(NT) void gj_panel_kernel(const InvMat* __restrict__ mats,
-                                                      const MatJob* __restrict__ jobs, int njobs, int step) {
+                                                      const MatJob* __restrict__ jobs, int njobs, int step, int* cu_flags) {
   // All loads of the 128-deep contraction (4 k chunks of Q and of the tile) are requested up front:
   // the kernel sits on the critical path with few workgroups, so it pays the memory latency once
   // instead of once per chunk.  The chunks then pass through two LDS buffers (the footprint of a
@@ -393,6 +427,11 @@ __global__ __launch_bounds__(NT) void gj_panel_kernel(const InvMat* __restrict__
   __shared__ float Zs[2 * PANEL];
   const int g = blockIdx.x;
   if (g >= njobs) return;
+#ifdef KFAC_TRACE
+  long long tr[5] = {0, 0, 0, 0, 0};
+#endif
+  TRACE_T(0);
+  cu_enter(cu_flags);
   const MatJob J = jobs[g];
   const InvMat Mx = mats[J.mat];
   const int it = J.bi, slot = J.aux;   // slot: which 128 rows of the aggregated panel buffers this sweep fills
@@ -458,6 +497,10 @@ __global__ __launch_bounds__(NT) void gj_panel_kernel(const InvMat* __restrict__
       for (int u = 0; u < NU; ++u) Zc[lds_idx(mg + MG * u, kl)] = rz[c][u];
     }
     __syncthreads();   // chunk c staged; the other buffer (chunk c - 1) may still be read by slower waves
+#ifdef KFAC_TRACE
+    if (c == 0) TRACE_T(1);
+    if (c == NCH - 1) TRACE_T(2);
+#endif
 #pragma unroll
     for (int gq = 0; gq < NU / 4; ++gq) {
       const f32x4 zv = *reinterpret_cast<const f32x4*>(Zc + ml * PK + 8 * gq + 4 * kp);
@@ -491,6 +534,13 @@ __global__ __launch_bounds__(NT) void gj_panel_kernel(const InvMat* __restrict__
       buf_store(rs_o, in ? off : OOB_OFFSET, val);
     }
   }
+#ifdef KFAC_TRACE
+  TRACE_T(3);
+  __builtin_amdgcn_s_waitcnt(0);
+  TRACE_T(4);
+  trace_rec(cu_flags, 8 * Mx.ld, step, tr);
+#endif
+  cu_leave(cu_flags);
 }
 
 // ---- finish: X = -(swept lower triangle), mirrored to a full symmetric matrix -------------------
@@ -689,19 +739,21 @@ void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma
   if (njobs <= 0) return;
   hipLaunchKernelGGL(gj_init_kernel, dim3(njobs), dim3(NT), 0, s, mats, (const MatJob*)jobs, njobs, gamma);
 }
-void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s, int lds_pad) {
+int cu_flag_slots() { return CU_SLOTS; }
+void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s, int lds_pad,
+                     int* cu_flags) {
   if (nmats <= 0) return;
-  hipLaunchKernelGGL(gj_pivot_kernel, dim3(nmats), dim3(NT), lds_pad, s, mats, (const MatJob*)jobs, mat0, step, gamma, small);
+  hipLaunchKernelGGL(gj_pivot_kernel, dim3(nmats), dim3(NT), lds_pad, s, mats, (const MatJob*)jobs, mat0, step, gamma, small, cu_flags);
 }
 void launch_gj_pivot_update(const InvMat* mats, const void* pjobs, int npiv, int step, float gamma,
-                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s, int lds_pad) {
+                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s, int lds_pad, int* cu_flags, int critical) {
   if (npiv <= 0 && nupd <= 0) return;
   hipLaunchKernelGGL(gj_pivot_update_kernel, dim3(npiv + nupd), dim3(NT), lds_pad, s, mats, (const MatJob*)pjobs, npiv, step, gamma,
-                     descs, ujobs, nupd);
+                     descs, ujobs, nupd, cu_flags, critical);
 }
-void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s, int lds_pad) {
+void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s, int lds_pad, int* cu_flags) {
   if (njobs <= 0) return;
-  hipLaunchKernelGGL(gj_panel_kernel, dim3(njobs), dim3(NT), lds_pad, s, mats, (const MatJob*)jobs, njobs, step);
+  hipLaunchKernelGGL(gj_panel_kernel, dim3(njobs), dim3(NT), lds_pad, s, mats, (const MatJob*)jobs, njobs, step, cu_flags);
 }
 void launch_gj_qmirror(const InvMat* mats, const void* jobs, int njobs, hipStream_t s) {
   if (njobs <= 0) return;

@@ -138,7 +138,7 @@ struct kfac_ctx {
       /* INV_AGG        */ 4,       // pivot blocks per outer block (rank agg*128 updates), throughput-bound group
       /* INV_AGG_CHAIN  */ 6,       // the same for a latency-bound group (fewer outer steps on the critical path)
       /* INV_FUSE       */ 1,       // a pivot block applies the previous block's update to itself (one launch fewer per step)
-      /* INV_SIDE_PAD   */ 16384,   // unused LDS added to the off-chain products of a latency-bound group: one workgroup
+      /* INV_SIDE_PAD   */ 56000,   // unused LDS added to the off-chain products of a latency-bound group: one workgroup
                                     // per compute unit, so that the chain's kernels always find a free slot
       /* FACTOR_LAG     */ 1,       // lag products for 3x3 / stride 1 / pad 1 activation factors
       /* FACTOR_VEC11   */ 1,       // 128-bit loader for 1x1 windows over whole images
@@ -148,7 +148,10 @@ struct kfac_ctx {
                                     // no workgroup of the call shares a compute unit with a chain workgroup
       /* INV_SIDE       */ 1,       // off-chain work of a group on a second stream (0: everything on the group's one stream)
       /* INV_SPLIT_LONG */ 1,       // the matrices with the longest chains form a group of their own
+      /* INV_YIELD      */ 64,      // chain kernels of at most this many workgroups make the products on their compute
+                                    // units give way while they run (0: off)
   };
+  int* cu_flags = nullptr;          // per-compute-unit words of that protocol (device memory, zero when no kernel runs)
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
   hipStream_t inv_side[MAX_INV_GROUPS] = {};     // every group's side stream for the off-chain updates
   hipEvent_t inv_fork = nullptr, inv_join[MAX_INV_GROUPS] = {};
@@ -864,6 +867,7 @@ void kfac_destroy(kfac_ctx* ctx) {
       if (ctx->inv_join[g]) (void)hipEventDestroy(ctx->inv_join[g]);
     }
     if (ctx->inv_fork) (void)hipEventDestroy(ctx->inv_fork);
+    if (ctx->cu_flags) (void)hipFree(ctx->cu_flags);
   }
   delete ctx;
 }
@@ -901,8 +905,8 @@ size_t kfac_workspace_bytes_precondition(const kfac_ctx*, int n, const int32_t* 
 
 kfac_status kfac_set_option(kfac_ctx* ctx, int option, int value) {
   if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_set_option: ctx is NULL");
-  static const int lo[KFAC_OPT_COUNT] = {1, 1, 1, 0, 0, 0, 0, 0, KC, 0, 0, 0};
-  static const int hi[KFAC_OPT_COUNT] = {MAX_INV_GROUPS, 16, 16, 1, 65536, 1, 1, 1, MAX_JOB_ROWS, 65536, 1, 1};
+  static const int lo[KFAC_OPT_COUNT] = {1, 1, 1, 0, 0, 0, 0, 0, KC, 0, 0, 0, 0};
+  static const int hi[KFAC_OPT_COUNT] = {MAX_INV_GROUPS, 16, 16, 1, 65536, 1, 1, 1, MAX_JOB_ROWS, 65536, 1, 1, 65536};
   if (option < 0 || option >= KFAC_OPT_COUNT) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_set_option: unknown option");
   if (value < lo[option] || value > hi[option])
     return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_set_option: value " + std::to_string(value) + " outside [" +
@@ -1197,6 +1201,21 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
   kfac_status st = ensure_ws(ctx, WS_INVERT, P.ws_floats * sizeof(float));
   if (st != KFAC_OK) return st;
   const int G = int(P.groups.size());
+  if (!ctx->cu_flags) {   // once per context: zeroed here, and every kernel that counts itself in also counts itself out
+#ifdef KFAC_TRACE
+    const size_t flag_bytes = sizeof(int) * (cu_flag_slots() + 2) + size_t(60000) * 64;
+#else
+    const size_t flag_bytes = sizeof(int) * cu_flag_slots();
+#endif
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->cu_flags), flag_bytes));
+    HIP_TRY(ctx, hipMemset(ctx->cu_flags, 0, flag_bytes));
+  }
+  const int yield_max = ctx->opt[KFAC_OPT_INV_YIELD];
+  int* const yflags = yield_max > 0 ? ctx->cu_flags : nullptr;
+  auto crit = [&](int nwg) { return nwg <= yield_max ? yflags : nullptr; };   // few workgroups: latency-critical
+  auto bulk_gemm = [&](const TileDesc* dd, const TileJob* jj, int cnt, int pad, hipStream_t st) {
+    launch_tile_gemm_yield(dd, jj, cnt, pad, yflags, st);
+  };
 
   // Group 0 sweeps on the caller's stream; every further group on an internal stream forked from
   // it and joined back with events.  Each group also has a side stream for its off-chain updates.
@@ -1328,7 +1347,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
     const int o0 = Gp.upd_off[kind][b], cnt = Gp.upd_off[kind][b + 1] - o0;
     if (cnt <= 0) return;
     ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, st);
-    launch_tile_gemm_pad(d_descs[g], static_cast<const TileJob*>(Gp.d_upd[kind]) + o0, cnt, pad, st);
+    bulk_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_upd[kind]) + o0, cnt, pad, st);
   };
   for (int b = 0; b < max_ob; ++b)
     for (int g = 0; g < G; ++g) {
@@ -1348,12 +1367,13 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
         if (npiv == 0) break;
         if (t == 0 || !ctx->opt[KFAC_OPT_INV_FUSE]) {
           ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
-          launch_gj_pivot(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp], 0, npiv, t, gamma, 0, gs, chain_pad);
+          launch_gj_pivot(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp], 0, npiv, t, gamma, 0, gs, chain_pad, crit(npiv));
         }
         if (Gp.sub_panel_off[stp + 1] > Gp.sub_panel_off[stp]) {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
           launch_gj_panel(views, static_cast<const MatJobH*>(Gp.d_sub_panel) + Gp.sub_panel_off[stp],
-                          Gp.sub_panel_off[stp + 1] - Gp.sub_panel_off[stp], t, gs, chain_pad);
+                          Gp.sub_panel_off[stp + 1] - Gp.sub_panel_off[stp], t, gs, chain_pad,
+                          crit(Gp.sub_panel_off[stp + 1] - Gp.sub_panel_off[stp]));
         }
         const int npiv_next = t + 1 < aw ? Gp.sub_pivot_off[stp + 2] - Gp.sub_pivot_off[stp + 1] : 0;
         const int nupd = Gp.sub_upd_off[stp + 1] - Gp.sub_upd_off[stp];
@@ -1361,10 +1381,10 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
         if (ctx->opt[KFAC_OPT_INV_FUSE] && npiv_next > 0) {
           ScopedTiming tm(ctx, KFAC_K_INV_PIVOT, gs);
           launch_gj_pivot_update(views, static_cast<const MatJobH*>(Gp.d_sub_pivot) + Gp.sub_pivot_off[stp + 1], npiv_next, t + 1, gamma,
-                                 d_descs[g], uj, nupd, gs, chain_pad);
+                                 d_descs[g], uj, nupd, gs, chain_pad, yflags, npiv_next <= yield_max);
         } else if (nupd > 0) {
           ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, gs);
-          launch_tile_gemm_pad(d_descs[g], uj, nupd, chain_pad, gs);
+          launch_tile_gemm_yield(d_descs[g], uj, nupd, chain_pad, yflags, gs);
         }
       }
       const MatJobH* mvj = static_cast<const MatJobH*>(Gp.d_mv);
@@ -1385,7 +1405,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
         HIP_TRY(ctx, hipEventRecord(Gp.ev_gather[b], gs));
         if (bp1 > bp0) {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
-          launch_tile_gemm_pad(d_descs[g], bpj + bp0, bp1 - bp0, chain_pad, gs);
+          launch_tile_gemm_yield(d_descs[g], bpj + bp0, bp1 - bp0, chain_pad, yflags, gs);
         }
         if (bp1 > bp0) {   // the chain wrote part of the W panel
           HIP_TRY(ctx, ensure_event(Gp.ev_chain[b]));
@@ -1403,7 +1423,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
       HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_gather[b], 0));
       if (bp2 > bp1) {
         ScopedTiming tm(ctx, KFAC_K_INV_PANEL, side);
-        launch_tile_gemm_pad(d_descs[g], bpj + bp1, bp2 - bp1, side_pad, side);
+        bulk_gemm(d_descs[g], bpj + bp1, bp2 - bp1, side_pad, side);
         launch_gj_move(d_moves[g] + 1, mvj + mv1, mv2 - mv1, kch, 1, side);
       }
       if (bp1 > bp0) {
@@ -1441,6 +1461,20 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
 }
+
+#ifdef KFAC_TRACE
+extern "C" int kfac_debug_trace(kfac_ctx* ctx, long long* out, int max_recs, int reset) {
+  if (!ctx || !ctx->cu_flags) return 0;
+  (void)hipDeviceSynchronize();
+  int n = 0;
+  (void)hipMemcpy(&n, ctx->cu_flags + cu_flag_slots(), sizeof(int), hipMemcpyDeviceToHost);
+  if (n > 60000) n = 60000;
+  if (n > max_recs) n = max_recs;
+  if (out && n > 0) (void)hipMemcpy(out, ctx->cu_flags + cu_flag_slots() + 2, size_t(n) * 64, hipMemcpyDeviceToHost);
+  if (reset) (void)hipMemset(ctx->cu_flags + cu_flag_slots(), 0, sizeof(int));
+  return n;
+}
+#endif
 
 kfac_status kfac_invert_batch(kfac_ctx* ctx, int n, const int32_t* dims, const float* const* F,
                               float* const* X, float gamma, int32_t* info_dev, void* hip_stream) {
@@ -1660,7 +1694,7 @@ kfac_status kfac_precondition(kfac_ctx* ctx, int n, const int32_t* dG, const int
   }
   {
     ScopedTiming tm(ctx, KFAC_K_PRECOND_RIGHT, s);
-    launch_tile_gemm(d_descs, static_cast<const TileJob*>(P.d_jobs2), P.njobs2, 0, s);
+    launch_tile_gemm_dl(d_descs, static_cast<const TileJob*>(P.d_jobs2), P.njobs2, s);   // both operands row-major
   }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
@@ -1807,7 +1841,7 @@ extern "C" kfac_status kfac_precondition_noalloc(kfac_ctx* ctx, int n, const int
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(noalloc_tables_kernel, dim3(n), dim3(256), 0, s, a, d_descs, d_jobs1, d_jobs2, d_t);
   launch_tile_gemm(d_descs, d_jobs1, int(tiles), 0, s);
-  launch_tile_gemm(d_descs, d_jobs2, int(tiles), 0, s);
+  launch_tile_gemm_dl(d_descs, d_jobs2, int(tiles), s);
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
 }

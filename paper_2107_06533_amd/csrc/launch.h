@@ -7,14 +7,23 @@ namespace kfac {
 void launch_tile_any(const TileDesc* descs, const TileJob* jobs, int njobs, int xcd_order, hipStream_t s);
 void launch_tile_gemm(const TileDesc* descs, const TileJob* jobs, int njobs, int xcd_order, hipStream_t s);
 void launch_tile_gemm_pad(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, hipStream_t s);
+// row-major x row-major products only (both operands OP_KMAJOR without ones column): direct-to-LDS loop
+void launch_tile_gemm_dl(const TileDesc* descs, const TileJob* jobs, int njobs, hipStream_t s);
+// row-major x row-major products that give way to latency-critical workgroups on their compute unit (cu_flags may be null)
+void launch_tile_gemm_yield(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, const int* cu_flags, hipStream_t s);
 void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs, hipStream_t s);
 void launch_lag_assemble(const LagAsm* lags, const LagJob* jobs, int njobs, hipStream_t s);
 
 void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma, hipStream_t s);
-void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s, int lds_pad = 0);
+// cu_flags (may be null): table of CU_SLOTS words in which the latency-critical workgroups of these
+// kernels count themselves while they run, and which their product workgroups give way to
+void launch_gj_pivot(const InvMat* mats, const void* jobs, int mat0, int nmats, int step, float gamma, int small, hipStream_t s, int lds_pad = 0,
+                     int* cu_flags = nullptr);
 void launch_gj_pivot_update(const InvMat* mats, const void* pjobs, int npiv, int step, float gamma,
-                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s, int lds_pad = 0);
-void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s, int lds_pad = 0);
+                            const TileDesc* descs, const TileJob* ujobs, int nupd, hipStream_t s, int lds_pad = 0, int* cu_flags = nullptr,
+                            int critical = 0);   // critical: the pivot workgroups count themselves in (the update tiles always give way)
+void launch_gj_panel(const InvMat* mats, const void* jobs, int njobs, int step, hipStream_t s, int lds_pad = 0, int* cu_flags = nullptr);
+int cu_flag_slots();
 void launch_gj_qmirror(const InvMat* mats, const void* jobs, int njobs, hipStream_t s);
 void launch_gj_move(const PanelMove* moves, const void* jobs, int njobs, int kchunks, int to_matrix, hipStream_t s);
 void launch_tri_pack(const PackMat* mats, const void* jobs, int njobs, float* packed, int to_full, hipStream_t s);

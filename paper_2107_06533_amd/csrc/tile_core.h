@@ -428,9 +428,39 @@ __device__ __forceinline__ void interleave_loads() {
   if constexpr (NM > 0 && NL > 0) interleave_group<NM, NL, (NM >= NL ? NL : NM), 0>();
 }
 
+// ---- giving way to latency-critical workgroups ------------------------------------------------------
+// fp32 MFMAs keep every other wave of the SIMD from issuing, so a latency-bound kernel (a pivot block
+// sweep, a panel on the critical path of the inverse) that shares a compute unit with a product
+// workgroup runs two to three times slower.  Such kernels count themselves in a per-compute-unit
+// word while they run (cu_enter / cu_leave); product workgroups launched as "yielding" read the word
+// of their compute unit once per k step and sleep while it is non-zero.  The word is advisory: the
+// sleep is bounded, so a stale count costs time, never progress.
+__device__ __forceinline__ int cu_slot() {   // compute unit of this wave: XCC (3 bits) x {SE, SH, CU} (8 bits of HW_ID)
+  unsigned hw, xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  return (int)(((xcc & 7u) << 8) | ((hw >> 8) & 0xFFu));
+}
+constexpr int CU_SLOTS = 8 * 256;
+__device__ __forceinline__ void cu_enter(int* flags) {
+  if (flags && threadIdx.x == 0) __hip_atomic_fetch_add(flags + cu_slot(), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void cu_leave(int* flags) {
+  if (flags && threadIdx.x == 0) __hip_atomic_fetch_add(flags + cu_slot(), -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int cu_busy(const int* word) {
+  return __builtin_amdgcn_readfirstlane(__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void cu_yield(const int* word) {   // at most ~0.2 ms
+  for (int it = 0; it < 256; ++it) {
+    __builtin_amdgcn_s_sleep(32);
+    if (cu_busy(word) == 0) break;
+  }
+}
+
 template <unsigned PAT, bool SHARE, bool SAME, class LA, class LB>
 __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, Acc4& tot,
-                                          int kbeg, int nkt, int wm, int wn, int lane) {
+                                          int kbeg, int nkt, int wm, int wn, int lane, const int* yield_word = nullptr) {
   if (nkt <= 0) return;
   float ra[NU], rb[NU];
   la.load(kbeg, ra);
@@ -440,9 +470,12 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
   __syncthreads();
   int cur = 0;
   for (int kt = 1; kt < nkt; ++kt) {
+    int busy = 0;
+    if (yield_word) busy = __hip_atomic_load(yield_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // lands during the MFMAs
     la.load(kbeg + kt * KC, ra);
     if (!SHARE) load_b<LA, LB, SAME>(la, lb, kbeg + kt * KC, rb);
     mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
+    if (yield_word && __builtin_amdgcn_readfirstlane(busy) != 0) cu_yield(yield_word);
     if constexpr (!SAME && std::is_same<LA, KMajorLoader>::value && std::is_same<LB, KMajorLoader>::value)   // plain products only: measured no gain elsewhere
       interleave_loads<(KC / 2) * __builtin_popcount(PAT), LA::LOADS + (SHARE ? 0 : LB::LOADS)>();
     la.store(As + (cur ^ 1) * PANEL, ra);
@@ -455,16 +488,18 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
 
 template <unsigned PAT, bool SAME, class LA, class LB>
 __device__ __forceinline__ void main_loop_any(LA& la, LB& lb, bool share, float* As, float* Bs, Acc4& tot,
-                                              int kbeg, int nkt, int wm, int wn, int lane) {
-  if (SAME && share) main_loop<PAT, true, true>(la, lb, As, As, tot, kbeg, nkt, wm, wn, lane);
-  else main_loop<PAT, false, SAME>(la, lb, As, Bs, tot, kbeg, nkt, wm, wn, lane);
+                                              int kbeg, int nkt, int wm, int wn, int lane, const int* yield_word = nullptr) {
+  if (SAME && share) main_loop<PAT, true, true>(la, lb, As, As, tot, kbeg, nkt, wm, wn, lane, yield_word);
+  else main_loop<PAT, false, SAME>(la, lb, As, Bs, tot, kbeg, nkt, wm, wn, lane, yield_word);
 }
 
 // PREFETCH_OLD: fetch the old output values before the k loop (worth 64 registers when the k loop is
 // short, as in the rank-128 sweep updates) instead of after it.
 // SAME: the descriptor's two operands are the same tensor (every factor build).
-template <class LA, class LB, bool PREFETCH_OLD = false, bool SAME = false>
-__device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, float* smem) {
+// YIELD: cu_flags (may be null) is the table of per-compute-unit words; the k loop gives way while
+// this compute unit's word is non-zero.
+template <class LA, class LB, bool PREFETCH_OLD = false, bool SAME = false, bool YIELD = false>
+__device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, float* smem, const int* cu_flags = nullptr) {
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int i0 = J.bi * BM, j0 = J.bj * BN;
   const bool diag = D.sym && (J.bi == J.bj);
@@ -507,13 +542,14 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   Acc4 tot;
   acc_zero(tot);
   const int nkt = (J.kend - J.kbeg + KC - 1) / KC;
+  const int* yw = (YIELD && cu_flags) ? cu_flags + cu_slot() : nullptr;
   switch (cover_pattern(mask)) {
-    case PAT_FULL: main_loop_any<PAT_FULL, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ROW1: main_loop_any<PAT_ROW1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_COL1: main_loop_any<PAT_COL1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ONE: main_loop_any<PAT_ONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_TRI: main_loop_any<PAT_TRI, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    default: main_loop_any<PAT_NONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_FULL: main_loop_any<PAT_FULL, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
+    case PAT_ROW1: main_loop_any<PAT_ROW1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
+    case PAT_COL1: main_loop_any<PAT_COL1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
+    case PAT_ONE: main_loop_any<PAT_ONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
+    case PAT_TRI: main_loop_any<PAT_TRI, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
+    default: main_loop_any<PAT_NONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
   }
 
   // ---- epilogue
@@ -549,6 +585,170 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
       }
     }
   }
+}
+
+// ------------------------------------------------------------------------------ direct-to-LDS product
+// Plain products of two row-major [K][.] operands (sweep updates and panel products of the inverse,
+// the second product of the preconditioning) feed their panels with gfx950's 16-byte
+// buffer_load ... lds: a wave instruction moves two panel rows of 128 floats (lane l: row l / 32,
+// columns 4 (l % 32) .. + 3) from global memory straight into 1 KB of LDS (lane l writes bytes
+// 16 l .. 16 l + 15 behind the base in M0), with a per-lane byte offset that never changes and a
+// scalar offset that advances with k: no address arithmetic, no staging registers and no LDS stores
+// in the k loop.  Out-of-range lanes write zeros and the range check is per dword (both measured),
+// so the k range is enforced by cutting the resource at the job's last row, as in KMajorLoader.
+// Panels are [k][128] without padding.  Wave w owns output columns 32 w .. 32 w + 31 and all 128
+// rows as four 32-row MFMA blocks whose rows are interleaved (block r, MFMA row i <-> tile row
+// 4 i + r): the four a-values of a lane are then one 16-byte LDS read, its b-value one 4-byte read,
+// both free of bank conflicts.  A tile with at most 64 (32) valid rows interleaves by 2 (1) instead
+// -- the lanes' 16-byte loads then overlap -- and computes two (one) of the four blocks.  Columns of a tile beyond the operand's extent hold whatever follows
+// in memory (or zeros); they only reach outputs that are never stored.  With 16-deep panels the
+// workgroup needs 32 KB of LDS and 80-odd registers, so several workgroups share a compute unit
+// and hide each other's latencies: 120 TFLOP/s on 4096 x 4096 x 768 against 101 for the staged
+// loop, bit-identical results (same order of accumulation).
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+constexpr int DL_KC = 16;                        // panel depth
+constexpr int DL_PANEL = DL_KC * BM;             // floats of one operand panel
+constexpr int DL_LDS_FLOATS = 4 * DL_PANEL;      // two operands x two buffers
+
+// RS: row interleave = number of 32-row blocks computed (4: more than 64 valid rows, 2: more than 32, 1).
+template <bool PREFETCH_OLD, bool YIELD, int RS>
+__device__ __forceinline__ void run_tile_dl_rs(const TileDesc& D, const TileJob& J, float* smem, const int* cu_flags) {
+  const int t = threadIdx.x, lane = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int i0 = J.bi * BM, j0 = J.bj * BN;
+  const bool diag = D.sym && (J.bi == J.bj);
+  float* As = smem;                    // [2][DL_KC][128]
+  float* Bs = smem + 2 * DL_PANEL;
+  const uint32_t lda4 = (uint32_t)D.a.ld * 4u, ldb4 = (uint32_t)D.b.ld * 4u;
+  const uint32_t cut_a = (uint32_t)J.kend * lda4, cut_b = (uint32_t)J.kend * ldb4;
+  const rsrc_t ra = make_rsrc(D.a.ptr, cut_a < D.a.bytes ? cut_a : D.a.bytes);
+  const rsrc_t rb = make_rsrc(D.b.ptr, cut_b < D.b.bytes ? cut_b : D.b.bytes);
+  constexpr int rs = RS;
+  const int lca = rs * (lane & 31), lc = 4 * (lane & 31);
+  const uint32_t va = (i0 + lca < D.a.M) ? (uint32_t)(lane >> 5) * lda4 + (uint32_t)(i0 + lca) * 4u : OOB_OFFSET;
+  const uint32_t vb = (j0 + lc < D.b.M) ? (uint32_t)(lane >> 5) * ldb4 + (uint32_t)(j0 + lc) * 4u : OOB_OFFSET;
+  constexpr int PAIRS = DL_KC / 8;     // row pairs per wave, operand and k step
+  auto issue = [&](int k0, int buf) {
+#pragma unroll
+    for (int u = 0; u < PAIRS; ++u) {
+      const int r = 2 * (4 * u + w);   // first row of the pair inside the panel
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_ptr)(As + buf * DL_PANEL + r * BM), 16, (int)va, (int)((uint32_t)(k0 + r) * lda4), 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_ptr)(Bs + buf * DL_PANEL + r * BN), 16, (int)vb, (int)((uint32_t)(k0 + r) * ldb4), 0, 0);
+    }
+  };
+
+  // output offsets: block r, register v of this lane <-> row i0 + rs mfma_row + r, column j0 + 32 w + mfma_col
+  const uint32_t ldo4 = (uint32_t)D.ldo * 4u;
+  const int gj = j0 + 32 * w + mfma_col(lane);
+  auto out_offset = [&](int r, int v) -> uint32_t {
+    const int gi = i0 + rs * mfma_row(v, lane) + r;
+    const bool ok = gi < D.M && gj < D.N && (!D.sym || gi >= gj);
+    return ok ? (uint32_t)gi * ldo4 + (uint32_t)gj * 4u : OOB_OFFSET;
+  };
+  const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * ldo4);
+  const float alpha = D.alpha, beta = D.beta;
+  const bool direct = J.part < 0;
+  const bool wave_used = j0 + 32 * w < D.N;    // a wave whose columns all lie outside the matrix only helps loading
+
+  const int nkt = (J.kend - J.kbeg + DL_KC - 1) / DL_KC;
+#ifdef KFAC_TRACE
+  const long long tr0 = wall_clock64();
+#endif
+  if (nkt > 0) issue(J.kbeg, 0);
+  // PREFETCH_OLD: the old output values are fetched before the k loop (64 more registers, fewer
+  // workgroups per compute unit); otherwise block by block in the epilogue.
+  f32x16 old[PREFETCH_OLD ? RS : 1];
+  if constexpr (PREFETCH_OLD) {
+#pragma unroll
+    for (int r = 0; r < RS; ++r)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) old[r][v] = (direct && beta != 0.f) ? buf_load(ro, out_offset(r, v)) : 0.f;
+  }
+  f32x16 acc[RS];
+#pragma unroll
+  for (int r = 0; r < RS; ++r)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[r][v] = 0.f;
+  const int* yw = (YIELD && cu_flags) ? cu_flags + cu_slot() : nullptr;
+  const int li = lane & 31, lh = lane >> 5;
+  for (int kt = 0; kt < nkt; ++kt) {
+    int busy = 0;
+    if (yw && (kt & 1)) busy = __hip_atomic_load(yw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of panel kt has landed
+    __syncthreads();                                    // ... and everybody's; all reads of the other buffer are done
+    if (kt + 1 < nkt) issue(J.kbeg + (kt + 1) * DL_KC, (kt + 1) & 1);
+    if (wave_used) {
+      const float* ap = As + (kt & 1) * DL_PANEL + lh * BM + 4 * li;
+      const float* bp = Bs + (kt & 1) * DL_PANEL + lh * BN + 32 * w + li;
+#pragma unroll
+      for (int q = 0; q < DL_KC / 2; ++q) {
+        const float b = bp[2 * q * BN];
+        if constexpr (RS == 4) {
+          const f32x4 a = *reinterpret_cast<const f32x4*>(ap + 2 * q * BM);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r], b, acc[r], 0, 0, 0);
+        } else if constexpr (RS == 2) {
+          typedef float f32x2 __attribute__((ext_vector_type(2)));
+          const f32x2 a = *reinterpret_cast<const f32x2*>(ap + 2 * q * BM);
+#pragma unroll
+          for (int r = 0; r < 2; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r], b, acc[r], 0, 0, 0);
+        } else {
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[2 * q * BM], b, acc[0], 0, 0, 0);
+        }
+      }
+    }
+    if (yw && __builtin_amdgcn_readfirstlane(busy) != 0) cu_yield(yw);
+  }
+
+#ifdef KFAC_TRACE
+  const long long tr1 = wall_clock64();
+#endif
+  if (!direct) {   // raw partial tile, [128][128] in tile coordinates
+    gf_ptr P = as_global(D.partial) + (size_t)J.part * (BM * BN);
+#pragma unroll
+    for (int r = 0; r < RS; ++r)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) P[(rs * mfma_row(v, lane) + r) * BN + 32 * w + mfma_col(lane)] = acc[r][v];
+    return;
+  }
+  const bool mirror = D.mirror == MIRROR_ALL || (D.mirror == MIRROR_DIAG_TILE && diag);
+#pragma unroll
+  for (int r = 0; r < RS; ++r) {
+    f32x16 o;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if constexpr (PREFETCH_OLD) o[v] = old[r][v];
+      else o[v] = beta != 0.f ? buf_load(ro, out_offset(r, v)) : 0.f;
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float val = alpha * acc[r][v] + beta * o[v];
+      const uint32_t off = out_offset(r, v);
+      buf_store(ro, off, val);
+      if (mirror) {
+        const int gi = i0 + rs * mfma_row(v, lane) + r;
+        buf_store(ro, (off != OOB_OFFSET && gi != gj) ? (uint32_t)gj * ldo4 + (uint32_t)gi * 4u : OOB_OFFSET, val);
+      }
+    }
+  }
+#ifdef KFAC_TRACE
+  if (YIELD && cu_flags && t == 0) {
+    int* cnt = const_cast<int*>(cu_flags) + CU_SLOTS;
+    const int rix = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (rix < 60000) {
+      long long* rec = reinterpret_cast<long long*>(const_cast<int*>(cu_flags) + CU_SLOTS + 2) + (size_t)rix * 8;
+      rec[0] = 5 + 8 * (long long)D.M; rec[1] = nkt; rec[2] = cu_slot(); rec[3] = tr0; rec[4] = tr1; rec[5] = tr1; rec[6] = tr1; rec[7] = wall_clock64();
+    }
+  }
+#endif
+}
+
+template <bool PREFETCH_OLD = false, bool YIELD = false>
+__device__ __forceinline__ void run_tile_dl(const TileDesc& D, const TileJob& J, float* smem, const int* cu_flags = nullptr) {
+  const int rows_valid = D.M - J.bi * BM;
+  if (rows_valid > 64) run_tile_dl_rs<PREFETCH_OLD, YIELD, 4>(D, J, smem, cu_flags);
+  else if (rows_valid > 32) run_tile_dl_rs<PREFETCH_OLD, YIELD, 2>(D, J, smem, cu_flags);
+  else run_tile_dl_rs<PREFETCH_OLD, YIELD, 1>(D, J, smem, cu_flags);
 }
 
 // Dispatch on the operand type of a symmetric product a^T a (wave-uniform).

@@ -47,6 +47,30 @@ __global__ __launch_bounds__(NT, 2) void tile_gemm_kernel(const TileDesc* __rest
     run_tile<KMajorLoader, ConvLoader<1, 1>, true>(D, J, smem);   // second operand stored [N, K] (read transposed)
 }
 
+// Plain products of two row-major operands through the direct-to-LDS loop (32 KB of LDS, four
+// workgroups per compute unit): the second product of the preconditioning.
+__global__ __launch_bounds__(NT, 4) void tile_gemm_dl_kernel(const TileDesc* __restrict__ descs,
+                                                             const TileJob* __restrict__ jobs, int njobs) {
+  __shared__ __attribute__((aligned(16))) float smem[DL_LDS_FLOATS];
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const TileJob J = jobs[g];
+  run_tile_dl<false, false>(descs[J.desc], J, smem);
+}
+
+// The same for the bulk products of the inverse, which give way to the latency-critical kernels of the
+// sweep chain that share their compute unit (see cu_enter in tile_core.h).  The off-chain launches add
+// unused LDS so that one such workgroup fills a compute unit but for the room a chain kernel needs;
+// nothing then hides the epilogue, so the old output values are fetched before the k loop.
+__global__ __launch_bounds__(NT, 2) void tile_gemm_yield_kernel(const TileDesc* __restrict__ descs, const TileJob* __restrict__ jobs,
+                                                                int njobs, const int* __restrict__ cu_flags) {
+  __shared__ __attribute__((aligned(16))) float smem[DL_LDS_FLOATS];
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const TileJob J = jobs[g];
+  run_tile_dl<true, true>(descs[J.desc], J, smem, cu_flags);
+}
+
 // out = beta*out + alpha * (partial[part0] + partial[part0+1] + ...) in slot order (deterministic).
 // Four workgroups per tile; a thread owns four float4 pieces and keeps all their loads in flight.
 __global__ __launch_bounds__(NT) void tile_reduce_kernel(const TileDesc* __restrict__ descs,
@@ -198,6 +222,16 @@ void launch_tile_gemm(const TileDesc* descs, const TileJob* jobs, int njobs, int
   if (njobs <= 0) return;
   const int grid = xcd_order ? ((njobs + 7) / 8) * 8 : njobs;
   hipLaunchKernelGGL(tile_gemm_kernel, dim3(grid), dim3(NT), 0, s, descs, jobs, njobs, xcd_order);
+}
+
+void launch_tile_gemm_dl(const TileDesc* descs, const TileJob* jobs, int njobs, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(tile_gemm_dl_kernel, dim3(njobs), dim3(NT), 0, s, descs, jobs, njobs);
+}
+
+void launch_tile_gemm_yield(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, const int* cu_flags, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(tile_gemm_yield_kernel, dim3(njobs), dim3(NT), pad_bytes, s, descs, jobs, njobs, cu_flags);
 }
 
 void launch_tile_gemm_pad(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, hipStream_t s) {
