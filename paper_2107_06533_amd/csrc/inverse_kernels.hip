@@ -409,7 +409,7 @@ __global__ __launch_bounds__(NT) void gj_pivot_update_kernel(const InvMat* __res
     cu_leave(mine);
   } else if (g - npiv < nupd) {
     const TileJob J = ujobs[g - npiv];
-    run_tile_dl<false, true>(descs[J.desc], J, smem, cu_flags);
+    run_tile_dl<true, true>(descs[J.desc], J, smem, cu_flags);
   }
 }
 
