@@ -97,6 +97,41 @@ def cpu_baseline(layers, hp, budget_s, flops_total):
     }
 
 
+def cpu_baseline_small(names=("fc", "cnn")):
+    """The oracle on the two small workloads, whole and unsampled (fc: its 3 steps), with all host
+    threads and with one: 1 warm-up + 3 runs each, median."""
+    import numpy as np
+    import oracle
+    from synth import inputs, shapes
+    from threadpoolctl import threadpool_limits
+    out = {}
+    for name in names:
+        hp = shapes.config_hparams(name)
+        layers = shapes.config_layers(name)
+        steps = 3 if name == "fc" else 1
+        ins = [[inputs.layer_inputs(l, hp["cid"], st, i, hp["relu"]) for i, l in enumerate(layers)] for st in range(steps)]
+
+        def run():
+            A = [np.eye(l.dA) for l in layers]
+            G = [np.eye(l.dG) for l in layers]
+            for st in range(steps):
+                a, g, v = zip(*ins[st])
+                A, G, _, _, _ = oracle.kfac_step(layers, a, g, v, A, G, hp["xi"], hp["gamma"])
+
+        res = {}
+        for label, limit in (("all_threads_ms", None), ("one_thread_ms", 1)):
+            ts = []
+            with threadpool_limits(limits=limit):
+                for rep in range(4):
+                    t0 = time.perf_counter()
+                    run()
+                    ts.append((time.perf_counter() - t0) * 1e3)
+            res[label] = round(float(np.median(ts[1:])), 2)
+        res["steps"] = steps
+        out[name] = res
+    return out
+
+
 def fit_inverse_model(pk, torch, np):
     """The paper's computation model of the inverse (Eq. inverting-model) fitted to this GPU with the
     paper's protocol: matrices of dimension 64 .. 8192, 10 warm-up and 100 timed runs each."""
@@ -209,9 +244,15 @@ def main():
     torch.cuda.synchronize()
     wall_s = time.perf_counter() - t0
     ms_per_step = wall_s * 1e3 / args.steps
+    per_call = [[], [], []]
+    step_ev_ms = []
     for e in evs:
         for k in range(3):
-            call_ms[k] += e[k].elapsed_time(e[k + 1]) / args.steps
+            t = e[k].elapsed_time(e[k + 1])
+            call_ms[k] += t / args.steps
+            per_call[k].append(t)
+        step_ev_ms.append(e[0].elapsed_time(e[3]))
+    call_median = [float(np.median(x)) for x in per_call]
     dom_ms, dom_n = ctx.timing_read("factor_tiles")
     ctx.timing_enable([])
     assert int(info.abs().sum()) == 0, "a factor was reported not positive definite"
@@ -308,13 +349,22 @@ def main():
     # flops the tile jobs really execute (tile granularity): fewer than the algorithmic count where
     # 3x3 activation factors are assembled from lag products, more where tiles are ragged
     executed = {name: ctx.plan_stats(i)["mfma_flops"] for i, name in enumerate(("update_factors", "invert_batch", "precondition"))}
-    traffic = None
+    # HBM bytes per launch of the dominant kernel: rocprofv3 counters cannot be read from inside this
+    # process, so the figure comes from the committed counter summary of the same command line
+    # (profiles/traffic.json, written by `python -m paper_2107_06533_amd.profile_summary`)
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.config, {}).get("factor_tiles_bytes_per_launch")
+            rec = json.load(open(tpath)).get(args.config, {})
+            traffic = rec.get("factor_tiles_bytes_per_launch")
+            traffic_src = f"{rec.get('source')} (rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this command, not this run)" if traffic else None
         except Exception:
             traffic = None
+    inv_stats, pre_stats = ctx.plan_stats(1), ctx.plan_stats(2)
+    nblk_max = max((d + 127) // 128 for d in dims)
+    right = (breakdown or {}).get("precond_right", {}).get("ms_per_step")
+    pre_right_flops = sum(2 * l.dG * l.dA * l.dA for l in layers)
     out = {
         "metric": "kfac_step_ms (factors + inverses + precondition)",
         "value": round(ms_per_step, 4),
@@ -332,25 +382,52 @@ def main():
                    "xi": hp["xi"], "gamma": hp["gamma"], "setup_s": round(setup_s, 1)},
         "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 2),
         "frac_of_fp32_mfma_peak": round(fl["total"] / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+        "ms_per_step_median": round(float(np.median(step_ev_ms)), 4),
+        # per call: mean and median of the K timed steps (HIP events on the caller's stream); tflops and
+        # frac_peak by the ALGORITHMIC flop count, frac_peak_executed by the flops the tile jobs execute
+        # (what the matrix cores sustain: lower where lag products skip work, higher where tiles are ragged)
         "calls": {
-            "update_factors": {"ms": round(call_ms[0], 4), "tflops": round(factor_flops / call_ms[0] / 1e9, 2),
-                               "frac_peak": round(factor_flops / call_ms[0] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)},
-            "invert_batch": {"ms": round(call_ms[1], 4), "tflops": round(fl["inverse"] / call_ms[1] / 1e9, 2),
-                             "frac_peak": round(fl["inverse"] / call_ms[1] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)},
-            "precondition": {"ms": round(call_ms[2], 4), "tflops": round(fl["precondition"] / call_ms[2] / 1e9, 2),
-                             "frac_peak": round(fl["precondition"] / call_ms[2] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)},
+            name: {"ms": round(call_ms[k], 4), "ms_median": round(call_median[k], 4),
+                   "tflops": round(alg / call_ms[k] / 1e9, 2),
+                   "frac_peak": round(alg / call_ms[k] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+                   "frac_peak_executed": round(executed[name] / call_ms[k] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)}
+            for k, (name, alg) in enumerate((("update_factors", factor_flops), ("invert_batch", fl["inverse"]),
+                                             ("precondition", fl["precondition"])))
         },
         "algorithmic_flops": fl,
         "roofline": {
             "kernel": "tile_any_kernel (grouped factor build, one launch per step)",
             "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": traffic,
+            "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": traffic, "traffic_source": traffic_src,
+            "basis": "achieved and frac credit the ALGORITHMIC flops R*d*(d+1) per factor; lag products execute fewer, so the "
+                     "utilisation of the matrix cores is executed_frac (algorithmic frac may exceed it, and 1, on lag-heavy sets)",
             "avg_launch_ms": round(dom_avg_ms, 4), "flops_per_launch": factor_flops,
             "executed_flops_per_launch": executed["update_factors"],
             "executed_tflops": round(executed["update_factors"] / (dom_avg_ms * 1e-3) / 1e12, 2),
             "executed_frac": round(executed["update_factors"] / (dom_avg_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
         },
         "executed_flops": executed,
+        # the other two calls against the same roofline (whole call, mean of the timed steps)
+        "roofline_calls": {
+            "invert_batch": {
+                "bound": "mfma", "achieved": round(fl["inverse"] / call_ms[1] / 1e9, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(fl["inverse"] / call_ms[1] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+                "executed_frac": round(executed["invert_batch"] / call_ms[1] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+                "launches_per_call": inv_stats["n_launches"],
+                # the sweep is a chain of dependent pivot blocks: that of the largest matrix bounds the call from below
+                "critical_path": {"pivot_blocks": nblk_max, "ms_per_pivot_block": round(call_ms[1] / nblk_max, 4),
+                                  "note": "call time / pivot blocks of the largest matrix; in-kernel times of one chain step "
+                                          "(pivot block sweep + panel) are in the design notes"}},
+            "precondition": {
+                "bound": "mfma", "achieved": round(fl["precondition"] / call_ms[2] / 1e9, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(fl["precondition"] / call_ms[2] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+                "executed_frac": round(executed["precondition"] / call_ms[2] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+                "launches_per_call": pre_stats["n_launches"],
+                "right_product": None if not right else {
+                    "kernel": "tile_gemm_dl_kernel (out = T . Ainv, direct-to-LDS loop)", "ms": right,
+                    "tflops": round(pre_right_flops / right / 1e9, 2),
+                    "frac": round(pre_right_flops / right / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)}},
+        },
     }
     if breakdown is not None:
         out["kernel_breakdown"] = breakdown
@@ -360,6 +437,7 @@ def main():
         out["stale_inverses"] = stale
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(layers, hp, args.cpu_budget, fl["total"])
+        out["cpu_baseline_small"] = cpu_baseline_small()
     ctx.close()
     print(json.dumps(out))
 
