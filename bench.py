@@ -314,6 +314,21 @@ def main():
         torch.cuda.synchronize()
         packed_io["invert_packed_ms"] = round(ev_q[0].elapsed_time(ev_q[1]) / reps, 4)
         packed_io["invert_then_pack_ms"] = round(ev_q[1].elapsed_time(ev_q[2]) / reps, 4)
+        # factor build with the packed triangles written by the same kernels, against factor build + pack
+        ev_f = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for _ in range(2):
+            ctx.kfac_update_factors_packed(layers, a_d, g_d, A_d, G_d, hp["xi"], pbuf, stream=stream)
+        ev_f[0].record(stream)
+        for _ in range(reps):
+            ctx.kfac_update_factors_packed(layers, a_d, g_d, A_d, G_d, hp["xi"], pbuf, stream=stream)
+        ev_f[1].record(stream)
+        for _ in range(reps):
+            ctx.kfac_update_factors(layers, a_d, g_d, A_d, G_d, hp["xi"], stream=stream)
+            ctx.kfac_pack_triangles(dims, A_d + G_d, pbuf, stream=stream)
+        ev_f[2].record(stream)
+        torch.cuda.synchronize()
+        packed_io["update_packed_ms"] = round(ev_f[0].elapsed_time(ev_f[1]) / reps, 4)
+        packed_io["update_then_pack_ms"] = round(ev_f[1].elapsed_time(ev_f[2]) / reps, 4)
         del pbuf
         step()          # the unpack above overwrote the inverses: restore a consistent state
         torch.cuda.synchronize()

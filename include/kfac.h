@@ -137,6 +137,20 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n_layers, const kfac_layer* l
                                 float xi, float scale_a, float scale_g, void* hip_stream);
 
 /*
+ * The same call with a second output (Sec. IV-A: a worker communicates d(d+1)/2 elements per
+ * symmetric factor; Sec. V-B: the upper triangle including the diagonal): `packed` (device buffer)
+ * receives the packed upper triangles of the updated factors, all A_l in layer order followed by all
+ * G_l -- the layout kfac_pack_triangles produces for the matrix list (A_0 .. A_{n-1}, G_0 .. G_{n-1}),
+ * kfac_packed_elems over (dA_0 .. dA_{n-1}, dG_0 .. dG_{n-1}) floats -- written by the kernels that
+ * write the factors, bit-identical to packing them afterwards.  The segment of a factor that is
+ * skipped (NULL act / gout entry) is left untouched.  packed must not be NULL.
+ */
+kfac_status kfac_update_factors_packed(kfac_ctx* ctx, int n_layers, const kfac_layer* layers,
+                                       const float* const* act, const float* const* gout,
+                                       float* const* A, float* const* G,
+                                       float xi, float scale_a, float scale_g, float* packed, void* hip_stream);
+
+/*
  * Damped inverse of a heterogeneous set of symmetric positive-definite matrices
  * (Sec. II-B: Tikhonov term gamma I added before inverting; Sec. IV-B: N tensors
  * T_i in R^{d_i x d_i}, the same f applied to each):

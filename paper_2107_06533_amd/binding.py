@@ -14,7 +14,7 @@ EXPORTS = [
     "kfac_create", "kfac_destroy", "kfac_last_error",
     "kfac_layer_dA", "kfac_layer_dG", "kfac_layer_rows",
     "kfac_workspace_bytes_factors", "kfac_workspace_bytes_invert", "kfac_workspace_bytes_precondition",
-    "kfac_update_factors", "kfac_invert_batch", "kfac_invert_batch_packed", "kfac_check_info", "kfac_precondition",
+    "kfac_update_factors", "kfac_update_factors_packed", "kfac_invert_batch", "kfac_invert_batch_packed", "kfac_check_info", "kfac_precondition",
     "kfac_packed_elems", "kfac_pack_triangles", "kfac_unpack_triangles", "kfac_place_inversions",
     "kfac_get_plan_stats", "kfac_timing_enable", "kfac_timing_read",
     "kfac_set_option", "kfac_get_option", "kfac_precondition_noalloc",
@@ -91,6 +91,8 @@ def load():
     lib.kfac_workspace_bytes_precondition.restype = C.c_size_t
     lib.kfac_update_factors.argtypes = [vp, C.c_int, lp, fpp, fpp, fpp, fpp, C.c_float, C.c_float, C.c_float, vp]
     lib.kfac_update_factors.restype = C.c_int
+    lib.kfac_update_factors_packed.argtypes = [vp, C.c_int, lp, fpp, fpp, fpp, fpp, C.c_float, C.c_float, C.c_float, vp, vp]
+    lib.kfac_update_factors_packed.restype = C.c_int
     lib.kfac_invert_batch.argtypes = [vp, C.c_int, i32p, fpp, fpp, C.c_float, vp, vp]
     lib.kfac_invert_batch.restype = C.c_int
     lib.kfac_invert_batch_packed.argtypes = [vp, C.c_int, i32p, fpp, fpp, vp, C.c_float, vp, vp]
@@ -222,6 +224,17 @@ class Context:
         st = self.lib.kfac_update_factors(self.h, n, arr, _ptr_array(act, n), _ptr_array(gout, n),
                                           _ptr_array(A, n), _ptr_array(G, n),
                                           float(xi), float(scale_a), float(scale_g), _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def kfac_update_factors_packed(self, layers, act, gout, A, G, xi: float, packed, scale_a: float = 0.0,
+                                   scale_g: float = 0.0, stream=None, check: bool = True) -> int:
+        n = len(layers)
+        arr = (layer_struct * max(n, 1))(*[make_layer(l) for l in layers])
+        st = self.lib.kfac_update_factors_packed(self.h, n, arr, _ptr_array(act, n), _ptr_array(gout, n),
+                                                 _ptr_array(A, n), _ptr_array(G, n),
+                                                 float(xi), float(scale_a), float(scale_g), _ptr(packed), _stream_handle(stream))
         if check:
             self._check(st)
         return st

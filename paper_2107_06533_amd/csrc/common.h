@@ -77,6 +77,8 @@ struct TileDesc {
   Operand a, b;
   float* out;
   float* partial;   // split-reduction slots, [slot][BM*BN]
+  float* packed;    // symmetric outputs, may be null: packed upper triangle of out (element (i, j), i <= j, at
+                    // i*M - i*(i-1)/2 + (j - i)), written by the kernel that writes out
   int32_t ldo;
   int32_t M, N;     // output extents
   int32_t sym;      // 1: only tiles bi >= bj exist; a diagonal tile stages one panel, skips blocks above the diagonal
@@ -114,6 +116,7 @@ enum : int32_t { LAG_G1 = 0, LAG_G2, LAG_TOP, LAG_BOT, LAG_LEFT, LAG_RIGHT, LAG_
 struct LagAsm {
   const float* G[LAG_NMAT];   // G1 [C][10C], G2 [C][3C + bias], rows/columns [C][15C + bias], corners [C][9C + bias]
   float* A;                   // [dA][dA], dA = 9C + bias
+  float* P;                   // may be null: packed upper triangle of A, dA (dA + 1) / 2 floats
   int32_t C, bias, dA, pad0;
   float alpha, beta;          // A <- beta * A + alpha * (assembled sums)
   float rows;                 // number of rows R (the bias-bias entry sums R ones)

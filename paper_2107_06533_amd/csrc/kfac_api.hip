@@ -963,10 +963,13 @@ kfac_status kfac_timing_read(kfac_ctx* ctx, int kclass, double* total_ms, int64_
 }
 
 // ----------------------------------------------------------------------------------- factors
-kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
-                                const float* const* act, const float* const* gout,
-                                float* const* A, float* const* G,
-                                float xi, float scale_a, float scale_g, void* hip_stream) {
+// kfac_update_factors and kfac_update_factors_packed: `packed` (may be NULL) additionally receives the
+// packed upper triangles of the updated factors (all A in layer order, then all G), written by the
+// kernels that write the factors.
+static kfac_status update_factors_impl(kfac_ctx* ctx, int n, const kfac_layer* layers,
+                                       const float* const* act, const float* const* gout,
+                                       float* const* A, float* const* G,
+                                       float xi, float scale_a, float scale_g, float* packed, void* hip_stream) {
   if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_update_factors: ctx is NULL");
   if (n < 0) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors: n_layers < 0");
   if (n == 0) return KFAC_OK;
@@ -1029,6 +1032,16 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
   kfac_status st = ensure_ws(ctx, WS_FACTORS, (slot_floats + P.lag_floats) * sizeof(float));
   if (st != KFAC_OK) return st;
   float* lag_ws = static_cast<float*>(ctx->ws[WS_FACTORS]) + slot_floats;
+  std::vector<size_t> packed_off(2 * size_t(n), 0);   // float offset of A_l (entry l) and G_l (entry n + l) in `packed`
+  {
+    size_t off = 0;
+    for (int which = 0; which < 2; ++which)
+      for (int l = 0; l < n; ++l) {
+        const size_t d = size_t(which == 0 ? dA_of(P.layers[l]) : P.layers[l].c_out);
+        packed_off[size_t(which) * n + l] = off;
+        off += d * (d + 1) / 2;
+      }
+  }
   std::vector<uint8_t> is_lag(n, 0);
   for (const LagLayer& lg : P.lags) is_lag[lg.layer] = 1;
   for (int l = 0; l < n; ++l)
@@ -1039,6 +1052,7 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
       D.a.ptr = which == 0 ? act[l] : gout[l];
       D.b.ptr = D.a.ptr;
       D.out = which == 0 ? A[l] : G[l];
+      D.packed = packed ? packed + packed_off[size_t(which) * n + l] : nullptr;
       D.partial = static_cast<float*>(ctx->ws[WS_FACTORS]);
       const float sc = which == 0 ? scale_a : scale_g;
       const float scale = sc > 0.f ? sc : float(1.0 / double(D.a.K));
@@ -1059,6 +1073,7 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
     }
     const double rows = double(rows_of(L));
     Q.A = A[lg.layer];
+    Q.P = packed ? packed + packed_off[lg.layer] : nullptr;
     Q.C = L.c_in; Q.bias = L.has_bias; Q.dA = dA_of(L);
     Q.alpha = (1.f - xi) * (scale_a > 0.f ? scale_a : float(1.0 / rows));
     Q.beta = xi;
@@ -1083,6 +1098,21 @@ kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
   }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;
+}
+
+kfac_status kfac_update_factors(kfac_ctx* ctx, int n, const kfac_layer* layers,
+                                const float* const* act, const float* const* gout,
+                                float* const* A, float* const* G,
+                                float xi, float scale_a, float scale_g, void* hip_stream) {
+  return update_factors_impl(ctx, n, layers, act, gout, A, G, xi, scale_a, scale_g, nullptr, hip_stream);
+}
+
+kfac_status kfac_update_factors_packed(kfac_ctx* ctx, int n, const kfac_layer* layers,
+                                       const float* const* act, const float* const* gout,
+                                       float* const* A, float* const* G,
+                                       float xi, float scale_a, float scale_g, float* packed, void* hip_stream) {
+  if (ctx && n > 0 && !packed) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_update_factors_packed: packed is NULL");
+  return update_factors_impl(ctx, n, layers, act, gout, A, G, xi, scale_a, scale_g, packed, hip_stream);
 }
 
 // ----------------------------------------------------------------------------------- inverse

@@ -583,6 +583,11 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
         const int gj = j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane);
         buf_store(ro, (off != OOB_OFFSET && gi != gj) ? (uint32_t)gj * ldo4 + (uint32_t)gi * 4u : OOB_OFFSET, val);
       }
+      if (D.packed && off != OOB_OFFSET) {   // stored element (gi, gj), gi >= gj, is element (gj, gi) of the upper triangle
+        const size_t gi = (size_t)(i0 + wm * 64 + (qd >> 1) * 32 + mfma_row(v, lane));
+        const size_t gj = (size_t)(j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane));
+        as_global(D.packed)[gj * (size_t)D.M - gj * (gj - 1) / 2 + (gi - gj)] = val;
+      }
     }
   }
 }

@@ -120,6 +120,8 @@ __global__ __launch_bounds__(NT) void tile_reduce_kernel(const TileDesc* __restr
       buf_store(ro, off[u][c], val);
       if (mirror)
         buf_store(ro, (off[u][c] != OOB_OFFSET && gi != gj) ? (uint32_t)gj * ldo4 + (uint32_t)gi * 4u : OOB_OFFSET, val);
+      if (D.packed && D.sym && off[u][c] != OOB_OFFSET)   // element (gj, gi) of the upper triangle
+        as_global(D.packed)[(size_t)gj * D.M - (size_t)gj * (gj - 1) / 2 + (size_t)(gi - gj)] = val;
     }
   }
 }
@@ -202,13 +204,17 @@ __global__ __launch_bounds__(NT) void lag_assemble_kernel(const LagAsm* __restri
     const float val = L.alpha * v[u] + L.beta * old[u];
     tile[lr][lc] = val;
     if (r < dA && cc <= r) A[(uint32_t)r * (uint32_t)dA + (uint32_t)cc] = val;
+    if (L.P && r < dA && cc == r) as_global(L.P)[(size_t)r * dA - (size_t)r * (r - 1) / 2] = val;
   }
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
     const int lr = lr0 + 4 * u;
     const int r = J.bj * LAG_TILE + lr, c = J.bi * LAG_TILE + lc;   // element (r, c) of the mirrored tile = tile[lc][lr]
-    if (c < dA && r < c) A[(uint32_t)r * (uint32_t)dA + (uint32_t)c] = tile[lc][lr];
+    if (c < dA && r < c) {
+      A[(uint32_t)r * (uint32_t)dA + (uint32_t)c] = tile[lc][lr];
+      if (L.P) as_global(L.P)[(size_t)r * dA - (size_t)r * (r - 1) / 2 + (size_t)(c - r)] = tile[lc][lr];   // row r of the upper triangle
+    }
   }
 }
 

@@ -443,3 +443,53 @@ def test_precondition_with_last_inverses_while_inverting(ctx):
         for X_t, F_ref in ((X_new[i], A_ref[i]), (X_new[n + i], G_ref[i])):
             res = inv_residual(F_ref, hp["gamma"], host64(X_t))
             assert res <= TOL_INVERSE, f"layer {i}: new inverse residual {res:.3e}"
+
+
+# ------------------------------------------------------------------------------ packed factor output
+def test_update_factors_packed_output(ctx):
+    """kfac_update_factors_packed: the packed triangles written with the factors (all A in layer order,
+    then all G) are, bit for bit, the oracle's packing of the factors the same call returns, on every
+    kernel that writes a factor: tiles written directly, split reductions, lag-product assembly,
+    linear layers; the factors themselves meet the usual bar against the oracle's factors, and the
+    segment of a skipped factor is left untouched."""
+    import torch
+    layers = [shapes.linear(50, 70, 33, name="lin"),                      # direct tiles, ones column
+              shapes.conv(2, 20, 12, 11, 200, 3, 1, 1, name="c3"),        # 3x3 patch product, dA = 181
+              shapes.conv(2, 64, 6, 6, 16, 3, 1, 1, name="lag"),          # lag products, dA = 577
+              shapes.conv(40, 4, 16, 16, 140, 1, 1, 0, name="split"),     # R = 10240: split reduction of G (140) and A (5)
+              shapes.conv(3, 16, 10, 10, 130, 1, 2, 0, name="s2")]        # strided 1x1
+    hp = dict(cid=9, relu=True)
+    ins = [inputs.layer_inputs(l, hp["cid"], 0, i, hp["relu"]) for i, l in enumerate(layers)]
+    acts, gouts, _ = zip(*ins)
+    gouts = [g * 1e3 for g in gouts]                                       # gradients of size one: the new term counts
+    xi = 0.3
+    rng = np.random.default_rng(5)
+    def old(d):
+        B = rng.standard_normal((d, d)).astype(np.float32)
+        return ((B @ B.T) / d).astype(np.float32)
+    A0, G0 = [old(l.dA) for l in layers], [old(l.dG) for l in layers]
+    a_d, g_d = [dev(x) for x in acts], [dev(x) for x in gouts]
+    A_d, G_d = [dev(x) for x in A0], [dev(x) for x in G0]
+    dims = [l.dA for l in layers] + [l.dG for l in layers]
+    tot, off = ctx.packed_elems(dims)
+    packed = torch.full((tot,), float("nan"), device="cuda")
+    g_skip = list(g_d)
+    g_skip[1] = None                                                       # G of layer 1 is not updated
+    ctx.kfac_update_factors_packed(layers, a_d, g_skip, A_d, G_d, xi, packed)
+    torch.cuda.synchronize()
+    got = packed.cpu().numpy()
+    n = len(layers)
+    for i, l in enumerate(layers):
+        A32, G32 = A_d[i].cpu().numpy(), G_d[i].cpu().numpy()
+        assert np.array_equal(got[off[i]:off[i] + oracle.packed_size(l.dA)], oracle.pack_upper(A32)), f"{l.name}: packed A"
+        wantA = oracle.update_factor_A(l, acts[i], A0[i].astype(np.float64), xi)
+        assert rel_fro(A32.astype(np.float64), wantA) <= TOL_FACTOR, l.name
+        seg = got[off[n + i]:off[n + i] + oracle.packed_size(l.dG)]
+        if i == 1:
+            assert np.all(np.isnan(seg)), "segment of a skipped factor was written"
+            assert np.array_equal(G32, G0[i])
+            continue
+        assert np.array_equal(seg, oracle.pack_upper(G32)), f"{l.name}: packed G"
+        wantG = oracle.update_factor_G(l, gouts[i], G0[i].astype(np.float64), xi)
+        assert rel_fro(G32.astype(np.float64), wantG) <= TOL_FACTOR, l.name
+    assert ctx.kfac_update_factors_packed(layers, a_d, g_d, A_d, G_d, xi, None, check=False) == 1   # packed is required
