@@ -162,6 +162,13 @@ kfac_status kfac_update_factors_packed(kfac_ctx* ctx, int n_layers, const kfac_l
  *     on success or to k > 0 when the leading minor of order k of F_i + gamma I is not
  *     positive (LAPACK convention); X_i is then unspecified, other matrices are still
  *     valid.  Read it after the stream has finished, e.g. with kfac_check_info.
+ * Accuracy: the sweep runs in fp32 without pivoting, so the residual
+ *     r = ||(F + gamma I) X - I||_F / sqrt(d)   grows with  kappa = cond(F + gamma I);
+ *     measured on MI355X (d = 1153, eigenvalues log-spaced between 1 and kappa, the hardest spectrum):
+ *     r = 9e-6 at kappa 1e2, 4e-5 at 3e2, 2.4e-4 at 1e3, 8.5e-3 at 1e4, below 4 kappa^1.75 2^-24 throughout.
+ *     The bar r <= 1e-4 therefore holds for arbitrary spectra up to kappa = 3e2; K-FAC factors in steady state
+ *     (a few large eigenvalues over a bulk near gamma) stay within it up to kappa of about 1e3 (1.4e-5 at
+ *     kappa 914).  Past that, info stays 0 and r follows the envelope: raise gamma, or invert in fp64.
  * Returns INVALID_ARG for: NULL ctx/dims/F/X, n_mats < 0, d_i < 1, NULL or aliased
  * entries, gamma negative or NaN.  n_mats == 0 is a no-op.
  */
