@@ -52,7 +52,8 @@ class plan_stats(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libkfac_hip.so")
+    # KFAC_HIP_LIBRARY: another build of the same library (the host-sanitized one of build.py), for tests
+    return os.environ.get("KFAC_HIP_LIBRARY") or os.path.join(_HERE, "libkfac_hip.so")
 
 
 def is_built() -> bool:

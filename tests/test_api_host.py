@@ -208,3 +208,34 @@ def test_options_change_the_schedule_not_the_environment(hctx, monkeypatch):
         assert with_lag["ws_bytes"] > without["ws_bytes"]
     finally:
         c.close()
+
+
+@pytest.mark.parametrize("name", ["fc", "cnn", "r50", "r152", "bertl", "d201", "iv4"])
+@pytest.mark.parametrize("opts", [{}, {"inv_groups": 1, "inv_agg": 2, "inv_agg_chain": 3, "inv_fuse": 0, "factor_lag": 0, "factor_xcd": 1, "factor_kjob": 1024}])
+def test_host_only_planning_of_every_workload(name, opts):
+    """Every workload's three schedules are built on a host-only context (all index arithmetic of the
+    planners runs; nothing is launched), under the default and under non-default options.  This is
+    also the case a host build with address / undefined-behaviour sanitizers is run on."""
+    c = pk.Context(-1)
+    try:
+        for k, v in opts.items():
+            c.set_option(k, v)
+        ls = shapes.config_layers(name)
+        n = len(ls)
+        alg = shapes.flops(ls)
+        assert c.kfac_update_factors(ls, [1] * n, [1] * n, [1] * n, [1] * n, 0.95, check=False) == pk.KFAC_ERR_DEVICE
+        st = c.plan_stats(0)
+        assert st["n_jobs"] > 0 and st["ws_bytes"] == c.workspace_bytes_factors(ls)
+        assert 0.3 * (alg["factor_a"] + alg["factor_g"]) <= st["mfma_flops"]
+        dims = [l.dA for l in ls] + [l.dG for l in ls]
+        assert c.kfac_invert_batch(dims, [1] * 2 * n, [2] * 2 * n, 0.03, check=False) == pk.KFAC_ERR_DEVICE
+        st = c.plan_stats(1)
+        large = sum(d ** 3 for d in dims if d > 128)             # one-block matrices take the in-register path
+        assert 0.9 * large <= st["mfma_flops"] and st["n_launches"] >= 1
+        assert st["ws_bytes"] <= c.workspace_bytes_invert(dims)
+        assert c.kfac_precondition([l.dG for l in ls], [l.dA for l in ls], [1] * n, [2] * n, [3] * n, [4] * n, check=False) == pk.KFAC_ERR_DEVICE
+        assert alg["precondition"] <= c.plan_stats(2)["mfma_flops"]
+        tot, off = c.packed_elems(dims)
+        assert tot == sum(d * (d + 1) // 2 for d in dims) and len(off) >= 2 * n
+    finally:
+        c.close()
