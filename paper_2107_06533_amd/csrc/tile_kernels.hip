@@ -16,6 +16,9 @@ __device__ __forceinline__ int xcd_job_index(int g, int n) {
 #ifndef KFAC_WAVES
 #define KFAC_WAVES 2
 #endif
+#ifdef KFAC_TRACE
+__device__ long long* g_factor_trace = nullptr;   // debugging aid: [0] = record count, then 4 words per tile job
+#endif
 __global__ __launch_bounds__(NT, KFAC_WAVES) void tile_any_kernel(const TileDesc* __restrict__ descs,
                                                          const TileJob* __restrict__ jobs, int njobs,
                                                          int xcd_order) {
@@ -26,9 +29,41 @@ __global__ __launch_bounds__(NT, KFAC_WAVES) void tile_any_kernel(const TileDesc
   const TileJob J = jobs[g];
   if (J.desc < 0) return;   // padding of an XCD segment
   const TileDesc& D = descs[J.desc];
+#ifdef KFAC_TRACE
+  const long long t0 = wall_clock64();
+#endif
   if (D.sym) run_tile_sym(D, J, smem);
   else run_tile_lag(D, J, smem);
+#ifdef KFAC_TRACE
+  if (g_factor_trace && threadIdx.x == 0) {
+    const unsigned long long r = atomicAdd((unsigned long long*)g_factor_trace, 1ull);
+    if (r < 100000) {
+      long long* rec = g_factor_trace + 1 + r * 4;
+      rec[0] = ((long long)D.a.type << 8) | ((long long)D.b.type << 16) | (D.sym ? 1 : 0) | ((long long)(J.part >= 0) << 1);
+      rec[1] = J.kend - J.kbeg; rec[2] = t0; rec[3] = wall_clock64();
+    }
+  }
+#endif
 }
+#ifdef KFAC_TRACE
+extern "C" int kfac_debug_factor_trace(long long* out, int max_recs) {   // first call arms the trace
+  static long long* buf = nullptr;
+  if (!buf) {
+    (void)hipMalloc(reinterpret_cast<void**>(&buf), (1 + 4 * 100000) * sizeof(long long));
+    (void)hipMemset(buf, 0, (1 + 4 * 100000) * sizeof(long long));
+    (void)hipMemcpyToSymbol(HIP_SYMBOL(g_factor_trace), &buf, sizeof(buf));
+    return 0;
+  }
+  (void)hipDeviceSynchronize();
+  long long n = 0;
+  (void)hipMemcpy(&n, buf, sizeof(n), hipMemcpyDeviceToHost);
+  if (n > 100000) n = 100000;
+  if (n > max_recs) n = max_recs;
+  if (out && n > 0) (void)hipMemcpy(out, buf + 1, size_t(n) * 32, hipMemcpyDeviceToHost);
+  (void)hipMemset(buf, 0, sizeof(long long));
+  return int(n);
+}
+#endif
 
 // Only row-major operands (preconditioning products, sweep updates): smaller code, same engine.
 __global__ __launch_bounds__(NT, 2) void tile_gemm_kernel(const TileDesc* __restrict__ descs,
