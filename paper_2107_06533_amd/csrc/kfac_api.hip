@@ -500,11 +500,13 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
           if (k == LAG_G1) D.b = lag_operand(L, OP_CONV25, 2, 5, -1, 2, 0, w[0], w[1], w[2], w[3]);
           else if (k == LAG_G2) D.b = lag_operand(L, OP_CONV13, 1, 3, 0, 0, b, w[0], w[1], w[2], w[3]);
           else {
-            // lags a strip's tap can ask for: the tap in row i = 0 (which drops the bottom row) pairs
-            // with rows i' >= 0 only, i.e. lags 0..2, and so on
+            // A border row pairs with itself only: the tap in row i = 0 (which drops the bottom row) asks
+            // for lags dy = i' - i >= 0, and below the bottom row there is nothing, so dy = 0 and the
+            // five lags along the row remain; likewise a border column (dx = 0, five lags along it) and
+            // a corner pixel (lag 0 only).
             static const int geo[LAG_NMAT][4] = {{0, 0, 0, 0}, {0, 0, 0, 0},                 // KH, KW, pad_h, pad_w
-                                                 {3, 5, 2, 2}, {3, 5, 0, 2}, {5, 3, 2, 2}, {5, 3, 2, 0},
-                                                 {3, 3, 2, 2}, {3, 3, 2, 0}, {3, 3, 0, 2}, {3, 3, 0, 0}};
+                                                 {1, 5, 0, 2}, {1, 5, 0, 2}, {5, 1, 2, 0}, {5, 1, 2, 0},
+                                                 {1, 1, 0, 0}, {1, 1, 0, 0}, {1, 1, 0, 0}, {1, 1, 0, 0}};
             D.b = lag_operand(L, OP_CONVGEN, geo[k][0], geo[k][1], geo[k][2], geo[k][3], b, w[0], w[1], w[2], w[3]);
           }
           D.M = D.a.M; D.N = D.ldo = D.b.M;

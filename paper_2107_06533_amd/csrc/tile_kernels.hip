@@ -168,7 +168,7 @@ constexpr int LAG_TILE = 64;
 // Raw sum for the tap column (c, i, j) against the tap column (c2, i2, j2), or against the bias
 // column when isbias (then c2 = C, i2 = j2 = 0 are ignored).  All offsets fit 32 bits.
 __device__ __forceinline__ float lag_value(const LagAsm& L, int c, int i, int j, int c2, int i2, int j2, bool isbias) {
-  const uint32_t C = (uint32_t)L.C, ld1 = 10u * C, ld2 = 3u * C + L.bias, ld15 = 15u * C + L.bias, ld9 = 9u * C + L.bias;
+  const uint32_t C = (uint32_t)L.C, ld1 = 10u * C, ld2 = 3u * C + L.bias, ld5 = 5u * C + L.bias, ldc = C + L.bias;
   const int dy = isbias ? 0 : i2 - i, dx = isbias ? 0 : j2 - j;
   gcf_ptr G1 = as_global(L.G[LAG_G1]);
   gcf_ptr G2 = as_global(L.G[LAG_G2]);
@@ -179,22 +179,22 @@ __device__ __forceinline__ float lag_value(const LagAsm& L, int c, int i, int j,
   else if (dy < 0) v = G1[c2 * ld1 + c * 10 + (-dy - 1) * 5 - dx + 2];
   else v = G2[c2 * ld2 + c * 3 - dx];
   // Pixels q whose output pixel q - (t - 1) lies outside the grid are taken out again: bottom row for
-  // i = 0, top row for i = 2, right column for j = 0, left column for j = 2.  Each strip matrix holds
-  // only the lags its tap row / column can ask for (lag = window index - pad); in the bias column
-  // (c2 = C) the index below lands on the ones column of every strip.
-  const int ph = i == 0 ? 0 : 2, pw = j == 0 ? 0 : 2;        // pads of the 3-wide lag windows
-  const int uy = isbias ? 0 : dy + ph, ux = isbias ? 0 : dx + pw;
-  if (i != 1) {
-    gcf_ptr S = as_global(i == 0 ? L.G[LAG_BOT] : L.G[LAG_TOP]);                           // [C][15C + bias], 3 x 5 lags
-    v -= S[c * ld15 + c2 * 15 + uy * 5 + (isbias ? 0 : dx + 2)];
+  // i = 0, top row for i = 2, right column for j = 0, left column for j = 2.  The partner pixel q + lag
+  // of a pixel in the bottom row lies below the image unless dy <= 0, and the tap i = 0 only asks for
+  // dy >= 0 (the top row: the other way round), so a row strip contributes for dy = 0 only; a column
+  // strip for dx = 0 only; their common corner pixel for lag 0 only.  In the bias column (c2 = C,
+  // dy = dx = 0) the indices below land on the ones column of every strip.
+  if (i != 1 && dy == 0) {
+    gcf_ptr S = as_global(i == 0 ? L.G[LAG_BOT] : L.G[LAG_TOP]);                           // [C][5C + bias], lags dx = -2..2
+    v -= S[c * ld5 + c2 * 5 + (isbias ? 0 : dx + 2)];
   }
-  if (j != 1) {
-    gcf_ptr S = as_global(j == 0 ? L.G[LAG_RIGHT] : L.G[LAG_LEFT]);                        // [C][15C + bias], 5 x 3 lags
-    v -= S[c * ld15 + c2 * 15 + (isbias ? 0 : (dy + 2) * 3) + ux];
+  if (j != 1 && dx == 0) {
+    gcf_ptr S = as_global(j == 0 ? L.G[LAG_RIGHT] : L.G[LAG_LEFT]);                        // [C][5C + bias], lags dy = -2..2
+    v -= S[c * ld5 + c2 * 5 + (isbias ? 0 : dy + 2)];
   }
-  if (i != 1 && j != 1) {
-    gcf_ptr S = as_global(i == 0 ? (j == 0 ? L.G[LAG_BR] : L.G[LAG_BL]) : (j == 0 ? L.G[LAG_TR] : L.G[LAG_TL]));   // [C][9C + bias]
-    v += S[c * ld9 + c2 * 9 + uy * 3 + ux];
+  if (i != 1 && j != 1 && dy == 0 && dx == 0) {
+    gcf_ptr S = as_global(i == 0 ? (j == 0 ? L.G[LAG_BR] : L.G[LAG_BL]) : (j == 0 ? L.G[LAG_TR] : L.G[LAG_TL]));   // [C][C + bias]
+    v += S[c * ldc + c2];
   }
   return v;
 }
