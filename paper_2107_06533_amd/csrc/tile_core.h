@@ -331,7 +331,7 @@ struct Conv11VecLoader {
 // One staged k step (KC deep).  Lane l supplies a(k = l/32, i = l%32) and b(k = l/32, j = l%32).
 // PAT is the compile-time set of the wave's 32x32 blocks that are computed (bit a*2+b): the
 // MFMA sequence is straight-line code for every pattern.
-constexpr unsigned PAT_FULL = 0xF, PAT_ROW1 = 0x3, PAT_COL1 = 0x5, PAT_ONE = 0x1, PAT_TRI = 0xD, PAT_NONE = 0;
+constexpr unsigned PAT_FULL = 0xF, PAT_ROW1 = 0x3, PAT_ROW2 = 0xC, PAT_COL1 = 0x5, PAT_ONE = 0x1, PAT_TRI = 0xD, PAT_NONE = 0;
 
 template <unsigned PAT>
 __device__ __forceinline__ void mma_ktile(const float* __restrict__ As, const float* __restrict__ Bs,
@@ -371,6 +371,7 @@ __device__ __forceinline__ void mma_ktile(const float* __restrict__ As, const fl
 __device__ __forceinline__ unsigned cover_pattern(unsigned mask) {
   if (mask == 0) return PAT_NONE;
   if (mask == PAT_TRI) return PAT_TRI;
+  if (!(mask & 0x3)) return PAT_ROW2;
   const bool rows2 = mask & 0xC, cols2 = mask & 0xA;
   return rows2 ? (cols2 ? PAT_FULL : PAT_COL1) : (cols2 ? PAT_ROW1 : PAT_ONE);
 }
@@ -393,6 +394,24 @@ __device__ __forceinline__ unsigned block_mask(const TileDesc& D, int bi, int bj
       if (v) mask |= 1u << (a * 2 + b);
     }
   return mask;
+}
+
+// Which blocks wave w of a 2x2-wave tile computes.  Off the diagonal: the 2x2 blocks at (w / 2, w % 2).
+// On a diagonal tile of a symmetric product only the ten blocks on or below the diagonal are wanted;
+// as 3 + 0 + 4 + 3 over the waves in place, the tile would take as long as a full one, so the wave
+// above the diagonal takes the lower block row of the wave below the diagonal: 3 + 2 + 2 + 3.
+struct WavePlace {
+  int wm, wn;
+  unsigned mask;
+};
+__device__ __forceinline__ WavePlace wave_place(const TileDesc& D, int bi, int bj, int w) {
+  WavePlace p{w >> 1, w & 1, 0xFu};
+  if (D.sym && bi == bj) {
+    if (w == 1) p = WavePlace{1, 0, 0xCu};
+    else if (w == 2) p.mask = 0x3u;
+  }
+  p.mask &= block_mask(D, bi, bj, p.wm, p.wn);
+  return p;
 }
 
 // LDS floats needed by run_tile: 2 operands x 2 buffers
@@ -493,6 +512,64 @@ __device__ __forceinline__ void main_loop_any(LA& la, LB& lb, bool share, float*
   else main_loop<PAT, false, SAME>(la, lb, As, Bs, tot, kbeg, nkt, wm, wn, lane, yield_word);
 }
 
+// Byte offset of output element (block qd, register v) of this lane in a tile's epilogue: OOB_OFFSET when
+// the element is outside the matrix, above the diagonal of a symmetric output, or in a block that is
+// not computed.
+struct OutMap {
+  int i0, j0, wm, wn, lane, M, N, sym;
+  unsigned mask;
+  uint32_t ldo4;
+  __device__ __forceinline__ int row(int qd, int v) const { return i0 + wm * 64 + (qd >> 1) * 32 + mfma_row(v, lane); }
+  __device__ __forceinline__ int col(int qd) const { return j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane); }
+  __device__ __forceinline__ uint32_t operator()(int qd, int v) const {
+    const int gi = row(qd, v), gj = col(qd);
+    const bool ok = ((mask >> qd) & 1u) && gi < M && gj < N && (!sym || gi >= gj);
+    return ok ? (uint32_t)gi * ldo4 + (uint32_t)gj * 4u : OOB_OFFSET;
+  }
+};
+
+__device__ __forceinline__ void load_old(const rsrc_t ro, const OutMap& om, Acc4& old) {
+#pragma unroll
+  for (int qd = 0; qd < 4; ++qd)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) old.c[qd][v] = buf_load(ro, om(qd, v));
+}
+
+// Epilogue of a 2x2-wave tile: raw partial tile, or out = beta out + alpha acc with mirror and packed copy.
+// have_old: the old values are already in `old` (fetched before the k loop).
+__device__ __forceinline__ void finish_tile(const TileDesc& D, const TileJob& J, const OutMap& om, const rsrc_t ro,
+                                            const Acc4& tot, Acc4& old, bool have_old, bool diag) {
+  const int lane = om.lane, wm = om.wm, wn = om.wn;
+  const unsigned mask = om.mask;
+  if (J.part >= 0) {
+    gf_ptr P = as_global(D.partial) + (size_t)J.part * (BM * BN);
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      if (!(mask & (1u << qd))) continue;
+      const int rb0 = wm * 64 + (qd >> 1) * 32, cb0 = wn * 64 + (qd & 1) * 32;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) P[(rb0 + mfma_row(v, lane)) * BN + cb0 + mfma_col(lane)] = tot.c[qd][v];
+    }
+    return;
+  }
+  const float alpha = D.alpha, beta = D.beta;
+  const bool mirror = D.mirror == MIRROR_ALL || (D.mirror == MIRROR_DIAG_TILE && diag);
+  if (!have_old && beta != 0.f) load_old(ro, om, old);
+#pragma unroll
+  for (int qd = 0; qd < 4; ++qd) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float val = alpha * tot.c[qd][v] + beta * old.c[qd][v];
+      const uint32_t off = om(qd, v);
+      buf_store(ro, off, val);
+      const int gi = om.row(qd, v), gj = om.col(qd);
+      if (mirror) buf_store(ro, (off != OOB_OFFSET && gi != gj) ? (uint32_t)gj * om.ldo4 + (uint32_t)gi * 4u : OOB_OFFSET, val);
+      if (D.packed && off != OOB_OFFSET)   // stored element (gi, gj), gi >= gj, is element (gj, gi) of the upper triangle
+        as_global(D.packed)[(size_t)gj * (size_t)D.M - (size_t)gj * (size_t)(gj - 1) / 2 + (size_t)(gi - gj)] = val;
+    }
+  }
+}
+
 // PREFETCH_OLD: fetch the old output values before the k loop (worth 64 registers when the k loop is
 // short, as in the rank-128 sweep updates) instead of after it.
 // SAME: the descriptor's two operands are the same tensor (every factor build).
@@ -500,7 +577,9 @@ __device__ __forceinline__ void main_loop_any(LA& la, LB& lb, bool share, float*
 // this compute unit's word is non-zero.
 template <class LA, class LB, bool PREFETCH_OLD = false, bool SAME = false, bool YIELD = false>
 __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, float* smem, const int* cu_flags = nullptr) {
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
+  const int t = threadIdx.x, lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const WavePlace wp = wave_place(D, J.bi, J.bj, w);
+  const int wm = wp.wm, wn = wp.wn;
   const int i0 = J.bi * BM, j0 = J.bj * BN;
   const bool diag = D.sym && (J.bi == J.bj);
   const bool share = SAME && diag;   // a == b on a diagonal tile: stage one panel only
@@ -513,31 +592,17 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   lb.init(SAME ? D.a : D.b, j0, J.kend, t);
   if constexpr (SAME && std::is_same<LA, LB>::value) lb.share_geometry(la);
 
-  const unsigned mask = block_mask(D, J.bi, J.bj, wm, wn);
-
-  // Byte offset of output element (block qd, register v) of this lane, OOB_OFFSET when the element
-  // is outside the matrix, above the diagonal of a symmetric output, or in a block that is not computed.
-  const uint32_t ldo4 = (uint32_t)D.ldo * 4u;
-  auto out_offset = [&](int qd, int v) -> uint32_t {
-    const int gi = i0 + wm * 64 + (qd >> 1) * 32 + mfma_row(v, lane);
-    const int gj = j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane);
-    const bool ok = ((mask >> qd) & 1u) && gi < D.M && gj < D.N && (!D.sym || gi >= gj);
-    return ok ? (uint32_t)gi * ldo4 + (uint32_t)gj * 4u : OOB_OFFSET;
-  };
-  const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * ldo4);
-  const float alpha = D.alpha, beta = D.beta;
+  const unsigned mask = wp.mask;
+  const OutMap om{i0, j0, wm, wn, lane, D.M, D.N, D.sym, mask, (uint32_t)D.ldo * 4u};
+  const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * om.ldo4);
   const bool direct = J.part < 0;
 
   // Old output values (running average, sweep update) are fetched before the k loop so that their
   // latency is covered by the MFMA work; they are all in registers before anything is stored.
   Acc4 old;
   acc_zero(old);
-  if (PREFETCH_OLD && direct && beta != 0.f) {
-#pragma unroll
-    for (int qd = 0; qd < 4; ++qd)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) old.c[qd][v] = buf_load(ro, out_offset(qd, v));
-  }
+  const bool have_old = PREFETCH_OLD && direct && D.beta != 0.f;
+  if (have_old) load_old(ro, om, old);
 
   Acc4 tot;
   acc_zero(tot);
@@ -546,50 +611,158 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   switch (cover_pattern(mask)) {
     case PAT_FULL: main_loop_any<PAT_FULL, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
     case PAT_ROW1: main_loop_any<PAT_ROW1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
+    case PAT_ROW2: main_loop_any<PAT_ROW2, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
     case PAT_COL1: main_loop_any<PAT_COL1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
     case PAT_ONE: main_loop_any<PAT_ONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
     case PAT_TRI: main_loop_any<PAT_TRI, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
     default: main_loop_any<PAT_NONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
   }
+  finish_tile(D, J, om, ro, tot, old, have_old, diag);
+}
 
-  // ---- epilogue
-  if (!direct) {
-    gf_ptr P = as_global(D.partial) + (size_t)J.part * (BM * BN);
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+// ------------------------------------------------------------------------------ direct-to-LDS panels of 1x1 views
+// Symmetric products of whole-image 1x1 views (OP_CONV11V on both sides: every G factor of a
+// convolution whose output images hold a multiple of four pixels, and the A factors of such 1x1
+// convolutions) load their panels with the 16-byte buffer_load ... lds as well.  The tensor is
+// channel-major (k contiguous), so a panel is [128 channels][KC k] with 128-byte rows; lane l of a wave
+// instruction moves one quad of four k, eight lanes a row, eight rows an instruction.  Where a lane's
+// quad lands is fixed by the instruction (16 l bytes behind the base), which quad it fetches is not:
+// row r stores quad q at position q ^ ((r >> 1) & 7), so that the 16-byte fragment reads of the MFMA
+// loop (32 lanes = 32 rows, the same quad) spread over all banks.  Lane half h of the MFMA loop reads
+// quad 2g + h of its row and feeds MFMA e = 0..3 of group g with k = 8g + 4h + e: the two halves
+// pair k with k + 4 rather than with k + 1 (any pairing gives the same sum).  Per k step a wave
+// issues four loads an operand and a dozen address instructions; nothing is staged in registers and
+// nothing is stored to LDS but the ones column.
+constexpr int DM_PANEL = BM * KC;   // floats of one such panel
+static_assert(KC == 32, "eight quads a row");
+static_assert(4 * DM_PANEL <= TILE_LDS_FLOATS, "fits the LDS of the staged loop");
+
+struct Conv11DirectLoader {
+  rsrc_t rs;
+  uint32_t moff, soff32, skip;   // byte offset of the lane's channel of instruction 0; of 32 channels; (C - 1) * HW
+  unsigned valid;                // bit j: the lane's channel of instruction j exists
+  int q4, kend, w;               // first k of the lane's quad inside a panel
+  int bias_row;                  // row of the ones column in this tile if this wave loads it, else -1
+  FastDiv dHW;
+
+  __device__ __forceinline__ void init(const Operand& op, int m0, int kend_, int lane, int wave) {
+    w = wave;
+    const int mreal = op.M - op.bias;
+    const uint32_t HW = (uint32_t)(op.OH * op.OW);
+    const int f = 4 * (wave & 1) | (lane >> 4);          // ((row >> 1) & 7) of every row this lane loads
+    q4 = 4 * ((lane & 7) ^ f);
+    valid = 0;
 #pragma unroll
-    for (int qd = 0; qd < 4; ++qd) {
-      if (!(mask & (1u << qd))) continue;
-      const int rb0 = wm * 64 + (qd >> 1) * 32, cb0 = wn * 64 + (qd & 1) * 32;
+    for (int j = 0; j < 4; ++j)
+      if (m0 + 32 * j + 8 * wave + (lane >> 3) < mreal) valid |= 1u << j;
+    moff = (uint32_t)(m0 + 8 * wave + (lane >> 3)) * HW * 4u;
+    soff32 = 32u * HW * 4u;
+    skip = (uint32_t)(op.C - 1) * HW;
+    dHW = op.dOHW;
+    kend = kend_;
+    rs = make_rsrc(op.ptr, op.bytes);
+    const int rb = mreal - m0;
+    bias_row = (op.bias && rb >= 0 && rb < BM && ((rb >> 3) & 3) == wave) ? rb : -1;
+  }
+  // requests panel [k0, k0 + KC) into `panel` ([128][KC], swizzled as above)
+  __device__ __forceinline__ void issue(float* panel, int k0) const {
+    const uint32_t kq = (uint32_t)(k0 + q4);
+    const uint32_t n = fast_div(kq, dHW);
+    const uint32_t vo = (int)kq < kend ? (kq + n * skip) * 4u + moff : OOB_OFFSET;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) P[(rb0 + mfma_row(v, lane)) * BN + cb0 + mfma_col(lane)] = tot.c[qd][v];
+    for (int j = 0; j < 4; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr)(panel + (32 * j + 8 * w) * KC), 16,
+                                               (int)(((valid >> j) & 1u) ? vo : OOB_OFFSET), (int)((uint32_t)j * soff32), 0, 0);
+  }
+  // after this wave's loads of the panel have landed: the ones column (its lanes read out of range: zeros)
+  __device__ __forceinline__ void fix_bias(float* panel, int k0, int lane) const {
+    if (bias_row >= 0 && lane < 8) {
+      const int q = lane ^ ((bias_row >> 1) & 7);
+      const float one = k0 + 4 * q < kend ? 1.f : 0.f;
+      *reinterpret_cast<f32x4*>(panel + bias_row * KC + 4 * lane) = f32x4{one, one, one, one};
     }
-    return;
   }
-  const bool mirror = D.mirror == MIRROR_ALL || (D.mirror == MIRROR_DIAG_TILE && diag);
-  if (!PREFETCH_OLD && beta != 0.f) {
+};
+
+template <unsigned PAT>
+__device__ __forceinline__ void mma_ktile_dm(const float* __restrict__ As, const float* __restrict__ Bs,
+                                             Acc4& acc, int wm, int wn, int lane) {
+  if (PAT == PAT_NONE) return;
+  const int i = lane & 31, c = (lane >> 5) ^ ((i >> 1) & 7);   // quad 2g + h of row i sits at position (2g) ^ c
+  const float* ap = As + (wm * 64 + i) * KC;
+  const float* bp = Bs + (wn * 64 + i) * KC;
+  const f32x4 z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int qd = 0; qd < 4; ++qd)
+  for (int g = 0; g < KC / 8; ++g) {
+    const int pos = 4 * ((2 * g) ^ c);
+    f32x4 a0 = z, a1 = z, b0 = z, b1 = z;
+    if (PAT & 0x3) a0 = *reinterpret_cast<const f32x4*>(ap + pos);
+    if (PAT & 0xC) a1 = *reinterpret_cast<const f32x4*>(ap + 32 * KC + pos);
+    if (PAT & 0x5) b0 = *reinterpret_cast<const f32x4*>(bp + pos);
+    if (PAT & 0xA) b1 = *reinterpret_cast<const f32x4*>(bp + 32 * KC + pos);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) old.c[qd][v] = buf_load(ro, out_offset(qd, v));
-  }
-#pragma unroll
-  for (int qd = 0; qd < 4; ++qd) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const float val = alpha * tot.c[qd][v] + beta * old.c[qd][v];
-      const uint32_t off = out_offset(qd, v);
-      buf_store(ro, off, val);
-      if (mirror) {
-        const int gi = i0 + wm * 64 + (qd >> 1) * 32 + mfma_row(v, lane);
-        const int gj = j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane);
-        buf_store(ro, (off != OOB_OFFSET && gi != gj) ? (uint32_t)gj * ldo4 + (uint32_t)gi * 4u : OOB_OFFSET, val);
-      }
-      if (D.packed && off != OOB_OFFSET) {   // stored element (gi, gj), gi >= gj, is element (gj, gi) of the upper triangle
-        const size_t gi = (size_t)(i0 + wm * 64 + (qd >> 1) * 32 + mfma_row(v, lane));
-        const size_t gj = (size_t)(j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane));
-        as_global(D.packed)[gj * (size_t)D.M - gj * (gj - 1) / 2 + (gi - gj)] = val;
-      }
+    for (int e = 0; e < 4; ++e) {
+      if (PAT & 1u) acc.c[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], b0[e], acc.c[0], 0, 0, 0);
+      if (PAT & 2u) acc.c[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], b1[e], acc.c[1], 0, 0, 0);
+      if (PAT & 4u) acc.c[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], b0[e], acc.c[2], 0, 0, 0);
+      if (PAT & 8u) acc.c[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], b1[e], acc.c[3], 0, 0, 0);
     }
   }
+}
+
+template <unsigned PAT>
+__device__ __forceinline__ void main_loop_dm(const Conv11DirectLoader& la, const Conv11DirectLoader& lb, bool share,
+                                             float* As, float* Bs, Acc4& tot, int kbeg, int nkt, int wm, int wn, int lane) {
+  if (nkt <= 0) return;
+  la.issue(As, kbeg);
+  if (!share) lb.issue(Bs, kbeg);
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int cur = kt & 1, k0 = kbeg + kt * KC;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of panel kt has landed
+    la.fix_bias(As + cur * DM_PANEL, k0, lane);
+    if (!share) lb.fix_bias(Bs + cur * DM_PANEL, k0, lane);
+    __syncthreads();                                    // everybody's part has; all reads of the other buffer are done
+    if (kt + 1 < nkt) {
+      la.issue(As + (cur ^ 1) * DM_PANEL, k0 + KC);
+      if (!share) lb.issue(Bs + (cur ^ 1) * DM_PANEL, k0 + KC);
+    }
+    mma_ktile_dm<PAT>(As + cur * DM_PANEL, (share ? As : Bs) + cur * DM_PANEL, tot, wm, wn, lane);
+  }
+}
+
+// a^T a of an OP_CONV11V operand (the descriptor's b is ignored): same tiles, patterns and epilogue as
+// run_tile<., ., false, true>, other k loop.  smem: 4 * DM_PANEL floats, 16-byte aligned.
+__device__ __forceinline__ void run_tile_dm(const TileDesc& D, const TileJob& J, float* smem) {
+  const int t = threadIdx.x, lane = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const WavePlace wp = wave_place(D, J.bi, J.bj, w);
+  const int wm = wp.wm, wn = wp.wn;
+  const int i0 = J.bi * BM, j0 = J.bj * BN;
+  const bool diag = D.sym && (J.bi == J.bj);
+  float* As = smem;
+  float* Bs = smem + 2 * DM_PANEL;
+  Conv11DirectLoader la, lb;
+  la.init(D.a, i0, J.kend, lane, w);
+  lb.init(D.a, j0, J.kend, lane, w);
+  const unsigned mask = wp.mask;
+  const OutMap om{i0, j0, wm, wn, lane, D.M, D.N, D.sym, mask, (uint32_t)D.ldo * 4u};
+  const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * om.ldo4);
+  Acc4 tot, old;
+  acc_zero(tot);
+  acc_zero(old);
+  const int nkt = (J.kend - J.kbeg + KC - 1) / KC;
+  switch (cover_pattern(mask)) {
+    case PAT_FULL: main_loop_dm<PAT_FULL>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ROW1: main_loop_dm<PAT_ROW1>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ROW2: main_loop_dm<PAT_ROW2>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_COL1: main_loop_dm<PAT_COL1>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_ONE: main_loop_dm<PAT_ONE>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_TRI: main_loop_dm<PAT_TRI>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    default: main_loop_dm<PAT_NONE>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+  }
+  finish_tile(D, J, om, ro, tot, old, false, diag);
 }
 
 // ------------------------------------------------------------------------------ direct-to-LDS product
@@ -610,7 +783,6 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
 // workgroup needs 32 KB of LDS and 80-odd registers, so several workgroups share a compute unit
 // and hide each other's latencies: 120 TFLOP/s on 4096 x 4096 x 768 against 101 for the staged
 // loop, bit-identical results (same order of accumulation).
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
 constexpr int DL_KC = 16;                        // panel depth
 constexpr int DL_PANEL = DL_KC * BM;             // floats of one operand panel
 constexpr int DL_LDS_FLOATS = 4 * DL_PANEL;      // two operands x two buffers
@@ -760,7 +932,11 @@ __device__ __forceinline__ void run_tile_dl(const TileDesc& D, const TileJob& J,
 __device__ __forceinline__ void run_tile_sym(const TileDesc& D, const TileJob& J, float* smem) {
   const int ta = D.a.type;
   if (ta == OP_KMAJOR) run_tile<KMajorLoader, KMajorLoader, false, true>(D, J, smem);
+#ifdef KFAC_NO_DM
   else if (ta == OP_CONV11V) run_tile<Conv11VecLoader, Conv11VecLoader, false, true>(D, J, smem);
+#else
+  else if (ta == OP_CONV11V) run_tile_dm(D, J, smem);
+#endif
   else if (ta == OP_CONV11) run_tile<ConvLoader<1, 1>, ConvLoader<1, 1>, false, true>(D, J, smem);
   else if (ta == OP_CONV33) run_tile<ConvLoader<3, 3>, ConvLoader<3, 3>, false, true>(D, J, smem);
   else if (ta == OP_CONV77) run_tile<ConvLoader<7, 7>, ConvLoader<7, 7>, false, true>(D, J, smem);

@@ -22,7 +22,7 @@ __device__ long long* g_factor_trace = nullptr;   // debugging aid: [0] = record
 __global__ __launch_bounds__(NT, KFAC_WAVES) void tile_any_kernel(const TileDesc* __restrict__ descs,
                                                          const TileJob* __restrict__ jobs, int njobs,
                                                          int xcd_order) {
-  __shared__ float smem[TILE_LDS_FLOATS];
+  __shared__ __attribute__((aligned(16))) float smem[TILE_LDS_FLOATS];
   int g = blockIdx.x;
   if (xcd_order) g = xcd_job_index(g, njobs);
   if (g >= njobs) return;
