@@ -508,10 +508,10 @@ __global__ __launch_bounds__(NT) void gj_panel_kernel(const InvMat* __restrict__
       for (int e = 0; e < 4; ++e) Zt[(size_t)(slot * NB + c * KC + kp + 2 * (4 * gq + e)) * ldp + i0 + ml] = zv[e];
     }
     switch (pat) {
-      case PAT_FULL: mma_ktile<PAT_FULL>(Qc, Zc, acc, wm, wn, lane); break;
-      case PAT_ROW1: mma_ktile<PAT_ROW1>(Qc, Zc, acc, wm, wn, lane); break;
-      case PAT_COL1: mma_ktile<PAT_COL1>(Qc, Zc, acc, wm, wn, lane); break;
-      case PAT_ONE: mma_ktile<PAT_ONE>(Qc, Zc, acc, wm, wn, lane); break;
+      case PAT_FULL: mma_ktile<PAT_FULL>(Qc, Zc, acc, wm * 64, wn * 64, lane); break;
+      case PAT_ROW1: mma_ktile<PAT_ROW1>(Qc, Zc, acc, wm * 64, wn * 64, lane); break;
+      case PAT_COL1: mma_ktile<PAT_COL1>(Qc, Zc, acc, wm * 64, wn * 64, lane); break;
+      case PAT_ONE: mma_ktile<PAT_ONE>(Qc, Zc, acc, wm * 64, wn * 64, lane); break;
       default: break;
     }
   }

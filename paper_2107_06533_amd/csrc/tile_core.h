@@ -335,11 +335,11 @@ constexpr unsigned PAT_FULL = 0xF, PAT_ROW1 = 0x3, PAT_ROW2 = 0xC, PAT_COL1 = 0x
 
 template <unsigned PAT>
 __device__ __forceinline__ void mma_ktile(const float* __restrict__ As, const float* __restrict__ Bs,
-                                          Acc4& acc, int wm, int wn, int lane) {
+                                          Acc4& acc, int r0, int c0, int lane) {
   if (PAT == PAT_NONE) return;
-  // lane l feeds a(k, i = l%32) and b(k, j = l%32) with k = 8g + 2s + l/32 for MFMA s of group g
-  const float* ap = As + (wm * 64 + (lane & 31)) * PK + 4 * (lane >> 5);
-  const float* bp = Bs + (wn * 64 + (lane & 31)) * PK + 4 * (lane >> 5);
+  // r0, c0: first row / column of the wave's 2x2 group of blocks inside the tile;  lane l feeds a(k, i = l%32) and b(k, j = l%32) with k = 8g + 2s + l/32 for MFMA s of group g
+  const float* ap = As + (r0 + (lane & 31)) * PK + 4 * (lane >> 5);
+  const float* bp = Bs + (c0 + (lane & 31)) * PK + 4 * (lane >> 5);
   const f32x4 z = {0.f, 0.f, 0.f, 0.f};
   f32x4 a0 = z, a1 = z, b0 = z, b1 = z;
   if (PAT & 0x3) a0 = *reinterpret_cast<const f32x4*>(ap);
@@ -380,37 +380,61 @@ __device__ __forceinline__ unsigned cover_pattern(unsigned mask) {
 __device__ __forceinline__ int mfma_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 __device__ __forceinline__ int mfma_col(int lane) { return lane & 31; }
 
-// Which of the wave's four 32x32 blocks hold any wanted output.
-__device__ __forceinline__ unsigned block_mask(const TileDesc& D, int bi, int bj, int wm, int wn) {
+// Which of the four 32x32 blocks of the 2x2 group at (r0, c0) of tile (bi, bj) hold any wanted output.
+__device__ __forceinline__ unsigned block_mask(const TileDesc& D, int bi, int bj, int r0, int c0) {
   unsigned mask = 0;
   const bool diag = D.sym && bi == bj;
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      const int rlo = bi * BM + wm * 64 + a * 32, clo = bj * BN + wn * 64 + b * 32;
-      bool v = rlo < D.M && clo < D.N;
-      if (diag) v = v && (wm * 2 + a >= wn * 2 + b);
+      const int rl = r0 + a * 32, cl = c0 + b * 32;
+      bool v = rl < BM && cl < BN && bi * BM + rl < D.M && bj * BN + cl < D.N;
+      if (diag) v = v && rl >= cl;
       if (v) mask |= 1u << (a * 2 + b);
     }
   return mask;
 }
 
-// Which blocks wave w of a 2x2-wave tile computes.  Off the diagonal: the 2x2 blocks at (w / 2, w % 2).
-// On a diagonal tile of a symmetric product only the ten blocks on or below the diagonal are wanted;
-// as 3 + 0 + 4 + 3 over the waves in place, the tile would take as long as a full one, so the wave
-// above the diagonal takes the lower block row of the wave below the diagonal: 3 + 2 + 2 + 3.
+// Which blocks wave w of a tile computes: the 2x2 group of 32x32 blocks at rows r0.., columns c0..
+// of the tile, restricted to `mask`.  A full tile off the diagonal: the quadrant (w / 2, w % 2).
+// Otherwise the wanted blocks are dealt out as evenly as 2x2 groups allow, because a tile takes as
+// long as its busiest wave:
+//   diagonal tile of a symmetric product (ten blocks on or below the diagonal; in place they would
+//   fall 3 + 0 + 4 + 3): 3 + 2 + 2 + 3; with three valid block rows 2 + 2 + 1 + 1 of six, with two
+//   1 + 1 + 1 of three;
+//   at most two valid block rows (the one-row tail of the d = 128 m + 1 factors, products with 64
+//   rows): wave w takes block column w, one or two blocks, instead of two waves taking four;
+//   at most two valid block columns: the same with rows and columns exchanged.
 struct WavePlace {
-  int wm, wn;
+  int r0, c0;
   unsigned mask;
 };
 __device__ __forceinline__ WavePlace wave_place(const TileDesc& D, int bi, int bj, int w) {
-  WavePlace p{w >> 1, w & 1, 0xFu};
+  const int mrows = D.M - bi * BM, ncols = D.N - bj * BN;
+  const int rb = mrows >= BM ? 4 : (mrows + 31) >> 5, cb = ncols >= BN ? 4 : (ncols + 31) >> 5;
+  WavePlace p{64 * (w >> 1), 64 * (w & 1), 0xFu};
   if (D.sym && bi == bj) {
-    if (w == 1) p = WavePlace{1, 0, 0xCu};
-    else if (w == 2) p.mask = 0x3u;
+    if (rb == 4) {
+      if (w == 1) p = WavePlace{64, 0, 0xCu};
+      else if (w == 2) p.mask = 0x3u;
+    } else if (rb == 3) {
+      if (w == 0) p = WavePlace{0, 0, 0x5u};          // (0,0) (1,0)
+      else if (w == 1) p = WavePlace{32, 32, 0x5u};   // (1,1) (2,1)
+      else if (w == 2) p = WavePlace{64, 0, 0x1u};    // (2,0)
+      else p = WavePlace{64, 64, 0x1u};               // (2,2)
+    } else if (rb == 2) {
+      if (w == 0) p = WavePlace{0, 0, 0x1u};
+      else if (w == 1) p = WavePlace{32, 0, 0x1u};
+      else if (w == 2) p = WavePlace{32, 32, 0x1u};
+      else p.mask = 0;
+    }
+  } else if (rb <= 2 && cb > 2) {
+    p = WavePlace{0, 32 * w, rb == 1 ? 0x1u : 0x5u};
+  } else if (cb <= 2 && rb > 2) {
+    p = WavePlace{32 * w, 0, cb == 1 ? 0x1u : 0x3u};
   }
-  p.mask &= block_mask(D, bi, bj, p.wm, p.wn);
+  p.mask &= block_mask(D, bi, bj, p.r0, p.c0);
   return p;
 }
 
@@ -479,7 +503,7 @@ __device__ __forceinline__ void cu_yield(const int* word) {   // at most ~0.2 ms
 
 template <unsigned PAT, bool SHARE, bool SAME, class LA, class LB>
 __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, Acc4& tot,
-                                          int kbeg, int nkt, int wm, int wn, int lane, const int* yield_word = nullptr) {
+                                          int kbeg, int nkt, int r0, int c0, int lane, const int* yield_word = nullptr) {
   if (nkt <= 0) return;
   float ra[NU], rb[NU];
   la.load(kbeg, ra);
@@ -493,7 +517,7 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
     if (yield_word) busy = __hip_atomic_load(yield_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // lands during the MFMAs
     la.load(kbeg + kt * KC, ra);
     if (!SHARE) load_b<LA, LB, SAME>(la, lb, kbeg + kt * KC, rb);
-    mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
+    mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, r0, c0, lane);
     if (yield_word && __builtin_amdgcn_readfirstlane(busy) != 0) cu_yield(yield_word);
     if constexpr (!SAME && std::is_same<LA, KMajorLoader>::value && std::is_same<LB, KMajorLoader>::value)   // plain products only: measured no gain elsewhere
       interleave_loads<(KC / 2) * __builtin_popcount(PAT), LA::LOADS + (SHARE ? 0 : LB::LOADS)>();
@@ -502,25 +526,25 @@ __device__ __forceinline__ void main_loop(LA& la, LB& lb, float* As, float* Bs, 
     __syncthreads();
     cur ^= 1;
   }
-  mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, wm, wn, lane);
+  mma_ktile<PAT>(As + cur * PANEL, Bs + cur * PANEL, tot, r0, c0, lane);
 }
 
 template <unsigned PAT, bool SAME, class LA, class LB>
 __device__ __forceinline__ void main_loop_any(LA& la, LB& lb, bool share, float* As, float* Bs, Acc4& tot,
-                                              int kbeg, int nkt, int wm, int wn, int lane, const int* yield_word = nullptr) {
-  if (SAME && share) main_loop<PAT, true, true>(la, lb, As, As, tot, kbeg, nkt, wm, wn, lane, yield_word);
-  else main_loop<PAT, false, SAME>(la, lb, As, Bs, tot, kbeg, nkt, wm, wn, lane, yield_word);
+                                              int kbeg, int nkt, int r0, int c0, int lane, const int* yield_word = nullptr) {
+  if (SAME && share) main_loop<PAT, true, true>(la, lb, As, As, tot, kbeg, nkt, r0, c0, lane, yield_word);
+  else main_loop<PAT, false, SAME>(la, lb, As, Bs, tot, kbeg, nkt, r0, c0, lane, yield_word);
 }
 
 // Byte offset of output element (block qd, register v) of this lane in a tile's epilogue: OOB_OFFSET when
 // the element is outside the matrix, above the diagonal of a symmetric output, or in a block that is
 // not computed.
 struct OutMap {
-  int i0, j0, wm, wn, lane, M, N, sym;
+  int i0, j0, r0, c0, lane, M, N, sym;   // r0, c0: offset of the wave's 2x2 group of blocks inside the tile
   unsigned mask;
   uint32_t ldo4;
-  __device__ __forceinline__ int row(int qd, int v) const { return i0 + wm * 64 + (qd >> 1) * 32 + mfma_row(v, lane); }
-  __device__ __forceinline__ int col(int qd) const { return j0 + wn * 64 + (qd & 1) * 32 + mfma_col(lane); }
+  __device__ __forceinline__ int row(int qd, int v) const { return i0 + r0 + (qd >> 1) * 32 + mfma_row(v, lane); }
+  __device__ __forceinline__ int col(int qd) const { return j0 + c0 + (qd & 1) * 32 + mfma_col(lane); }
   __device__ __forceinline__ uint32_t operator()(int qd, int v) const {
     const int gi = row(qd, v), gj = col(qd);
     const bool ok = ((mask >> qd) & 1u) && gi < M && gj < N && (!sym || gi >= gj);
@@ -539,14 +563,14 @@ __device__ __forceinline__ void load_old(const rsrc_t ro, const OutMap& om, Acc4
 // have_old: the old values are already in `old` (fetched before the k loop).
 __device__ __forceinline__ void finish_tile(const TileDesc& D, const TileJob& J, const OutMap& om, const rsrc_t ro,
                                             const Acc4& tot, Acc4& old, bool have_old, bool diag) {
-  const int lane = om.lane, wm = om.wm, wn = om.wn;
+  const int lane = om.lane;
   const unsigned mask = om.mask;
   if (J.part >= 0) {
     gf_ptr P = as_global(D.partial) + (size_t)J.part * (BM * BN);
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd) {
       if (!(mask & (1u << qd))) continue;
-      const int rb0 = wm * 64 + (qd >> 1) * 32, cb0 = wn * 64 + (qd & 1) * 32;
+      const int rb0 = om.r0 + (qd >> 1) * 32, cb0 = om.c0 + (qd & 1) * 32;
 #pragma unroll
       for (int v = 0; v < 16; ++v) P[(rb0 + mfma_row(v, lane)) * BN + cb0 + mfma_col(lane)] = tot.c[qd][v];
     }
@@ -579,7 +603,7 @@ template <class LA, class LB, bool PREFETCH_OLD = false, bool SAME = false, bool
 __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, float* smem, const int* cu_flags = nullptr) {
   const int t = threadIdx.x, lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);
   const WavePlace wp = wave_place(D, J.bi, J.bj, w);
-  const int wm = wp.wm, wn = wp.wn;
+  const int r0 = wp.r0, c0 = wp.c0;
   const int i0 = J.bi * BM, j0 = J.bj * BN;
   const bool diag = D.sym && (J.bi == J.bj);
   const bool share = SAME && diag;   // a == b on a diagonal tile: stage one panel only
@@ -593,7 +617,7 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   if constexpr (SAME && std::is_same<LA, LB>::value) lb.share_geometry(la);
 
   const unsigned mask = wp.mask;
-  const OutMap om{i0, j0, wm, wn, lane, D.M, D.N, D.sym, mask, (uint32_t)D.ldo * 4u};
+  const OutMap om{i0, j0, r0, c0, lane, D.M, D.N, D.sym, mask, (uint32_t)D.ldo * 4u};
   const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * om.ldo4);
   const bool direct = J.part < 0;
 
@@ -609,13 +633,13 @@ __device__ __forceinline__ void run_tile(const TileDesc& D, const TileJob& J, fl
   const int nkt = (J.kend - J.kbeg + KC - 1) / KC;
   const int* yw = (YIELD && cu_flags) ? cu_flags + cu_slot() : nullptr;
   switch (cover_pattern(mask)) {
-    case PAT_FULL: main_loop_any<PAT_FULL, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
-    case PAT_ROW1: main_loop_any<PAT_ROW1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
-    case PAT_ROW2: main_loop_any<PAT_ROW2, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
-    case PAT_COL1: main_loop_any<PAT_COL1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
-    case PAT_ONE: main_loop_any<PAT_ONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
-    case PAT_TRI: main_loop_any<PAT_TRI, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
-    default: main_loop_any<PAT_NONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, wm, wn, lane, yw); break;
+    case PAT_FULL: main_loop_any<PAT_FULL, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, r0, c0, lane, yw); break;
+    case PAT_ROW1: main_loop_any<PAT_ROW1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, r0, c0, lane, yw); break;
+    case PAT_ROW2: main_loop_any<PAT_ROW2, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, r0, c0, lane, yw); break;
+    case PAT_COL1: main_loop_any<PAT_COL1, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, r0, c0, lane, yw); break;
+    case PAT_ONE: main_loop_any<PAT_ONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, r0, c0, lane, yw); break;
+    case PAT_TRI: main_loop_any<PAT_TRI, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, r0, c0, lane, yw); break;
+    default: main_loop_any<PAT_NONE, SAME>(la, lb, share, As, Bs, tot, J.kbeg, nkt, r0, c0, lane, yw); break;
   }
   finish_tile(D, J, om, ro, tot, old, have_old, diag);
 }
@@ -688,11 +712,11 @@ struct Conv11DirectLoader {
 
 template <unsigned PAT>
 __device__ __forceinline__ void mma_ktile_dm(const float* __restrict__ As, const float* __restrict__ Bs,
-                                             Acc4& acc, int wm, int wn, int lane) {
+                                             Acc4& acc, int r0, int c0, int lane) {
   if (PAT == PAT_NONE) return;
   const int i = lane & 31, c = (lane >> 5) ^ ((i >> 1) & 7);   // quad 2g + h of row i sits at position (2g) ^ c
-  const float* ap = As + (wm * 64 + i) * KC;
-  const float* bp = Bs + (wn * 64 + i) * KC;
+  const float* ap = As + (r0 + i) * KC;   // r0, c0 are multiples of 32: the swizzle of a row depends on i only
+  const float* bp = Bs + (c0 + i) * KC;
   const f32x4 z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int g = 0; g < KC / 8; ++g) {
@@ -714,7 +738,7 @@ __device__ __forceinline__ void mma_ktile_dm(const float* __restrict__ As, const
 
 template <unsigned PAT>
 __device__ __forceinline__ void main_loop_dm(const Conv11DirectLoader& la, const Conv11DirectLoader& lb, bool share,
-                                             float* As, float* Bs, Acc4& tot, int kbeg, int nkt, int wm, int wn, int lane) {
+                                             float* As, float* Bs, Acc4& tot, int kbeg, int nkt, int r0, int c0, int lane) {
   if (nkt <= 0) return;
   la.issue(As, kbeg);
   if (!share) lb.issue(Bs, kbeg);
@@ -728,7 +752,7 @@ __device__ __forceinline__ void main_loop_dm(const Conv11DirectLoader& la, const
       la.issue(As + (cur ^ 1) * DM_PANEL, k0 + KC);
       if (!share) lb.issue(Bs + (cur ^ 1) * DM_PANEL, k0 + KC);
     }
-    mma_ktile_dm<PAT>(As + cur * DM_PANEL, (share ? As : Bs) + cur * DM_PANEL, tot, wm, wn, lane);
+    mma_ktile_dm<PAT>(As + cur * DM_PANEL, (share ? As : Bs) + cur * DM_PANEL, tot, r0, c0, lane);
   }
 }
 
@@ -738,7 +762,7 @@ __device__ __forceinline__ void run_tile_dm(const TileDesc& D, const TileJob& J,
   const int t = threadIdx.x, lane = t & 63;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const WavePlace wp = wave_place(D, J.bi, J.bj, w);
-  const int wm = wp.wm, wn = wp.wn;
+  const int r0 = wp.r0, c0 = wp.c0;
   const int i0 = J.bi * BM, j0 = J.bj * BN;
   const bool diag = D.sym && (J.bi == J.bj);
   float* As = smem;
@@ -747,20 +771,20 @@ __device__ __forceinline__ void run_tile_dm(const TileDesc& D, const TileJob& J,
   la.init(D.a, i0, J.kend, lane, w);
   lb.init(D.a, j0, J.kend, lane, w);
   const unsigned mask = wp.mask;
-  const OutMap om{i0, j0, wm, wn, lane, D.M, D.N, D.sym, mask, (uint32_t)D.ldo * 4u};
+  const OutMap om{i0, j0, r0, c0, lane, D.M, D.N, D.sym, mask, (uint32_t)D.ldo * 4u};
   const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * om.ldo4);
   Acc4 tot, old;
   acc_zero(tot);
   acc_zero(old);
   const int nkt = (J.kend - J.kbeg + KC - 1) / KC;
   switch (cover_pattern(mask)) {
-    case PAT_FULL: main_loop_dm<PAT_FULL>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ROW1: main_loop_dm<PAT_ROW1>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ROW2: main_loop_dm<PAT_ROW2>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_COL1: main_loop_dm<PAT_COL1>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_ONE: main_loop_dm<PAT_ONE>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    case PAT_TRI: main_loop_dm<PAT_TRI>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
-    default: main_loop_dm<PAT_NONE>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, wm, wn, lane); break;
+    case PAT_FULL: main_loop_dm<PAT_FULL>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, r0, c0, lane); break;
+    case PAT_ROW1: main_loop_dm<PAT_ROW1>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, r0, c0, lane); break;
+    case PAT_ROW2: main_loop_dm<PAT_ROW2>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, r0, c0, lane); break;
+    case PAT_COL1: main_loop_dm<PAT_COL1>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, r0, c0, lane); break;
+    case PAT_ONE: main_loop_dm<PAT_ONE>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, r0, c0, lane); break;
+    case PAT_TRI: main_loop_dm<PAT_TRI>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, r0, c0, lane); break;
+    default: main_loop_dm<PAT_NONE>(la, lb, diag, As, Bs, tot, J.kbeg, nkt, r0, c0, lane); break;
   }
   finish_tile(D, J, om, ro, tot, old, false, diag);
 }
