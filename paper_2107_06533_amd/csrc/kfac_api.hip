@@ -51,8 +51,9 @@ struct FactorPlan {
   std::vector<TileDesc> descs;       // shape part filled at build time, pointers/scalars per call
   void* d_jobs = nullptr;
   void* d_rjobs = nullptr;
-  void* d_ljobs = nullptr;
-  int njobs = 0, nrjobs = 0, nljobs = 0;
+  void* d_ljobs = nullptr;   // mirror tiles of the lag-product factors
+  void* d_pjobs = nullptr;   // their channel-pair tiles
+  int njobs = 0, nrjobs = 0, nljobs = 0, npjobs = 0;
   size_t nslots = 0;
   std::vector<LagLayer> lags;        // activation factors built from lag products
   size_t lag_floats = 0;             // their scratch matrices, behind the split-reduction slots
@@ -415,7 +416,7 @@ std::vector<TileJob> xcd_arrange(const std::vector<std::vector<TileJob>>& groups
 
 // ------------------------------------------------------------------------------- factor plan
 void release(FactorPlan& p) {
-  free_dev(p.d_jobs); free_dev(p.d_rjobs); free_dev(p.d_ljobs); free_table(p.tab);
+  free_dev(p.d_jobs); free_dev(p.d_rjobs); free_dev(p.d_ljobs); free_dev(p.d_pjobs); free_table(p.tab);
   p = FactorPlan{};
 }
 void release(InvertPlan& p) {
@@ -448,7 +449,7 @@ struct FactorSchedule {
   std::vector<TileJob> jobs;
   std::vector<ReduceJob> rjobs;
   std::vector<LagLayer> lags;
-  std::vector<LagJob> ljobs;
+  std::vector<LagJob> ljobs, pjobs;   // mirror tiles; channel-pair tiles
   size_t nslots = 0, lag_floats = 0;
   kfac_plan_stats stats{};
 };
@@ -518,6 +519,11 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
         const int T = ceil_div(dA_of(L), 64);
         for (int bi = 0; bi < T; ++bi)
           for (int bj = 0; bj <= bi; ++bj) S.ljobs.push_back(LagJob{int(S.lags.size()), bi, bj, 0});
+        {   // tiles of channel pairs (c, c2), c2 <= c, over the channels 0 .. C - 1 and the bias pseudo-channel C
+          const int PR = lag_pair_rows(), PC = lag_pair_cols(), nch = L.c_in + (b ? 1 : 0);
+          for (int bi = 0; bi < ceil_div(nch, PR); ++bi)
+            for (int bj = 0; bj * PC <= std::min(nch - 1, bi * PR + PR - 1); ++bj) S.pjobs.push_back(LagJob{int(S.lags.size()), bi, bj, 0});
+        }
         S.lags.push_back(lg);
         continue;
       }
@@ -575,8 +581,8 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
   } else {
     for (auto& l : lists) S.jobs.insert(S.jobs.end(), l.begin(), l.end());
   }
-  S.stats.n_jobs = int64_t(S.jobs.size() + S.rjobs.size() + S.ljobs.size());
-  S.stats.n_launches = 1 + (S.rjobs.empty() ? 0 : 1) + (S.ljobs.empty() ? 0 : 1);
+  S.stats.n_jobs = int64_t(S.jobs.size() + S.rjobs.size() + S.ljobs.size() + S.pjobs.size());
+  S.stats.n_launches = 1 + (S.rjobs.empty() ? 0 : 1) + (S.ljobs.empty() ? 0 : 2);
   S.stats.ws_bytes = int64_t((S.nslots * size_t(BM) * BN + S.lag_floats) * sizeof(float));
   return S;
 }
@@ -1016,6 +1022,7 @@ static kfac_status update_factors_impl(kfac_ctx* ctx, int n, const kfac_layer* l
     P.lags = S.lags;
     P.lag_floats = S.lag_floats;
     P.nljobs = int(S.ljobs.size());
+    P.npjobs = int(S.pjobs.size());
     P.stats = S.stats;
     if (!ctx->host_only) {
       kfac_status st = upload_static(ctx, &P.d_jobs, S.jobs.data(), S.jobs.size() * sizeof(TileJob));
@@ -1023,6 +1030,7 @@ static kfac_status update_factors_impl(kfac_ctx* ctx, int n, const kfac_layer* l
       st = upload_static(ctx, &P.d_rjobs, S.rjobs.data(), S.rjobs.size() * sizeof(ReduceJob));
       if (st != KFAC_OK) return st;
       st = upload_static(ctx, &P.d_ljobs, S.ljobs.data(), S.ljobs.size() * sizeof(LagJob));
+      if (st == KFAC_OK) st = upload_static(ctx, &P.d_pjobs, S.pjobs.data(), S.pjobs.size() * sizeof(LagJob));
       if (st != KFAC_OK) return st;
     }
     P.valid = true;
@@ -1096,7 +1104,7 @@ static kfac_status update_factors_impl(kfac_ctx* ctx, int n, const kfac_layer* l
   if (P.nrjobs || P.nljobs) {
     ScopedTiming tm(ctx, KFAC_K_FACTOR_REDUCE, s);
     launch_tile_reduce(d_descs, static_cast<const ReduceJob*>(P.d_rjobs), P.nrjobs, s);
-    launch_lag_assemble(d_asms, static_cast<const LagJob*>(P.d_ljobs), P.nljobs, s);
+    launch_lag_assemble(d_asms, static_cast<const LagJob*>(P.d_pjobs), P.npjobs, static_cast<const LagJob*>(P.d_ljobs), P.nljobs, s);
   }
   HIP_TRY(ctx, hipGetLastError());
   return KFAC_OK;

@@ -12,7 +12,11 @@ void launch_tile_gemm_dl(const TileDesc* descs, const TileJob* jobs, int njobs, 
 // row-major x row-major products that give way to latency-critical workgroups on their compute unit (cu_flags may be null)
 void launch_tile_gemm_yield(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, const int* cu_flags, hipStream_t s);
 void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs, hipStream_t s);
-void launch_lag_assemble(const LagAsm* lags, const LagJob* jobs, int njobs, hipStream_t s);
+// pair_jobs: tiles of lag_pair_rows() x lag_pair_cols() channel pairs (bi, bj) that hold a pair c2 <= c, the
+// bias pseudo-channel C included; mirror_jobs: 64 x 64 tiles bi >= bj of the factor
+void launch_lag_assemble(const LagAsm* lags, const LagJob* pair_jobs, int npair, const LagJob* mirror_jobs, int nmirror, hipStream_t s);
+int lag_pair_rows();
+int lag_pair_cols();
 
 void launch_gj_init(const InvMat* mats, const void* jobs, int njobs, float gamma, hipStream_t s);
 // cu_flags (may be null): table of CU_SLOTS words in which the latency-critical workgroups of these

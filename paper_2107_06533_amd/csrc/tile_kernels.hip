@@ -161,84 +161,133 @@ __global__ __launch_bounds__(NT) void tile_reduce_kernel(const TileDesc* __restr
   }
 }
 
-// Assembly of a lag-product activation factor (see LagAsm): one 64 x 64 tile of the lower triangle
-// of A per workgroup; every element is a sum of at most four entries of the small lag matrices,
-// blended with the old value and written to both (q, q') and (q', q).
-constexpr int LAG_TILE = 64;
-// Raw sum for the tap column (c, i, j) against the tap column (c2, i2, j2), or against the bias
-// column when isbias (then c2 = C, i2 = j2 = 0 are ignored).  All offsets fit 32 bits.
-__device__ __forceinline__ float lag_value(const LagAsm& L, int c, int i, int j, int c2, int i2, int j2, bool isbias) {
-  const uint32_t C = (uint32_t)L.C, ld1 = 10u * C, ld2 = 3u * C + L.bias, ld5 = 5u * C + L.bias, ldc = C + L.bias;
-  const int dy = isbias ? 0 : i2 - i, dx = isbias ? 0 : j2 - j;
+// Assembly of a lag-product activation factor (see LagAsm), lower triangle: a thread owns one pair of
+// channels (c, c2), c2 <= c, i.e. the 9 x 9 block of A at rows 9c.., columns 9c2..  Its 81 entries
+// are sums of at most four of 49 entries of the small lag matrices, picked by compile-time tap indices:
+//   the lag product   dy > 0: G1[c][(c2, dy, dx)]      dy = 0, dx >= 0: G2[c][(c2, dx)]
+//                     dy < 0: G1[c2][(c, -dy, -dx)]    dy = 0, dx < 0:  G2[c2][(c, -dx)]     (backward lags: transposes)
+//   minus the border row that tap row i drops (bottom row for i = 0, top row for i = 2), which pairs
+//   with itself only (dy = 0), minus the border column that tap column j drops (dx = 0 only), plus
+//   their common corner pixel (dy = dx = 0).
+// The pseudo-channel c = C is the bias row: its entries against (c2, t2) are the sums of a over the
+// pixels tap t2 keeps, its last entry the number of rows.  Consecutive lanes hold consecutive c2, so a
+// wave reads and writes runs of 9 x 32 consecutive floats of a row of A.  The upper triangle is
+// filled in by lag_mirror_kernel.  All offsets fit 32 bits.
+constexpr int LAG_PC = 32, LAG_PR = NT / LAG_PC;   // pair tile: 8 row channels x 32 column channels
+__global__ __launch_bounds__(NT) void lag_pairs_kernel(const LagAsm* __restrict__ lags,
+                                                       const LagJob* __restrict__ jobs, int njobs) {
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const LagJob J = jobs[g];
+  const LagAsm L = lags[J.lag];
+  const int C = L.C;
+  const uint32_t uC = (uint32_t)C, dA = (uint32_t)L.dA;
+  const uint32_t ld1 = 10u * uC, ld2 = 3u * uC + L.bias, ld5 = 5u * uC + L.bias, ldc = uC + L.bias;
+  const int c2 = J.bj * LAG_PC + (int)(threadIdx.x & (LAG_PC - 1));
+  const int c = J.bi * LAG_PR + (int)(threadIdx.x / LAG_PC);
+  const int cmax = L.bias ? C : C - 1;
+  if (c > cmax || c2 > c) return;
+  gf_ptr A = as_global(L.A);
   gcf_ptr G1 = as_global(L.G[LAG_G1]);
   gcf_ptr G2 = as_global(L.G[LAG_G2]);
-  float v;   // forward lags are stored; a backward lag is the transposed entry of its opposite
-  if (isbias) v = G2[c * ld2 + 3u * C];   // sums of a over the whole image
-  else if (dy > 0) v = G1[c * ld1 + c2 * 10 + (dy - 1) * 5 + dx + 2];
-  else if (dy == 0 && dx >= 0) v = G2[c * ld2 + c2 * 3 + dx];
-  else if (dy < 0) v = G1[c2 * ld1 + c * 10 + (-dy - 1) * 5 - dx + 2];
-  else v = G2[c2 * ld2 + c * 3 - dx];
-  // Pixels q whose output pixel q - (t - 1) lies outside the grid are taken out again: bottom row for
-  // i = 0, top row for i = 2, right column for j = 0, left column for j = 2.  The partner pixel q + lag
-  // of a pixel in the bottom row lies below the image unless dy <= 0, and the tap i = 0 only asks for
-  // dy >= 0 (the top row: the other way round), so a row strip contributes for dy = 0 only; a column
-  // strip for dx = 0 only; their common corner pixel for lag 0 only.  In the bias column (c2 = C,
-  // dy = dx = 0) the indices below land on the ones column of every strip.
-  if (i != 1 && dy == 0) {
-    gcf_ptr S = as_global(i == 0 ? L.G[LAG_BOT] : L.G[LAG_TOP]);                           // [C][5C + bias], lags dx = -2..2
-    v -= S[c * ld5 + c2 * 5 + (isbias ? 0 : dx + 2)];
+  gcf_ptr TOP = as_global(L.G[LAG_TOP]), BOT = as_global(L.G[LAG_BOT]);
+  gcf_ptr LEFT = as_global(L.G[LAG_LEFT]), RIGHT = as_global(L.G[LAG_RIGHT]);
+  gcf_ptr TL = as_global(L.G[LAG_TL]), TR = as_global(L.G[LAG_TR]), BL = as_global(L.G[LAG_BL]), BR = as_global(L.G[LAG_BR]);
+  const float alpha = L.alpha, beta = L.beta;
+  const uint32_t uc = (uint32_t)c, uc2 = (uint32_t)c2;
+
+  if (c == C) {   // bias row
+    const uint32_t row = 9u * uC * dA;
+    if (c2 == C) {
+      const float old = beta != 0.f ? A[row + 9u * uC] : 0.f;
+      A[row + 9u * uC] = alpha * L.rows + beta * old;
+      return;
+    }
+    const float whole = G2[uc2 * ld2 + 3u * uC];
+    const float bot = BOT[uc2 * ld5 + 5u * uC], top = TOP[uc2 * ld5 + 5u * uC];
+    const float rgt = RIGHT[uc2 * ld5 + 5u * uC], lft = LEFT[uc2 * ld5 + 5u * uC];
+    const float br = BR[uc2 * ldc + uC], bl = BL[uc2 * ldc + uC], tr = TR[uc2 * ldc + uC], tl = TL[uc2 * ldc + uC];
+    float old[9];
+#pragma unroll
+    for (int t2 = 0; t2 < 9; ++t2) old[t2] = beta != 0.f ? A[row + 9u * uc2 + t2] : 0.f;
+#pragma unroll
+    for (int t2 = 0; t2 < 9; ++t2) {
+      const int i2 = t2 / 3, j2 = t2 % 3;
+      float v = whole;
+      if (i2 != 1) v -= i2 == 0 ? bot : top;
+      if (j2 != 1) v -= j2 == 0 ? rgt : lft;
+      if (i2 != 1 && j2 != 1) v += i2 == 0 ? (j2 == 0 ? br : bl) : (j2 == 0 ? tr : tl);
+      A[row + 9u * uc2 + t2] = alpha * v + beta * old[t2];
+    }
+    return;
   }
-  if (j != 1 && dx == 0) {
-    gcf_ptr S = as_global(j == 0 ? L.G[LAG_RIGHT] : L.G[LAG_LEFT]);                        // [C][5C + bias], lags dy = -2..2
-    v -= S[c * ld5 + c2 * 5 + (isbias ? 0 : dy + 2)];
+
+  float g1a[10], g1b[10], g2a[3], g2b[3], srow[2][5], scol[2][5], cor[4];
+#pragma unroll
+  for (int q = 0; q < 10; ++q) {
+    g1a[q] = G1[uc * ld1 + uc2 * 10u + q];
+    g1b[q] = G1[uc2 * ld1 + uc * 10u + q];
   }
-  if (i != 1 && j != 1 && dy == 0 && dx == 0) {
-    gcf_ptr S = as_global(i == 0 ? (j == 0 ? L.G[LAG_BR] : L.G[LAG_BL]) : (j == 0 ? L.G[LAG_TR] : L.G[LAG_TL]));   // [C][C + bias]
-    v += S[c * ldc + c2];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    g2a[q] = G2[uc * ld2 + uc2 * 3u + q];
+    g2b[q] = G2[uc2 * ld2 + uc * 3u + q];
   }
-  return v;
+#pragma unroll
+  for (int q = 0; q < 5; ++q) {
+    srow[0][q] = BOT[uc * ld5 + uc2 * 5u + q];     // tap row i = 0 drops the bottom row
+    srow[1][q] = TOP[uc * ld5 + uc2 * 5u + q];     // i = 2: the top row
+    scol[0][q] = RIGHT[uc * ld5 + uc2 * 5u + q];   // tap column j = 0 drops the right column
+    scol[1][q] = LEFT[uc * ld5 + uc2 * 5u + q];    // j = 2: the left column
+  }
+  cor[0] = BR[uc * ldc + uc2]; cor[1] = BL[uc * ldc + uc2];   // i = 0: j = 0, j = 2
+  cor[2] = TR[uc * ldc + uc2]; cor[3] = TL[uc * ldc + uc2];   // i = 2: j = 0, j = 2
+  const bool dpair = c == c2;   // diagonal block: entries with t2 <= t only
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    const int i = t / 3, j = t % 3;
+    const uint32_t row = (9u * uc + t) * dA + 9u * uc2;
+    float old[9];
+#pragma unroll
+    for (int t2 = 0; t2 < 9; ++t2) old[t2] = (beta != 0.f && (!dpair || t2 <= t)) ? A[row + t2] : 0.f;
+#pragma unroll
+    for (int t2 = 0; t2 < 9; ++t2) {
+      const int i2 = t2 / 3, j2 = t2 % 3, dy = i2 - i, dx = j2 - j;
+      float v;
+      if (dy > 0) v = g1a[(dy - 1) * 5 + dx + 2];
+      else if (dy == 0 && dx >= 0) v = g2a[dx];
+      else if (dy < 0) v = g1b[(-dy - 1) * 5 - dx + 2];
+      else v = g2b[-dx];
+      if (i != 1 && dy == 0) v -= srow[i == 0 ? 0 : 1][dx + 2];
+      if (j != 1 && dx == 0) v -= scol[j == 0 ? 0 : 1][dy + 2];
+      if (i != 1 && j != 1 && dy == 0 && dx == 0) v += cor[(i == 0 ? 0 : 2) + (j == 0 ? 0 : 1)];
+      if (!dpair || t2 <= t) A[row + t2] = alpha * v + beta * old[t2];
+    }
+  }
 }
 
-// One 64 x 64 tile of the lower triangle of A per workgroup (thread = one column, 16 rows).  Only
-// elements on or below the diagonal are computed; the mirror image goes through LDS so that both
-// copies are stored row by row, and both hold the same bits.
-__global__ __launch_bounds__(NT) void lag_assemble_kernel(const LagAsm* __restrict__ lags,
-                                                          const LagJob* __restrict__ jobs, int njobs) {
+// Upper triangle (and packed copy) of a lag-product activation factor from its finished lower
+// triangle: one 64 x 64 tile per workgroup, transposed through LDS so that both sides are moved row
+// by row; both triangles hold the same bits.
+constexpr int LAG_TILE = 64;
+__global__ __launch_bounds__(NT) void lag_mirror_kernel(const LagAsm* __restrict__ lags,
+                                                        const LagJob* __restrict__ jobs, int njobs) {
   __shared__ float tile[LAG_TILE][LAG_TILE + 1];
   const int g = blockIdx.x;
   if (g >= njobs) return;
   const LagJob J = jobs[g];
   const LagAsm L = lags[J.lag];
-  const int dA = L.dA, nb = 9 * L.C;
+  const int dA = L.dA;
   constexpr int PER = LAG_TILE * LAG_TILE / NT;
   gf_ptr A = as_global(L.A);
-  // a wave shares its row: row-derived index arithmetic runs on the scalar unit
-  const int lc = threadIdx.x & (LAG_TILE - 1), lr0 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int cc = J.bj * LAG_TILE + lc;                  // this thread's column
-  const bool cbias = cc >= nb;
-  const int c2 = cbias ? L.C : cc / 9, t2 = cbias ? 0 : cc - 9 * c2, i2 = t2 / 3, j2 = t2 - 3 * i2;
-  float v[PER], old[PER];
-#pragma unroll
-  for (int u = 0; u < PER; ++u) {
-    const int r = J.bi * LAG_TILE + lr0 + 4 * u;
-    v[u] = 0.f; old[u] = 0.f;
-    if (r >= dA || cc > r) continue;
-    if (r < nb) {
-      const int c = r / 9, t = r - 9 * c, i = t / 3, j = t - 3 * i;
-      v[u] = lag_value(L, c, i, j, c2, i2, j2, false);
-    } else if (!cbias) {
-      v[u] = lag_value(L, c2, i2, j2, L.C, 0, 0, true);   // bias row: the mirrored bias-column entry
-    } else {
-      v[u] = L.rows;                                      // bias-bias
-    }
-    if (L.beta != 0.f) old[u] = A[(uint32_t)r * (uint32_t)dA + (uint32_t)cc];
-  }
+  const int lc = threadIdx.x & (LAG_TILE - 1), lr0 = threadIdx.x >> 6;
+  const int cc = J.bj * LAG_TILE + lc;
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
     const int lr = lr0 + 4 * u, r = J.bi * LAG_TILE + lr;
-    const float val = L.alpha * v[u] + L.beta * old[u];
+    float val = 0.f;
+    if (r < dA && cc <= r) val = A[(uint32_t)r * (uint32_t)dA + (uint32_t)cc];
     tile[lr][lc] = val;
-    if (r < dA && cc <= r) A[(uint32_t)r * (uint32_t)dA + (uint32_t)cc] = val;
     if (L.P && r < dA && cc == r) as_global(L.P)[(size_t)r * dA - (size_t)r * (r - 1) / 2] = val;
   }
   __syncthreads();
@@ -280,10 +329,12 @@ void launch_tile_gemm_pad(const TileDesc* descs, const TileJob* jobs, int njobs,
   hipLaunchKernelGGL(tile_gemm_kernel, dim3(njobs), dim3(NT), pad_bytes, s, descs, jobs, njobs, 0);
 }
 
-void launch_lag_assemble(const LagAsm* lags, const LagJob* jobs, int njobs, hipStream_t s) {
-  if (njobs <= 0) return;
-  hipLaunchKernelGGL(lag_assemble_kernel, dim3(njobs), dim3(NT), 0, s, lags, jobs, njobs);
+void launch_lag_assemble(const LagAsm* lags, const LagJob* pair_jobs, int npair, const LagJob* mirror_jobs, int nmirror, hipStream_t s) {
+  if (npair > 0) hipLaunchKernelGGL(lag_pairs_kernel, dim3(npair), dim3(NT), 0, s, lags, pair_jobs, npair);
+  if (nmirror > 0) hipLaunchKernelGGL(lag_mirror_kernel, dim3(nmirror), dim3(NT), 0, s, lags, mirror_jobs, nmirror);
 }
+int lag_pair_rows() { return LAG_PR; }
+int lag_pair_cols() { return LAG_PC; }
 
 void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs, hipStream_t s) {
   if (njobs <= 0) return;

@@ -204,7 +204,7 @@ def test_options_change_the_schedule_not_the_environment(hctx, monkeypatch):
         c.set_option("factor_lag", 0)
         c.kfac_update_factors(L, [1], [1], [1], [1], 0.5, check=False)
         without = c.plan_stats(0)
-        assert with_lag["n_launches"] == 2 and without["n_launches"] == 1
+        assert with_lag["n_launches"] == 3 and without["n_launches"] == 1   # tiles + pair assembly + mirror; tiles alone
         assert with_lag["ws_bytes"] > without["ws_bytes"]
     finally:
         c.close()
