@@ -111,12 +111,13 @@ struct ReduceJob {
 // (negative lags are transposes), minus the same products restricted to one border row and one
 // border column of q, plus the corner pixel.  Of the lags the excluding tap can ask for, only those
 // along the strip pair two pixels inside the image (the tap that drops the bottom row asks for
-// dy >= 0, and nothing lies below that row), so a row strip needs the 1x5 lags dx = -2..2, a column
-// strip the 5x1 lags dy = -2..2 and a corner lag 0; a ones column gives the bias sums.
+// dy >= 0, and nothing lies below that row), and a strip is closed under shifts along itself, so a row
+// strip needs the forward lags dx = 0, 1, 2 (backward: transposes), a column strip dy = 0, 1, 2 and a
+// corner lag 0; a ones column gives the bias sums.
 enum : int32_t { LAG_G1 = 0, LAG_G2, LAG_TOP, LAG_BOT, LAG_LEFT, LAG_RIGHT, LAG_TL, LAG_TR, LAG_BL, LAG_BR, LAG_NMAT };
 
 struct LagAsm {
-  const float* G[LAG_NMAT];   // G1 [C][10C], G2 [C][3C + bias], rows/columns [C][5C + bias], corners [C][C + bias]
+  const float* G[LAG_NMAT];   // G1 [C][10C], G2 [C][3C + bias], rows/columns [C][3C + bias], corners [C][C + bias]
   float* A;                   // [dA][dA], dA = 9C + bias
   float* P;                   // may be null: packed upper triangle of A, dA (dA + 1) / 2 floats
   int32_t C, bias, dA, pad0;

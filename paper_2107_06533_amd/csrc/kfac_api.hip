@@ -503,10 +503,11 @@ FactorSchedule schedule_factors(int n, const kfac_layer* layers, const std::vect
           else {
             // A border row pairs with itself only: the tap in row i = 0 (which drops the bottom row) asks
             // for lags dy = i' - i >= 0, and below the bottom row there is nothing, so dy = 0 and the
-            // five lags along the row remain; likewise a border column (dx = 0, five lags along it) and
-            // a corner pixel (lag 0 only).
+            // lags along the row remain, of which the backward ones are transposes of the forward ones
+            // (the row is closed under the shift): dx = 0, 1, 2.  Likewise a border column (dx = 0,
+            // dy = 0, 1, 2) and a corner pixel (lag 0 only).
             static const int geo[LAG_NMAT][4] = {{0, 0, 0, 0}, {0, 0, 0, 0},                 // KH, KW, pad_h, pad_w
-                                                 {1, 5, 0, 2}, {1, 5, 0, 2}, {5, 1, 2, 0}, {5, 1, 2, 0},
+                                                 {1, 3, 0, 0}, {1, 3, 0, 0}, {3, 1, 0, 0}, {3, 1, 0, 0},
                                                  {1, 1, 0, 0}, {1, 1, 0, 0}, {1, 1, 0, 0}, {1, 1, 0, 0}};
             D.b = lag_operand(L, OP_CONVGEN, geo[k][0], geo[k][1], geo[k][2], geo[k][3], b, w[0], w[1], w[2], w[3]);
           }

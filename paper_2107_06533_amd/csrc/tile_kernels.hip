@@ -182,7 +182,7 @@ __global__ __launch_bounds__(NT) void lag_pairs_kernel(const LagAsm* __restrict_
   const LagAsm L = lags[J.lag];
   const int C = L.C;
   const uint32_t uC = (uint32_t)C, dA = (uint32_t)L.dA;
-  const uint32_t ld1 = 10u * uC, ld2 = 3u * uC + L.bias, ld5 = 5u * uC + L.bias, ldc = uC + L.bias;
+  const uint32_t ld1 = 10u * uC, ld2 = 3u * uC + L.bias, ld3 = ld2, ldc = uC + L.bias;   // strips: [C][3C + bias] as G2
   const int c2 = J.bj * LAG_PC + (int)(threadIdx.x & (LAG_PC - 1));
   const int c = J.bi * LAG_PR + (int)(threadIdx.x / LAG_PC);
   const int cmax = L.bias ? C : C - 1;
@@ -204,8 +204,8 @@ __global__ __launch_bounds__(NT) void lag_pairs_kernel(const LagAsm* __restrict_
       return;
     }
     const float whole = G2[uc2 * ld2 + 3u * uC];
-    const float bot = BOT[uc2 * ld5 + 5u * uC], top = TOP[uc2 * ld5 + 5u * uC];
-    const float rgt = RIGHT[uc2 * ld5 + 5u * uC], lft = LEFT[uc2 * ld5 + 5u * uC];
+    const float bot = BOT[uc2 * ld3 + 3u * uC], top = TOP[uc2 * ld3 + 3u * uC];
+    const float rgt = RIGHT[uc2 * ld3 + 3u * uC], lft = LEFT[uc2 * ld3 + 3u * uC];
     const float br = BR[uc2 * ldc + uC], bl = BL[uc2 * ldc + uC], tr = TR[uc2 * ldc + uC], tl = TL[uc2 * ldc + uC];
     float old[9];
 #pragma unroll
@@ -233,12 +233,21 @@ __global__ __launch_bounds__(NT) void lag_pairs_kernel(const LagAsm* __restrict_
     g2a[q] = G2[uc * ld2 + uc2 * 3u + q];
     g2b[q] = G2[uc2 * ld2 + uc * 3u + q];
   }
+  // strips hold the forward lags 0, 1, 2 along themselves; a backward lag is the transposed entry
+  // of its opposite: index 2 + lag in the arrays below
 #pragma unroll
-  for (int q = 0; q < 5; ++q) {
-    srow[0][q] = BOT[uc * ld5 + uc2 * 5u + q];     // tap row i = 0 drops the bottom row
-    srow[1][q] = TOP[uc * ld5 + uc2 * 5u + q];     // i = 2: the top row
-    scol[0][q] = RIGHT[uc * ld5 + uc2 * 5u + q];   // tap column j = 0 drops the right column
-    scol[1][q] = LEFT[uc * ld5 + uc2 * 5u + q];    // j = 2: the left column
+  for (int q = 0; q < 3; ++q) {
+    srow[0][2 + q] = BOT[uc * ld3 + uc2 * 3u + q];     // tap row i = 0 drops the bottom row
+    srow[1][2 + q] = TOP[uc * ld3 + uc2 * 3u + q];     // i = 2: the top row
+    scol[0][2 + q] = RIGHT[uc * ld3 + uc2 * 3u + q];   // tap column j = 0 drops the right column
+    scol[1][2 + q] = LEFT[uc * ld3 + uc2 * 3u + q];    // j = 2: the left column
+  }
+#pragma unroll
+  for (int q = 1; q < 3; ++q) {
+    srow[0][2 - q] = BOT[uc2 * ld3 + uc * 3u + q];
+    srow[1][2 - q] = TOP[uc2 * ld3 + uc * 3u + q];
+    scol[0][2 - q] = RIGHT[uc2 * ld3 + uc * 3u + q];
+    scol[1][2 - q] = LEFT[uc2 * ld3 + uc * 3u + q];
   }
   cor[0] = BR[uc * ldc + uc2]; cor[1] = BL[uc * ldc + uc2];   // i = 0: j = 0, j = 2
   cor[2] = TR[uc * ldc + uc2]; cor[3] = TL[uc * ldc + uc2];   // i = 2: j = 0, j = 2
