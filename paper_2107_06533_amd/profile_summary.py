@@ -43,7 +43,7 @@ def main(tag: str, out_dir: str) -> None:
         calls = int(r["Calls"]); tot = float(r["TotalDurationNs"]) / 1e6
         out.append(f"| {short(r['Name'])} | {calls} | {calls/steps:.1f} | {float(r['AverageNs'])/1e3:.1f} | {tot:.2f} | {tot/steps:.3f} | {float(r['Percentage']):.1f} |")
     out.append("")
-    out.append("Notes: inside kfac_invert_batch the sweep chain runs on the caller's stream and the off-chain updates on a side stream, so kernels of the two streams overlap and their per-step sums exceed the wall time of the call; tile_gemm_yield_kernel serves the inverse's panel and update products, tile_gemm_kernel and tile_gemm_dl_kernel the two preconditioning products; lag_assemble_kernel builds the 3x3 activation factors from the lag products that tile_any_kernel wrote.\n")
+    out.append("Notes: inside kfac_invert_batch the sweep chain runs on the caller's stream and the off-chain updates on a side stream, so kernels of the two streams overlap and their per-step sums exceed the wall time of the call; tile_gemm_yield_kernel serves the inverse's panel and update products, tile_gemm_kernel and tile_gemm_dl_kernel the two preconditioning products; lag_pairs_kernel and lag_mirror_kernel build the 3x3 activation factors from the lag products that tile_any_kernel wrote.\n")
     open(f"profiles/{tag}_kernel_trace.md", "w").write("\n".join(out))
 
     # traffic
@@ -66,7 +66,7 @@ def main(tag: str, out_dir: str) -> None:
     lines.append("| kernel | FETCH KiB/dispatch (raw) | fetched MB (scaled) | WRITE KiB/dispatch (raw) | written MB (scaled) |")
     lines.append("|---|---|---|---|---|")
     for k in per["FETCH_SIZE"]:
-        if not ("tile" in k or "gj_" in k): continue
+        if not ("tile" in k or "gj_" in k or "lag_" in k): continue
         f = per["FETCH_SIZE"][k]; w = per["WRITE_SIZE"].get(k, 0)
         lines.append(f"| {k} | {f:.0f} | {f*scale['FETCH_SIZE']*1024/1e6:.1f} | {w:.0f} | {w*scale['WRITE_SIZE']*1024/1e6:.1f} |")
         res[k] = {"fetch_bytes": f * scale["FETCH_SIZE"] * 1024, "write_bytes": w * scale["WRITE_SIZE"] * 1024}
