@@ -88,6 +88,11 @@ CONV_CASES = [
     (3, 5, 2, 2, 3, 1, 1, 1, 0, 0),
     (40, 16, 16, 16, 8, 1, 1, 1, 0, 1),     # R = 10240 > one job
     (5, 129, 4, 3, 257, 1, 1, 1, 0, 1),     # ragged channel tiles on both factors
+    (7, 257, 3, 4, 300, 1, 1, 1, 0, 1),     # ones column alone in the third tile row; G ends on a 44-row tile; 84 rows
+    (3, 80, 2, 2, 50, 1, 1, 1, 0, 0),       # single diagonal tiles of three and of two valid block rows
+    # lag products whose channel count is no multiple of the assembly's pair tiles
+    (2, 100, 6, 5, 4, 3, 3, 1, 1, 1),
+    (2, 96, 3, 8, 4, 3, 3, 1, 1, 0),
 ]
 
 
