@@ -91,7 +91,7 @@ typedef enum {
   KFAC_OPT_INV_AGG = 1,       /* 1..16  [4]     pivot blocks per outer block, throughput-bound group               */
   KFAC_OPT_INV_AGG_CHAIN = 2, /* 1..16  [6]     the same for a group bound by its chain of dependent launches      */
   KFAC_OPT_INV_FUSE = 3,      /* 0/1    [1]     pivot block applies the previous block's update to itself          */
-  KFAC_OPT_INV_SIDE_PAD = 4,  /* 0..65536 [56000] bytes of unused LDS added to off-chain products (occupancy)      */
+  KFAC_OPT_INV_SIDE_PAD = 4,  /* 0..65536 [56000] bytes of LDS beyond 32 KB held by off-chain products (occupancy)      */
   KFAC_OPT_FACTOR_LAG = 5,    /* 0/1    [1]     3x3/stride 1/pad 1 activation factors from products over pixel lags */
   KFAC_OPT_FACTOR_VEC11 = 6,  /* 0/1    [1]     128-bit loads for 1x1 windows over whole images                    */
   KFAC_OPT_FACTOR_XCD = 7,    /* 0/1    [0]     factor jobs dealt to the 8 XCDs in contiguous segments             */
@@ -100,7 +100,8 @@ typedef enum {
   KFAC_OPT_INV_SIDE = 10,     /* 0/1    [1]     off-chain work of a group on a second internal stream                  */
   KFAC_OPT_INV_SPLIT_LONG = 11, /* 0/1  [1]     the matrices with the longest chains form a group of their own         */
   KFAC_OPT_INV_YIELD = 12,    /* 0..65536 [64] sweep-chain kernels of at most this many workgroups make products give way   */
-  KFAC_OPT_COUNT = 13
+  KFAC_OPT_INV_QUARTER = 13,  /* 0/1    [1]     products on the sweep chain of the inverse on quarter tiles (four workgroups a tile) */
+  KFAC_OPT_COUNT = 14
 } kfac_option;
 kfac_status kfac_set_option(kfac_ctx* ctx, int option, int value);
 kfac_status kfac_get_option(const kfac_ctx* ctx, int option, int* value);

@@ -22,7 +22,7 @@ EXPORTS = [
 
 # kfac_option, in the order of the header
 OPTIONS = ["inv_groups", "inv_agg", "inv_agg_chain", "inv_fuse", "inv_side_pad",
-           "factor_lag", "factor_vec11", "factor_xcd", "factor_kjob", "inv_chain_pad", "inv_side", "inv_split_long", "inv_yield"]
+           "factor_lag", "factor_vec11", "factor_xcd", "factor_kjob", "inv_chain_pad", "inv_side", "inv_split_long", "inv_yield", "inv_quarter"]
 
 KERNEL_CLASSES = ["factor_tiles", "factor_reduce", "inv_small", "inv_init", "inv_pivot", "inv_panel",
                   "inv_update", "inv_finish", "precond_left", "precond_right", "tri_pack"]

@@ -91,7 +91,8 @@ struct TileJob {
   int32_t bi, bj;
   int32_t kbeg, kend;
   int32_t part;     // >= 0: write the raw tile to partial slot `part`; -1: apply the epilogue directly
-  int32_t pad0, pad1;
+  int32_t quarter;  // jobs of the quarter-tile kernel: 1 + the 32-column block of the tile this job computes
+  int32_t pad1;
 };
 
 // reduction of split tiles: out = beta*out + alpha * sum_s partial[part0 + s]

@@ -399,7 +399,7 @@ __global__ __launch_bounds__(NT) void gj_pivot_update_kernel(const InvMat* __res
                                                              int npiv, int step, float gamma,
                                                              const TileDesc* __restrict__ descs,
                                                              const TileJob* __restrict__ ujobs, int nupd, int* cu_flags, int critical) {
-  __shared__ __attribute__((aligned(16))) float smem[PIVOT_LDS_FLOATS > DL_LDS_FLOATS ? PIVOT_LDS_FLOATS : DL_LDS_FLOATS];
+  __shared__ __attribute__((aligned(16))) float smem[PIVOT_LDS_FLOATS > DL_DEEP_LDS_FLOATS ? PIVOT_LDS_FLOATS : DL_DEEP_LDS_FLOATS];
   const int g = blockIdx.x;
   if (g < npiv) {
     const InvMat Mx = mats[pjobs[g].mat];
@@ -409,7 +409,7 @@ __global__ __launch_bounds__(NT) void gj_pivot_update_kernel(const InvMat* __res
     cu_leave(mine);
   } else if (g - npiv < nupd) {
     const TileJob J = ujobs[g - npiv];
-    run_tile_dl<true, true>(descs[J.desc], J, smem, cu_flags);
+    run_tile_dl<true, true, DL_KC_DEEP>(descs[J.desc], J, smem, cu_flags);
   }
 }
 

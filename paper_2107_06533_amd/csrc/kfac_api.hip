@@ -81,6 +81,8 @@ struct InvertGroup {
   void* d_sub_pivot = nullptr; void* d_sub_panel = nullptr; void* d_sub_upd = nullptr;
   void* d_qm = nullptr; void* d_mv = nullptr; void* d_bp = nullptr;
   void* d_upd[3] = {nullptr, nullptr, nullptr};
+  void* d_chain_q = nullptr;         // quarter-tile jobs of the chain's products
+  std::vector<int> cq_bp_off, cq_bp_end, cq_diag_end;
   std::vector<hipEvent_t> ev_gather, ev_chain, ev_col, ev_rest;   // [outer block], created on first use
   DynTable tab;                      // [InvMat x n][InvMat x views][PanelMove x 2 views][TileDesc x (2 views + n_large)]
   size_t ws_floats = 0, ws_base = 0;
@@ -139,7 +141,7 @@ struct kfac_ctx {
       /* INV_AGG        */ 4,       // pivot blocks per outer block (rank agg*128 updates), throughput-bound group
       /* INV_AGG_CHAIN  */ 6,       // the same for a latency-bound group (fewer outer steps on the critical path)
       /* INV_FUSE       */ 1,       // a pivot block applies the previous block's update to itself (one launch fewer per step)
-      /* INV_SIDE_PAD   */ 56000,   // unused LDS added to the off-chain products of a latency-bound group: one workgroup
+      /* INV_SIDE_PAD   */ 56000,   // unused LDS beyond 32 KB in the off-chain products of a latency-bound group: one workgroup
                                     // per compute unit, so that the chain's kernels always find a free slot
       /* FACTOR_LAG     */ 1,       // lag products for 3x3 / stride 1 / pad 1 activation factors
       /* FACTOR_VEC11   */ 1,       // 128-bit loader for 1x1 windows over whole images
@@ -151,6 +153,7 @@ struct kfac_ctx {
       /* INV_SPLIT_LONG */ 1,       // the matrices with the longest chains form a group of their own
       /* INV_YIELD      */ 64,      // chain kernels of at most this many workgroups make the products on their compute
                                     // units give way while they run (0: off)
+      /* INV_QUARTER    */ 1,       // the chain's two products of an outer block on quarter tiles (four workgroups a tile)
   };
   int* cu_flags = nullptr;          // per-compute-unit words of that protocol (device memory, zero when no kernel runs)
   hipStream_t inv_stream[MAX_INV_GROUPS] = {};   // sweep chain of groups 1.. (group 0 uses the caller's stream)
@@ -424,6 +427,7 @@ void release(InvertPlan& p) {
     free_dev(g.d_init); free_dev(g.d_finish); free_dev(g.d_sub_pivot); free_dev(g.d_sub_panel); free_dev(g.d_sub_upd);
     free_dev(g.d_qm); free_dev(g.d_mv); free_dev(g.d_bp);
     for (int k = 0; k < 3; ++k) free_dev(g.d_upd[k]);
+    free_dev(g.d_chain_q);
     free_table(g.tab);
     for (hipEvent_t e : g.ev_chain) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : g.ev_gather) if (e) (void)hipEventDestroy(e);
@@ -615,6 +619,10 @@ struct InvertSchedule {
   std::vector<int> upd_off[3];
   std::vector<MatJobH> init, finish, sub_pivot, sub_panel, qm, mv;
   std::vector<TileJob> sub_upd, bp, upd[3];
+  // the chain's two product lists of every outer block (panel product for the next rows, update of the next
+  // diagonal sub-matrix) cut into quarter tiles
+  std::vector<TileJob> chain_q;
+  std::vector<int> cq_bp_off, cq_bp_end, cq_diag_end;   // [outer block]: [off, bp_end) panel product, [bp_end, diag_end) update
   size_t ws_floats = 0;
   kfac_plan_stats stats{};
 };
@@ -777,6 +785,23 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg, bool fuse = 
       S.upd_off[k][b + 1] = int(S.upd[k].size());
       launches += S.upd_off[k][b + 1] > S.upd_off[k][b];
     }
+    // quarter tiles of the chain's products: every 32-column block of a tile that holds wanted columns
+    auto quarters = [&](const TileJob& j, int ncols_total) {
+      for (int q = 0; q < 4; ++q) {
+        if (j.bj * BN + 32 * q >= ncols_total) break;
+        TileJob x = j;
+        x.quarter = q + 1;
+        S.chain_q.push_back(x);
+      }
+    };
+    S.cq_bp_off.push_back(int(S.chain_q.size()));
+    for (int i = S.bp_off[b]; i < S.bp_mid[b]; ++i) quarters(S.bp[i], 1 << 30);   // panel buffers are padded to whole tiles
+    S.cq_bp_end.push_back(int(S.chain_q.size()));
+    for (int i = S.upd_off[UPD_DIAG][b]; i < S.upd_off[UPD_DIAG][b + 1]; ++i) {
+      const TileJob& j = S.upd[UPD_DIAG][i];
+      quarters(j, dims[S.order[j.desc - 2 * S.n_views]]);
+    }
+    S.cq_diag_end.push_back(int(S.chain_q.size()));
   }
   S.stats.n_jobs = int64_t(S.init.size() + S.finish.size() + S.sub_pivot.size() + S.sub_panel.size() + S.sub_upd.size() + S.qm.size() +
                            2 * S.mv.size() + S.bp.size() + S.upd[0].size() + S.upd[1].size() + S.upd[2].size()) + S.n_small;
@@ -914,8 +939,8 @@ size_t kfac_workspace_bytes_precondition(const kfac_ctx*, int n, const int32_t* 
 
 kfac_status kfac_set_option(kfac_ctx* ctx, int option, int value) {
   if (!ctx) return fail(nullptr, KFAC_ERR_INVALID_ARG, "kfac_set_option: ctx is NULL");
-  static const int lo[KFAC_OPT_COUNT] = {1, 1, 1, 0, 0, 0, 0, 0, KC, 0, 0, 0, 0};
-  static const int hi[KFAC_OPT_COUNT] = {MAX_INV_GROUPS, 16, 16, 1, 65536, 1, 1, 1, MAX_JOB_ROWS, 65536, 1, 1, 65536};
+  static const int lo[KFAC_OPT_COUNT] = {1, 1, 1, 0, 0, 0, 0, 0, KC, 0, 0, 0, 0, 0};
+  static const int hi[KFAC_OPT_COUNT] = {MAX_INV_GROUPS, 16, 16, 1, 65536, 1, 1, 1, MAX_JOB_ROWS, 65536, 1, 1, 65536, 1};
   if (option < 0 || option >= KFAC_OPT_COUNT) return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_set_option: unknown option");
   if (value < lo[option] || value > hi[option])
     return fail(ctx, KFAC_ERR_INVALID_ARG, "kfac_set_option: value " + std::to_string(value) + " outside [" +
@@ -1208,6 +1233,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
       Gp.sub_panel_off = S.sub_panel_off; Gp.sub_upd_off = S.sub_upd_off;
       Gp.qm_off = S.qm_off; Gp.mv_off = S.mv_off; Gp.bp_off = S.bp_off; Gp.mv_mid = S.mv_mid; Gp.bp_mid = S.bp_mid;
       for (int k = 0; k < 3; ++k) Gp.upd_off[k] = S.upd_off[k];
+      Gp.cq_bp_off = S.cq_bp_off; Gp.cq_bp_end = S.cq_bp_end; Gp.cq_diag_end = S.cq_diag_end;
       Gp.ws_off = S.ws_off;
       Gp.ev_chain.assign(S.n_ob, nullptr); Gp.ev_col.assign(S.n_ob, nullptr); Gp.ev_rest.assign(S.n_ob, nullptr);
       Gp.ev_gather.assign(S.n_ob, nullptr);
@@ -1230,6 +1256,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
         if ((st = up(&Gp.d_bp, S.bp.data(), S.bp.size() * sizeof(TileJob))) != KFAC_OK) return st;
         for (int k = 0; k < 3; ++k)
           if ((st = up(&Gp.d_upd[k], S.upd[k].data(), S.upd[k].size() * sizeof(TileJob))) != KFAC_OK) return st;
+        if ((st = up(&Gp.d_chain_q, S.chain_q.data(), S.chain_q.size() * sizeof(TileJob))) != KFAC_OK) return st;
       }
     }
     P.valid = true;
@@ -1254,8 +1281,10 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
   const int yield_max = ctx->opt[KFAC_OPT_INV_YIELD];
   int* const yflags = yield_max > 0 ? ctx->cu_flags : nullptr;
   auto crit = [&](int nwg) { return nwg <= yield_max ? yflags : nullptr; };   // few workgroups: latency-critical
-  auto bulk_gemm = [&](const TileDesc* dd, const TileJob* jj, int cnt, int pad, hipStream_t st) {
-    launch_tile_gemm_yield(dd, jj, cnt, pad, yflags, st);
+  // deep: the group's products run one workgroup to a compute unit (latency-bound group) and take the
+  // 32-deep panels; the padding option counts from the 16-deep kernel's footprint
+  auto bulk_gemm = [&](const TileDesc* dd, const TileJob* jj, int cnt, int pad, bool deep, hipStream_t st) {
+    launch_tile_gemm_yield(dd, jj, cnt, deep ? std::max(0, pad - deep_lds_extra()) : pad, yflags, deep, st);
   };
 
   // Group 0 sweeps on the caller's stream; every further group on an internal stream forked from
@@ -1388,7 +1417,7 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
     const int o0 = Gp.upd_off[kind][b], cnt = Gp.upd_off[kind][b + 1] - o0;
     if (cnt <= 0) return;
     ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, st);
-    bulk_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_upd[kind]) + o0, cnt, pad, st);
+    bulk_gemm(d_descs[g], static_cast<const TileJob*>(Gp.d_upd[kind]) + o0, cnt, pad, Gp.latency_bound, st);
   };
   for (int b = 0; b < max_ob; ++b)
     for (int g = 0; g < G; ++g) {
@@ -1425,11 +1454,15 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
                                  d_descs[g], uj, nupd, gs, chain_pad, yflags, npiv_next <= yield_max);
         } else if (nupd > 0) {
           ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, gs);
-          launch_tile_gemm_yield(d_descs[g], uj, nupd, chain_pad, yflags, gs);
+          bulk_gemm(d_descs[g], uj, nupd, chain_pad, Gp.latency_bound, gs);
         }
       }
       const MatJobH* mvj = static_cast<const MatJobH*>(Gp.d_mv);
       const TileJob* bpj = static_cast<const TileJob*>(Gp.d_bp);
+      const TileJob* cqj = static_cast<const TileJob*>(Gp.d_chain_q);
+      // only the group of the longest chains: its few tiles are what the call waits for; the other groups' chain
+      // products are hundreds of tiles, which fill the machine as they are
+      const bool quarter = ctx->opt[KFAC_OPT_INV_QUARTER] != 0 && g == 0 && Gp.latency_bound;
       const int mv0 = Gp.mv_off[b], mv1 = Gp.mv_mid[b], mv2 = Gp.mv_off[b + 1];
       const int bp0 = Gp.bp_off[b], bp1 = Gp.bp_mid[b], bp2 = Gp.bp_off[b + 1];
       const int kch = aw * NB / 32;
@@ -1446,7 +1479,8 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
         HIP_TRY(ctx, hipEventRecord(Gp.ev_gather[b], gs));
         if (bp1 > bp0) {
           ScopedTiming tm(ctx, KFAC_K_INV_PANEL, gs);
-          launch_tile_gemm_yield(d_descs[g], bpj + bp0, bp1 - bp0, chain_pad, yflags, gs);
+          if (quarter) launch_tile_gemm_quarter(d_descs[g], cqj + Gp.cq_bp_off[b], Gp.cq_bp_end[b] - Gp.cq_bp_off[b], Gp.latency_bound ? yflags : nullptr, gs);
+          else bulk_gemm(d_descs[g], bpj + bp0, bp1 - bp0, chain_pad, Gp.latency_bound, gs);
         }
         if (bp1 > bp0) {   // the chain wrote part of the W panel
           HIP_TRY(ctx, ensure_event(Gp.ev_chain[b]));
@@ -1458,13 +1492,18 @@ static kfac_status invert_batch_impl(kfac_ctx* ctx, int n, const int32_t* dims, 
       const bool has_rest = Gp.upd_off[UPD_REST][b + 1] > Gp.upd_off[UPD_REST][b];
       if (has_diag) {
         if (last_rest[g] >= 0) HIP_TRY(ctx, hipStreamWaitEvent(gs, Gp.ev_rest[last_rest[g]], 0));
-        upd_launch(g, UPD_DIAG, b, gs, chain_pad);
+        if (quarter) {
+          ScopedTiming tm(ctx, KFAC_K_INV_UPDATE, gs);
+          launch_tile_gemm_quarter(d_descs[g], cqj + Gp.cq_bp_end[b], Gp.cq_diag_end[b] - Gp.cq_bp_end[b], Gp.latency_bound ? yflags : nullptr, gs);
+        } else {
+          upd_launch(g, UPD_DIAG, b, gs, chain_pad);
+        }
       }
       if (!has_panel) continue;
       HIP_TRY(ctx, hipStreamWaitEvent(side, Gp.ev_gather[b], 0));
       if (bp2 > bp1) {
         ScopedTiming tm(ctx, KFAC_K_INV_PANEL, side);
-        bulk_gemm(d_descs[g], bpj + bp1, bp2 - bp1, side_pad, side);
+        bulk_gemm(d_descs[g], bpj + bp1, bp2 - bp1, side_pad, Gp.latency_bound, side);
         launch_gj_move(d_moves[g] + 1, mvj + mv1, mv2 - mv1, kch, 1, side);
       }
       if (bp1 > bp0) {

@@ -10,7 +10,11 @@ void launch_tile_gemm_pad(const TileDesc* descs, const TileJob* jobs, int njobs,
 // row-major x row-major products only (both operands OP_KMAJOR without ones column): direct-to-LDS loop
 void launch_tile_gemm_dl(const TileDesc* descs, const TileJob* jobs, int njobs, hipStream_t s);
 // row-major x row-major products that give way to latency-critical workgroups on their compute unit (cu_flags may be null)
-void launch_tile_gemm_yield(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, const int* cu_flags, hipStream_t s);
+// deep: 32-deep panels (64 KB of LDS) for launches that run one workgroup to a compute unit, else 16-deep (32 KB)
+int deep_lds_extra();   // bytes of LDS the deep variant uses beyond the other
+void launch_tile_gemm_yield(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, const int* cu_flags, bool deep, hipStream_t s);
+// the same on jobs that each cover one 32-column block of a tile (TileJob::quarter = 1 + block); direct jobs only
+void launch_tile_gemm_quarter(const TileDesc* descs, const TileJob* jobs, int njobs, int* cu_flags, hipStream_t s);
 void launch_tile_reduce(const TileDesc* descs, const ReduceJob* jobs, int njobs, hipStream_t s);
 // pair_jobs: tiles of lag_pair_rows() x lag_pair_cols() channel pairs (bi, bj) that hold a pair c2 <= c, the
 // bias pseudo-channel C included; mirror_jobs: 64 x 64 tiles bi >= bj of the factor

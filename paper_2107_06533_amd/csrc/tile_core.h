@@ -810,16 +810,21 @@ __device__ __forceinline__ void run_tile_dm(const TileDesc& D, const TileJob& J,
 constexpr int DL_KC = 16;                        // panel depth
 constexpr int DL_PANEL = DL_KC * BM;             // floats of one operand panel
 constexpr int DL_LDS_FLOATS = 4 * DL_PANEL;      // two operands x two buffers
+constexpr int DL_KC_DEEP = 32;                   // panel depth of the kernels that run one workgroup to a compute unit
+constexpr int DL_DEEP_LDS_FLOATS = 4 * DL_KC_DEEP * BM;
 
 // RS: row interleave = number of 32-row blocks computed (4: more than 64 valid rows, 2: more than 32, 1).
-template <bool PREFETCH_OLD, bool YIELD, int RS>
+// KCD: panel depth, 16 (32 KB of LDS: several workgroups per compute unit) or 32 (64 KB: half as many
+// barriers and waits per contraction row, which is what counts where the workgroup is alone on its unit).
+template <bool PREFETCH_OLD, bool YIELD, int RS, int KCD>
 __device__ __forceinline__ void run_tile_dl_rs(const TileDesc& D, const TileJob& J, float* smem, const int* cu_flags) {
   const int t = threadIdx.x, lane = t & 63;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i0 = J.bi * BM, j0 = J.bj * BN;
   const bool diag = D.sym && (J.bi == J.bj);
-  float* As = smem;                    // [2][DL_KC][128]
-  float* Bs = smem + 2 * DL_PANEL;
+  constexpr int PANEL_F = KCD * BM;     // floats of one operand panel
+  float* As = smem;                    // [2][KCD][128]
+  float* Bs = smem + 2 * PANEL_F;
   const uint32_t lda4 = (uint32_t)D.a.ld * 4u, ldb4 = (uint32_t)D.b.ld * 4u;
   const uint32_t cut_a = (uint32_t)J.kend * lda4, cut_b = (uint32_t)J.kend * ldb4;
   const rsrc_t ra = make_rsrc(D.a.ptr, cut_a < D.a.bytes ? cut_a : D.a.bytes);
@@ -828,13 +833,13 @@ __device__ __forceinline__ void run_tile_dl_rs(const TileDesc& D, const TileJob&
   const int lca = rs * (lane & 31), lc = 4 * (lane & 31);
   const uint32_t va = (i0 + lca < D.a.M) ? (uint32_t)(lane >> 5) * lda4 + (uint32_t)(i0 + lca) * 4u : OOB_OFFSET;
   const uint32_t vb = (j0 + lc < D.b.M) ? (uint32_t)(lane >> 5) * ldb4 + (uint32_t)(j0 + lc) * 4u : OOB_OFFSET;
-  constexpr int PAIRS = DL_KC / 8;     // row pairs per wave, operand and k step
+  constexpr int PAIRS = KCD / 8;     // row pairs per wave, operand and k step
   auto issue = [&](int k0, int buf) {
 #pragma unroll
     for (int u = 0; u < PAIRS; ++u) {
       const int r = 2 * (4 * u + w);   // first row of the pair inside the panel
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_ptr)(As + buf * DL_PANEL + r * BM), 16, (int)va, (int)((uint32_t)(k0 + r) * lda4), 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_ptr)(Bs + buf * DL_PANEL + r * BN), 16, (int)vb, (int)((uint32_t)(k0 + r) * ldb4), 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_ptr)(As + buf * PANEL_F + r * BM), 16, (int)va, (int)((uint32_t)(k0 + r) * lda4), 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_ptr)(Bs + buf * PANEL_F + r * BN), 16, (int)vb, (int)((uint32_t)(k0 + r) * ldb4), 0, 0);
     }
   };
 
@@ -851,7 +856,7 @@ __device__ __forceinline__ void run_tile_dl_rs(const TileDesc& D, const TileJob&
   const bool direct = J.part < 0;
   const bool wave_used = j0 + 32 * w < D.N;    // a wave whose columns all lie outside the matrix only helps loading
 
-  const int nkt = (J.kend - J.kbeg + DL_KC - 1) / DL_KC;
+  const int nkt = (J.kend - J.kbeg + KCD - 1) / KCD;
 #ifdef KFAC_TRACE
   const long long tr0 = wall_clock64();
 #endif
@@ -877,12 +882,12 @@ __device__ __forceinline__ void run_tile_dl_rs(const TileDesc& D, const TileJob&
     if (yw && (kt & 1)) busy = __hip_atomic_load(yw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of panel kt has landed
     __syncthreads();                                    // ... and everybody's; all reads of the other buffer are done
-    if (kt + 1 < nkt) issue(J.kbeg + (kt + 1) * DL_KC, (kt + 1) & 1);
+    if (kt + 1 < nkt) issue(J.kbeg + (kt + 1) * KCD, (kt + 1) & 1);
     if (wave_used) {
-      const float* ap = As + (kt & 1) * DL_PANEL + lh * BM + 4 * li;
-      const float* bp = Bs + (kt & 1) * DL_PANEL + lh * BN + 32 * w + li;
+      const float* ap = As + (kt & 1) * PANEL_F + lh * BM + 4 * li;
+      const float* bp = Bs + (kt & 1) * PANEL_F + lh * BN + 32 * w + li;
 #pragma unroll
-      for (int q = 0; q < DL_KC / 2; ++q) {
+      for (int q = 0; q < KCD / 2; ++q) {
         const float b = bp[2 * q * BN];
         if constexpr (RS == 4) {
           const f32x4 a = *reinterpret_cast<const f32x4*>(ap + 2 * q * BM);
@@ -944,12 +949,95 @@ __device__ __forceinline__ void run_tile_dl_rs(const TileDesc& D, const TileJob&
 #endif
 }
 
-template <bool PREFETCH_OLD = false, bool YIELD = false>
+template <bool PREFETCH_OLD = false, bool YIELD = false, int KCD = DL_KC>
 __device__ __forceinline__ void run_tile_dl(const TileDesc& D, const TileJob& J, float* smem, const int* cu_flags = nullptr) {
   const int rows_valid = D.M - J.bi * BM;
-  if (rows_valid > 64) run_tile_dl_rs<PREFETCH_OLD, YIELD, 4>(D, J, smem, cu_flags);
-  else if (rows_valid > 32) run_tile_dl_rs<PREFETCH_OLD, YIELD, 2>(D, J, smem, cu_flags);
-  else run_tile_dl_rs<PREFETCH_OLD, YIELD, 1>(D, J, smem, cu_flags);
+  if (rows_valid > 64) run_tile_dl_rs<PREFETCH_OLD, YIELD, 4, KCD>(D, J, smem, cu_flags);
+  else if (rows_valid > 32) run_tile_dl_rs<PREFETCH_OLD, YIELD, 2, KCD>(D, J, smem, cu_flags);
+  else run_tile_dl_rs<PREFETCH_OLD, YIELD, 1, KCD>(D, J, smem, cu_flags);
+}
+
+// One 32 x 32 block of a tile per WAVE, operands straight from memory into registers in the MFMA's own
+// layout (lane (i, h) of k pair q holds element (2q + h, i) of each operand: 32 consecutive floats of
+// two rows per load), no LDS and no barriers: for the products that nothing else can overlap with
+// (the products on the sweep chain of the inverse), where a tile's sixteen blocks should run on
+// sixteen SIMDs at once and a block's time is the latency of its loads.  Loads run two chunks of
+// 16 k pairs ahead of the MFMAs.  Job (bi, bj, quarter): wave w takes row block w of column block
+// quarter - 1.  Old values fetched first; direct jobs only.
+constexpr int QB_CH = 16;   // k pairs per chunk
+struct QuarterOperands {
+  rsrc_t ra, rb;
+  uint32_t va, vb, lda4, ldb4;
+  int kbeg;
+  __device__ __forceinline__ void load(int c, float (&a)[QB_CH], float (&b)[QB_CH]) const {
+#pragma unroll
+    for (int q = 0; q < QB_CH; ++q) {
+      const uint32_t k = (uint32_t)(kbeg + 2 * (c * QB_CH + q));   // rows at or past the job's last row lie beyond the resource
+      a[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ra, (int)va, (int)(k * lda4), 0));
+      b[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)vb, (int)(k * ldb4), 0));
+    }
+  }
+};
+__device__ __forceinline__ void quarter_mma(const float (&a)[QB_CH], const float (&b)[QB_CH], f32x16& acc) {
+#pragma unroll
+  for (int q = 0; q < QB_CH; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q], b[q], acc, 0, 0, 0);
+}
+__device__ __forceinline__ void run_tile_quarter(const TileDesc& D, const TileJob& J) {
+  const int t = threadIdx.x, lane = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int li = lane & 31, lh = lane >> 5;
+  const int i0 = J.bi * BM + 32 * w, j0 = J.bj * BN + 32 * (J.quarter - 1);
+  if (i0 >= D.M || j0 >= D.N) return;          // wave-uniform; nothing below synchronises waves
+  if (D.sym && j0 > i0 + 31) return;           // block above the diagonal
+  const bool diag = D.sym && (J.bi == J.bj);
+  QuarterOperands op;
+  op.lda4 = (uint32_t)D.a.ld * 4u; op.ldb4 = (uint32_t)D.b.ld * 4u;
+  const uint32_t cut_a = (uint32_t)J.kend * op.lda4, cut_b = (uint32_t)J.kend * op.ldb4;
+  op.ra = make_rsrc(D.a.ptr, cut_a < D.a.bytes ? cut_a : D.a.bytes);
+  op.rb = make_rsrc(D.b.ptr, cut_b < D.b.bytes ? cut_b : D.b.bytes);
+  op.va = (i0 + li < D.a.M) ? (uint32_t)lh * op.lda4 + (uint32_t)(i0 + li) * 4u : OOB_OFFSET;
+  op.vb = (j0 + li < D.b.M) ? (uint32_t)lh * op.ldb4 + (uint32_t)(j0 + li) * 4u : OOB_OFFSET;
+  op.kbeg = J.kbeg;
+  const uint32_t ldo4 = (uint32_t)D.ldo * 4u;
+  const int gj = j0 + mfma_col(lane);
+  auto out_offset = [&](int v) -> uint32_t {
+    const int gi = i0 + mfma_row(v, lane);
+    const bool ok = gi < D.M && gj < D.N && (!D.sym || gi >= gj);
+    return ok ? (uint32_t)gi * ldo4 + (uint32_t)gj * 4u : OOB_OFFSET;
+  };
+  const rsrc_t ro = make_rsrc(D.out, (uint32_t)D.M * ldo4);
+  const float alpha = D.alpha, beta = D.beta;
+  const int nch = (J.kend - J.kbeg + 2 * QB_CH - 1) / (2 * QB_CH);
+  f32x16 old, acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    old[v] = beta != 0.f ? buf_load(ro, out_offset(v)) : 0.f;
+    acc[v] = 0.f;
+  }
+  float a0[QB_CH], b0[QB_CH], a1[QB_CH], b1[QB_CH], a2[QB_CH], b2[QB_CH];
+  if (nch > 0) op.load(0, a0, b0);
+  if (nch > 1) op.load(1, a1, b1);
+  for (int c = 0; c < nch; c += 3) {
+    if (c + 2 < nch) op.load(c + 2, a2, b2);
+    quarter_mma(a0, b0, acc);
+    if (c + 1 >= nch) break;
+    if (c + 3 < nch) op.load(c + 3, a0, b0);
+    quarter_mma(a1, b1, acc);
+    if (c + 2 >= nch) break;
+    if (c + 4 < nch) op.load(c + 4, a1, b1);
+    quarter_mma(a2, b2, acc);
+  }
+  const bool mirror = D.mirror == MIRROR_ALL || (D.mirror == MIRROR_DIAG_TILE && diag);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const float val = alpha * acc[v] + beta * old[v];
+    const uint32_t off = out_offset(v);
+    buf_store(ro, off, val);
+    if (mirror) {
+      const int gi = i0 + mfma_row(v, lane);
+      buf_store(ro, (off != OOB_OFFSET && gi != gj) ? (uint32_t)gj * ldo4 + (uint32_t)gi * 4u : OOB_OFFSET, val);
+    }
+  }
 }
 
 // Dispatch on the operand type of a symmetric product a^T a (wave-uniform).

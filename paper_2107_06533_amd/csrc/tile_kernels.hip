@@ -97,13 +97,27 @@ __global__ __launch_bounds__(NT, 4) void tile_gemm_dl_kernel(const TileDesc* __r
 // sweep chain that share their compute unit (see cu_enter in tile_core.h).  The off-chain launches add
 // unused LDS so that one such workgroup fills a compute unit but for the room a chain kernel needs;
 // nothing then hides the epilogue, so the old output values are fetched before the k loop.
+template <int KCD>
 __global__ __launch_bounds__(NT, 2) void tile_gemm_yield_kernel(const TileDesc* __restrict__ descs, const TileJob* __restrict__ jobs,
                                                                 int njobs, const int* __restrict__ cu_flags) {
-  __shared__ __attribute__((aligned(16))) float smem[DL_LDS_FLOATS];
+  __shared__ __attribute__((aligned(16))) float smem[4 * KCD * BM];
   const int g = blockIdx.x;
   if (g >= njobs) return;
   const TileJob J = jobs[g];
-  run_tile_dl<true, true>(descs[J.desc], J, smem, cu_flags);
+  run_tile_dl<true, true, KCD>(descs[J.desc], J, smem, cu_flags);
+}
+
+// The same products cut into 32 x 32 blocks, one a wave, fed from memory without LDS (TileJob::quarter), for
+// the launches on the sweep chain of the inverse: see run_tile_quarter.
+__global__ __launch_bounds__(NT, 2) void tile_gemm_quarter_kernel(const TileDesc* __restrict__ descs, const TileJob* __restrict__ jobs,
+                                                                   int njobs, int* cu_flags) {
+  const int g = blockIdx.x;
+  if (g >= njobs) return;
+  const TileJob J = jobs[g];
+  cu_enter(cu_flags);   // the products that share its compute unit give way (cu_flags may be null)
+  run_tile_quarter(descs[J.desc], J);
+  __syncthreads();      // every wave is done before the workgroup counts itself out
+  cu_leave(cu_flags);
 }
 
 // out = beta*out + alpha * (partial[part0] + partial[part0+1] + ...) in slot order (deterministic).
@@ -328,9 +342,16 @@ void launch_tile_gemm_dl(const TileDesc* descs, const TileJob* jobs, int njobs, 
   hipLaunchKernelGGL(tile_gemm_dl_kernel, dim3(njobs), dim3(NT), 0, s, descs, jobs, njobs);
 }
 
-void launch_tile_gemm_yield(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, const int* cu_flags, hipStream_t s) {
+int deep_lds_extra() { return 4 * (DL_DEEP_LDS_FLOATS - DL_LDS_FLOATS); }
+void launch_tile_gemm_yield(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, const int* cu_flags, bool deep, hipStream_t s) {
   if (njobs <= 0) return;
-  hipLaunchKernelGGL(tile_gemm_yield_kernel, dim3(njobs), dim3(NT), pad_bytes, s, descs, jobs, njobs, cu_flags);
+  if (deep) hipLaunchKernelGGL(tile_gemm_yield_kernel<DL_KC_DEEP>, dim3(njobs), dim3(NT), pad_bytes, s, descs, jobs, njobs, cu_flags);
+  else hipLaunchKernelGGL(tile_gemm_yield_kernel<DL_KC>, dim3(njobs), dim3(NT), pad_bytes, s, descs, jobs, njobs, cu_flags);
+}
+
+void launch_tile_gemm_quarter(const TileDesc* descs, const TileJob* jobs, int njobs, int* cu_flags, hipStream_t s) {
+  if (njobs <= 0) return;
+  hipLaunchKernelGGL(tile_gemm_quarter_kernel, dim3(njobs), dim3(NT), 0, s, descs, jobs, njobs, cu_flags);
 }
 
 void launch_tile_gemm_pad(const TileDesc* descs, const TileJob* jobs, int njobs, int pad_bytes, hipStream_t s) {

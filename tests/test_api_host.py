@@ -174,7 +174,7 @@ def test_options(hctx):
     c = pk.Context(-1)
     try:
         defaults = {"inv_groups": 2, "inv_agg": 4, "inv_agg_chain": 6, "inv_fuse": 1, "inv_side_pad": 56000,
-                    "factor_lag": 1, "factor_vec11": 1, "factor_xcd": 0, "factor_kjob": 8192, "inv_chain_pad": 0, "inv_side": 1, "inv_split_long": 1, "inv_yield": 64}
+                    "factor_lag": 1, "factor_vec11": 1, "factor_xcd": 0, "factor_kjob": 8192, "inv_chain_pad": 0, "inv_side": 1, "inv_split_long": 1, "inv_yield": 64, "inv_quarter": 1}
         assert set(defaults) == set(pk.OPTIONS)
         for k, v in defaults.items():
             assert c.get_option(k) == v, k
