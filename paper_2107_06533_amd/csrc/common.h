@@ -133,6 +133,7 @@ struct LagJob {
 
 // ---- batched inversion ---------------------------------------------------------------------
 constexpr int NB = 128;   // pivot block order of the blocked symmetric sweep
+constexpr int FINISH_TILE = 64;   // tile of the final negate-and-mirror pass
 
 struct InvMat {
   const float* F;   // input [d, d] (whole matrices only)

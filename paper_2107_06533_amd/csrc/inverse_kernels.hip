@@ -546,33 +546,37 @@ __global__ __launch_bounds__(NT) void gj_panel_kernel(const InvMat* __restrict__
 // ---- finish: X = -(swept lower triangle), mirrored to a full symmetric matrix -------------------
 __global__ __launch_bounds__(NT) void gj_finish_kernel(const InvMat* __restrict__ mats,
                                                        const MatJob* __restrict__ jobs, int njobs) {
-  __shared__ float tile[32][33];
+  constexpr int FT = FINISH_TILE, PER = FT * FT / NT;
+  __shared__ float tile[FT][FT + 1];
   const int g = blockIdx.x;
   if (g >= njobs) return;
   const MatJob J = jobs[g];
   const InvMat Mx = mats[J.mat];
   const int d = Mx.d;
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
-  const int i0 = J.bi * 32, j0 = J.bj * 32;
+  const int tx = threadIdx.x & (FT - 1), ty = threadIdx.x >> 6;   // 64 x 4: a wave moves 256 bytes of a row
+  const int i0 = J.bi * FT, j0 = J.bj * FT;
+  gf_ptr X = as_global(Mx.X);
+  float v[PER];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int li = ty + 8 * r;
-    const int i = i0 + li, j = j0 + tx;
-    float v = 0.f;
-    if (i < d && j < d && i >= j) {
-      v = -Mx.X[(size_t)i * d + j];
-      Mx.X[(size_t)i * d + j] = v;
-    }
-    tile[li][tx] = v;
+  for (int r = 0; r < PER; ++r) {
+    const int i = i0 + ty + 4 * r, j = j0 + tx;
+    v[r] = (i < d && j < d && i >= j) ? X[(size_t)i * d + j] : 0.f;
+  }
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const int li = ty + 4 * r, i = i0 + li, j = j0 + tx;
+    const float x = -v[r];
+    if (i < d && j < d && i >= j) X[(size_t)i * d + j] = x;
+    tile[li][tx] = x;
   }
   __syncthreads();
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int lj = ty + 8 * r;             // row of the mirrored tile = column index of the source
+  for (int r = 0; r < PER; ++r) {
+    const int lj = ty + 4 * r;             // row of the mirrored tile = column index of the source
     const int j = j0 + lj, i = i0 + tx;    // writes X[j][i] = X[i][j], i > j
-    if (i < d && j < d && i > j) Mx.X[(size_t)j * d + i] = tile[tx][lj];
+    if (i < d && j < d && i > j) X[(size_t)j * d + i] = tile[tx][lj];
     // packed upper triangle, row j: element (j, i), i >= j, at j*d - j(j-1)/2 + (i - j)
-    if (Mx.P && i < d && j < d && i >= j) Mx.P[(size_t)j * d - (size_t)j * (j - 1) / 2 + (i - j)] = tile[tx][lj];
+    if (Mx.P && i < d && j < d && i >= j) as_global(Mx.P)[(size_t)j * d - (size_t)j * (j - 1) / 2 + (i - j)] = tile[tx][lj];
   }
 }
 

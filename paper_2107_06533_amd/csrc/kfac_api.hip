@@ -670,8 +670,8 @@ InvertSchedule schedule_invert(int n, const int32_t* dims, int agg, bool fuse = 
     S.ws_off[m] = S.ws_floats;
     S.ws_floats += inv_ws_layout(S.ldp[m], agg).total;
     S.n_ob = std::max(S.n_ob, S.nob[m]);
-    const int t32 = ceil_div(d, 32);
-    for (int bi = 0; bi < t32; ++bi)
+    const int tf = ceil_div(d, FINISH_TILE);
+    for (int bi = 0; bi < tf; ++bi)
       for (int bj = 0; bj <= bi; ++bj) S.finish.push_back({m, bi, bj, 0});
   }
   // init jobs: the tiles of the first outer block's diagonal sub-matrix first (the sweep starts on
