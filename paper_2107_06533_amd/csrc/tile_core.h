@@ -1,8 +1,9 @@
 // 128x128 output-tile engine for gfx950: operand loaders (plain row-major and fused
 // patch-expansion of NCHW tensors), LDS staging, fp32 MFMA contraction, epilogues.
 //
-// One workgroup of 256 threads (4 wavefronts as 2x2, 64x64 outputs each, built from
-// v_mfma_f32_32x32x2_f32 blocks) computes  acc[i][j] = sum_k a(k, i0+i) * b(k, j0+j)
+// One workgroup of 256 threads (4 wavefronts, each a 2x2 group of v_mfma_f32_32x32x2_f32 blocks:
+// the quadrants of a full tile, dealt out differently over tiles that want fewer blocks, see
+// wave_place) computes  acc[i][j] = sum_k a(k, i0+i) * b(k, j0+j)
 // over a k-range.  Operands are staged in LDS as [m][k] panels (double-buffered, one barrier
 // per 32-deep k step) with k permuted inside groups of 8 so that the four values a lane feeds to
 // four consecutive MFMAs are one 16-byte LDS read; the next panel's global loads are in flight
@@ -12,6 +13,9 @@
 // its fp32 MFMA accumulator; longer reductions (ReLU activations over 10^5 rows are sums of
 // non-negative products, whose rounding error grows with the run length) are split into
 // several jobs whose partial tiles are added in a fixed order by the reduce kernel.
+// Further down: panels loaded straight into LDS for 1x1 whole-image views (run_tile_dm) and for
+// plain products of row-major operands (run_tile_dl), and products cut into one block a wave that
+// use no LDS at all (run_tile_quarter).
 #pragma once
 #include <type_traits>
 
@@ -1044,11 +1048,7 @@ __device__ __forceinline__ void run_tile_quarter(const TileDesc& D, const TileJo
 __device__ __forceinline__ void run_tile_sym(const TileDesc& D, const TileJob& J, float* smem) {
   const int ta = D.a.type;
   if (ta == OP_KMAJOR) run_tile<KMajorLoader, KMajorLoader, false, true>(D, J, smem);
-#ifdef KFAC_NO_DM
-  else if (ta == OP_CONV11V) run_tile<Conv11VecLoader, Conv11VecLoader, false, true>(D, J, smem);
-#else
   else if (ta == OP_CONV11V) run_tile_dm(D, J, smem);
-#endif
   else if (ta == OP_CONV11) run_tile<ConvLoader<1, 1>, ConvLoader<1, 1>, false, true>(D, J, smem);
   else if (ta == OP_CONV33) run_tile<ConvLoader<3, 3>, ConvLoader<3, 3>, false, true>(D, J, smem);
   else if (ta == OP_CONV77) run_tile<ConvLoader<7, 7>, ConvLoader<7, 7>, false, true>(D, J, smem);
