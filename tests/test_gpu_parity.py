@@ -498,3 +498,27 @@ def test_update_factors_packed_output(ctx):
         wantG = oracle.update_factor_G(l, gouts[i], G0[i].astype(np.float64), xi)
         assert rel_fro(G32.astype(np.float64), wantG) <= TOL_FACTOR, l.name
     assert ctx.kfac_update_factors_packed(layers, a_d, g_d, A_d, G_d, xi, None, check=False) == 1   # packed is required
+
+
+def test_chain_products_as_blocks_match_tile_jobs(kfac_lib):
+    """Option inv_quarter: the two products on the sweep chain of the long-chain group run as 32 x 32
+    blocks per wave fed from memory instead of 128 x 128 tile jobs.  Same contraction order, so the
+    inverses must agree bit for bit, ragged sizes and one-row tails included."""
+    import torch
+    dims = [1300, 1153, 1025, 641, 513, 257, 129, 64]     # the first three form the long-chain group
+    gamma = 0.03
+    Fs = [spd(d, 7 * d + 1, 5.0) + 0.5 * np.eye(d) for d in dims]
+    results = []
+    for quarter in (1, 0):
+        c = kfac_lib.Context(0)
+        try:
+            c.set_option("inv_quarter", quarter)
+            c.set_option("inv_agg_chain", 3)               # several outer blocks at these sizes
+            F_d, X_d, info = run_invert(c, Fs, gamma)
+            assert np.all(info == 0)
+            results.append(X_d)
+        finally:
+            c.close()
+    for d, a, b in zip(dims, *results):
+        assert torch.equal(a, b), f"d={d}: block products and tile jobs disagree"
+        assert inv_residual(host64(dev(Fs[dims.index(d)].astype(np.float32))), gamma, host64(a)) <= 1e-4
